@@ -1,0 +1,368 @@
+// CPU ORACLE for graph-based approximate nearest-neighbour search with
+// scalar-quantized traversal distances and full-precision reranking.
+//
+// THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow,
+// single-threaded restatement of what the paper's search computes, meant to
+// be checked against the paper by eye and used only by tests, the smoke check
+// and the CPU-baseline leg of the benchmark.  It shares no code, headers,
+// tables or helpers with the GPU library.
+//
+// What follows the paper:
+//   * search loop, pool and visited-set semantics: Algorithm 1 ("Deterministic
+//     Access Greedy Search") and its walk-through in Appendix A;
+//   * scalar quantization SQ-b: Appendix G ("Improving Quantization
+//     Precision"), uniform levels over [min, max];
+//   * Euclidean distance split into a stored norm plus an inner product:
+//     Section 5.2, "Distance Decomposition";
+//   * recall: Section 6.1 (|ANN_k ∩ NN_k| / k).
+// Where the paper is silent the readings are (each listed in the design notes):
+//   per-dimension ranges; 2^b - 1 steps so min -> 0 and max -> 2^b - 1; round
+//   half up; SQ4 packs dimension 2i in the low nibble; the query is folded
+//   with the step sizes and rounded to int8 so the traversal distance is an
+//   int32 dot product followed by one fused multiply-add; ties are broken by
+//   (key, id); entries are marked visited at initialisation; the selective
+//   rerank of the paper (described only in a cited work) is replaced by an
+//   exact rerank of a fixed-length pool prefix; inner-product "distance" is
+//   the negated inner product.
+//
+// Build: g++ -O2 -ffp-contract=off -std=c++17 -shared -fPIC
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+constexpr uint32_t kPad = 0xFFFFFFFFu;
+
+inline int row_bytes(int d, int bits) { return bits == 8 ? d : (d + 1) / 2; }
+
+inline int code_at(const uint8_t *row, int j, int bits) {
+  if (bits == 8) return row[j];
+  uint8_t byte = row[j >> 1];
+  return (j & 1) ? (byte >> 4) : (byte & 0x0F);
+}
+
+// Traversal key from the integer dot product (Section 5.2 decomposition with
+// the per-query constant ||q||^2 dropped; b.q = qlo + s * IDOT under SQ decode).
+inline float key_from_idot(int metric, float s, float qlo, int32_t idot, float norm_term) {
+  float key;
+  if (metric == 0) {
+    float h = norm_term - 2.0f * qlo;
+    key = std::fmaf(-2.0f * s, (float)idot, h);
+  } else {
+    key = -std::fmaf(s, (float)idot, qlo);
+  }
+  if (key == 0.0f) key = 0.0f;  // -0 -> +0
+  return key;
+}
+
+struct Entry {
+  float key;
+  uint32_t id;
+  int32_t idot;
+  bool expanded;
+};
+inline bool entry_less(const Entry &a, const Entry &b) {
+  return a.key < b.key || (a.key == b.key && a.id < b.id);
+}
+
+}  // namespace
+
+extern "C" {
+
+// ---------------------------------------------------------------- SQ (App. G)
+// Per-dimension range and step: lo_j = min_i X_ij, delta_j = (max - min) /
+// (2^b - 1) in fp32; an empty range gets delta = 1.
+void orc_sq_train(const float *X, int64_t n, int32_t d, int32_t bits, float *lo, float *delta) {
+  const float levels = (float)((1 << bits) - 1);
+  for (int j = 0; j < d; ++j) {
+    float mn = X[j], mx = X[j];
+    for (int64_t i = 1; i < n; ++i) {
+      float v = X[i * (int64_t)d + j];
+      if (v < mn) mn = v;
+      if (v > mx) mx = v;
+    }
+    lo[j] = mn;
+    delta[j] = (mx > mn) ? (mx - mn) / levels : 1.0f;
+  }
+}
+
+// c_ij = clamp(floor((x - lo_j) / delta_j + 0.5), 0, 2^b - 1).  Also emits the
+// norm term B_i = sum_j decode(c_ij)^2 (fp64 accumulation in index order,
+// rounded once), the "one additional FLOAT32 per database vector" of Sec. 5.2.
+void orc_sq_encode(const float *X, int64_t n, int32_t d, int32_t bits, const float *lo, const float *delta,
+                   uint8_t *codes, float *norm_term) {
+  const int rb = row_bytes(d, bits);
+  const int maxc = (1 << bits) - 1;
+  for (int64_t i = 0; i < n; ++i) {
+    uint8_t *row = codes + i * (int64_t)rb;
+    std::memset(row, 0, rb);
+    double nn = 0.0;
+    for (int j = 0; j < d; ++j) {
+      float u = (X[i * (int64_t)d + j] - lo[j]) / delta[j] + 0.5f;
+      int c;
+      if (!(u > 0.0f))
+        c = 0;
+      else if (u >= (float)(maxc + 1))
+        c = maxc;
+      else
+        c = (int)std::floor(u);
+      if (bits == 8)
+        row[j] = (uint8_t)c;
+      else
+        row[j >> 1] |= (uint8_t)((j & 1) ? (c << 4) : c);
+      float xhat = lo[j] + delta[j] * (float)c;
+      nn += (double)xhat * (double)xhat;
+    }
+    if (norm_term) norm_term[i] = (float)nn;
+  }
+}
+
+void orc_sq_decode(const uint8_t *codes, int64_t n, int32_t d, int32_t bits, const float *lo, const float *delta,
+                   float *out) {
+  const int rb = row_bytes(d, bits);
+  for (int64_t i = 0; i < n; ++i)
+    for (int j = 0; j < d; ++j)
+      out[i * (int64_t)d + j] = lo[j] + delta[j] * (float)code_at(codes + i * (int64_t)rb, j, bits);
+}
+
+// ---------------------------------------------------------------- query side
+// a_j = delta_j * q_j; s = max|a| / 127; t_j = round-half-even(a_j * (127 /
+// max|a|)) clamped to [-127, 127]; qlo = sum_j q_j * lo_j (fp64, index order,
+// rounded once).  Then q . decode(c) = qlo + sum_j a_j c_j ~ qlo + s * IDOT.
+void orc_query_prep(const float *q, int32_t d, const float *lo, const float *delta, int8_t *t, float *s_out,
+                    float *qlo_out) {
+  std::vector<float> a(d);
+  float amax = 0.0f;
+  for (int j = 0; j < d; ++j) {
+    a[j] = delta[j] * q[j];
+    float m = std::fabs(a[j]);
+    if (m > amax) amax = m;
+  }
+  float s = 1.0f, r = 0.0f;
+  if (amax > 0.0f) {
+    s = amax / 127.0f;
+    r = 127.0f / amax;
+  }
+  double acc = 0.0;
+  for (int j = 0; j < d; ++j) {
+    float v = std::nearbyintf(a[j] * r);  // default rounding mode: half to even
+    int ti = (int)v;
+    if (ti > 127) ti = 127;
+    if (ti < -127) ti = -127;
+    t[j] = (int8_t)ti;
+    acc += (double)q[j] * (double)lo[j];
+  }
+  *s_out = s;
+  *qlo_out = (float)acc;
+}
+
+int32_t orc_idot(const int8_t *t, const uint8_t *code_row, int32_t d, int32_t bits) {
+  int32_t acc = 0;
+  for (int j = 0; j < d; ++j) acc += (int32_t)t[j] * (int32_t)code_at(code_row, j, bits);
+  return acc;
+}
+
+float orc_key(int32_t metric, float s, float qlo, int32_t idot, float norm_term) {
+  return key_from_idot(metric, s, qlo, idot, norm_term);
+}
+
+// ---------------------------------------------------------------- search
+// Algorithm 1 for a batch of queries, one after the other.  The prefetch
+// parameters of the algorithm do not affect results and are absent.
+//   labels: NULL -> every edge passes; otherwise [n][degree] edge labels, an
+//            edge is usable when label <= alpha_s (Section 4.3).
+//   m_s:    at most m_s neighbours are taken per expansion (<= 0: no cap).
+//   entries: NULL -> every query starts from `entry_point`; otherwise
+//            [nq][n_entry] per-query initial nodes I (duplicates skipped).
+//   out_ids/out_keys/out_idot: [nq][ef], final pool in (key, id) order, padded
+//            with id 0xFFFFFFFF, key +inf, idot 0.
+//   out_counts: [nq][4] = expansions, distance evaluations (= |V|), pool size, 0.
+void orc_search_batch(int64_t n, int32_t d, int32_t degree, int32_t metric, int32_t bits, const uint8_t *codes,
+                      const float *lo, const float *delta, const float *norm_term, const uint32_t *adjacency,
+                      uint32_t entry_point, const float *Q, int32_t nq, const uint32_t *entries, int32_t n_entry,
+                      int32_t ef, const float *labels, float alpha_s, int32_t m_s, uint32_t *out_ids,
+                      float *out_keys, int32_t *out_idot, uint32_t *out_counts) {
+  const int rb = row_bytes(d, bits);
+  if (m_s <= 0) m_s = degree;
+  std::vector<uint8_t> visited(n);
+  std::vector<int8_t> t(d);
+  std::vector<Entry> pool;
+  for (int32_t qi = 0; qi < nq; ++qi) {
+    const float *q = Q + (int64_t)qi * d;
+    float s, qlo;
+    orc_query_prep(q, d, lo, delta, t.data(), &s, &qlo);
+    std::fill(visited.begin(), visited.end(), 0);
+    pool.clear();
+    uint32_t n_exp = 0, n_dist = 0;
+
+    auto evaluate_and_insert = [&](uint32_t v) {
+      int32_t idot = orc_idot(t.data(), codes + (int64_t)v * rb, d, bits);
+      float key = key_from_idot(metric, s, qlo, idot, norm_term ? norm_term[v] : 0.0f);
+      ++n_dist;
+      Entry e{key, v, idot, false};
+      if ((int)pool.size() >= ef && !entry_less(e, pool.back())) return;
+      auto pos = std::upper_bound(pool.begin(), pool.end(), e, entry_less);
+      pool.insert(pos, e);
+      if ((int)pool.size() > ef) pool.pop_back();  // drop the farthest
+    };
+
+    // initial nodes I go into the pool and into V
+    const uint32_t *I = entries ? entries + (int64_t)qi * n_entry : &entry_point;
+    const int nI = entries ? n_entry : 1;
+    for (int e = 0; e < nI; ++e) {
+      uint32_t v = I[e];
+      if (v == kPad || visited[v]) continue;
+      visited[v] = 1;
+      evaluate_and_insert(v);
+    }
+
+    for (;;) {
+      // closest un-expanded pool entry
+      int u = -1;
+      for (size_t p = 0; p < pool.size(); ++p)
+        if (!pool[p].expanded) {
+          u = (int)p;
+          break;
+        }
+      if (u < 0) break;
+      pool[u].expanded = true;
+      ++n_exp;
+      const uint32_t uid = pool[u].id;
+      // first pass over ids only: collect the unvisited neighbours N and mark them
+      std::vector<uint32_t> N;
+      for (int slot = 0; slot < degree; ++slot) {
+        uint32_t v = adjacency[(int64_t)uid * degree + slot];
+        if (v == kPad || visited[v]) continue;
+        if (labels && !(labels[(int64_t)uid * degree + slot] <= alpha_s)) continue;
+        if (!((int)N.size() < m_s)) continue;
+        visited[v] = 1;
+        N.push_back(v);
+      }
+      // second pass: touch the vectors of N only
+      for (uint32_t v : N) evaluate_and_insert(v);
+    }
+
+    for (int p = 0; p < ef; ++p) {
+      bool have = p < (int)pool.size();
+      out_ids[(int64_t)qi * ef + p] = have ? pool[p].id : kPad;
+      out_keys[(int64_t)qi * ef + p] = have ? pool[p].key : INFINITY;
+      if (out_idot) out_idot[(int64_t)qi * ef + p] = have ? pool[p].idot : 0;
+    }
+    if (out_counts) {
+      out_counts[(int64_t)qi * 4 + 0] = n_exp;
+      out_counts[(int64_t)qi * 4 + 1] = n_dist;
+      out_counts[(int64_t)qi * 4 + 2] = (uint32_t)pool.size();
+      out_counts[(int64_t)qi * 4 + 3] = 0;
+    }
+  }
+}
+
+// Re-evaluate pool entries with another (finer) code level and re-sort: the
+// middle stage of a low -> higher -> full precision cascade.
+//   ids: [nq][n_cand] (padding allowed); outputs same shape, (key, id) order.
+void orc_rescore_batch(int32_t d, int32_t metric, int32_t bits, const uint8_t *codes, const float *lo,
+                       const float *delta, const float *norm_term, const float *Q, int32_t nq, const uint32_t *ids,
+                       int32_t n_cand, uint32_t *out_ids, float *out_keys, int32_t *out_idot) {
+  const int rb = row_bytes(d, bits);
+  std::vector<int8_t> t(d);
+  std::vector<Entry> lst;
+  for (int32_t qi = 0; qi < nq; ++qi) {
+    float s, qlo;
+    orc_query_prep(Q + (int64_t)qi * d, d, lo, delta, t.data(), &s, &qlo);
+    lst.clear();
+    for (int c = 0; c < n_cand; ++c) {
+      uint32_t v = ids[(int64_t)qi * n_cand + c];
+      if (v == kPad) continue;
+      int32_t idot = orc_idot(t.data(), codes + (int64_t)v * rb, d, bits);
+      lst.push_back({key_from_idot(metric, s, qlo, idot, norm_term ? norm_term[v] : 0.0f), v, idot, false});
+    }
+    std::sort(lst.begin(), lst.end(), entry_less);
+    for (int c = 0; c < n_cand; ++c) {
+      bool have = c < (int)lst.size();
+      out_ids[(int64_t)qi * n_cand + c] = have ? lst[c].id : kPad;
+      out_keys[(int64_t)qi * n_cand + c] = have ? lst[c].key : INFINITY;
+      if (out_idot) out_idot[(int64_t)qi * n_cand + c] = have ? lst[c].idot : 0;
+    }
+  }
+}
+
+// ---------------------------------------------------------------- rerank
+// High-precision distance tau_h on the original vectors (fp64 accumulation,
+// rounded once to fp32) for the given candidates; sort by (distance, id);
+// return the best k.  L2: sum (q - x)^2.  IP: -(q . x).
+void orc_rerank_batch(const float *X, int32_t d, int32_t metric, const float *Q, int32_t nq, const uint32_t *cand,
+                      int32_t n_cand, int32_t k, uint32_t *out_ids, float *out_dist) {
+  struct Hit {
+    float dist;
+    uint32_t id;
+  };
+  std::vector<Hit> hits;
+  for (int32_t qi = 0; qi < nq; ++qi) {
+    const float *q = Q + (int64_t)qi * d;
+    hits.clear();
+    for (int c = 0; c < n_cand; ++c) {
+      uint32_t v = cand[(int64_t)qi * n_cand + c];
+      if (v == kPad) continue;
+      const float *x = X + (int64_t)v * d;
+      double acc = 0.0;
+      for (int j = 0; j < d; ++j) {
+        if (metric == 0) {
+          double t = (double)q[j] - (double)x[j];
+          acc += t * t;
+        } else {
+          acc += (double)q[j] * (double)x[j];
+        }
+      }
+      hits.push_back({(float)(metric == 0 ? acc : -acc), v});
+    }
+    std::sort(hits.begin(), hits.end(),
+              [](const Hit &a, const Hit &b) { return a.dist < b.dist || (a.dist == b.dist && a.id < b.id); });
+    for (int p = 0; p < k; ++p) {
+      bool have = p < (int)hits.size();
+      out_ids[(int64_t)qi * k + p] = have ? hits[p].id : kPad;
+      out_dist[(int64_t)qi * k + p] = have ? hits[p].dist : INFINITY;
+    }
+  }
+}
+
+// ---------------------------------------------------------------- exact kNN
+// NN_k by exhaustive fp64 evaluation, order (distance, id).
+void orc_bruteforce_topk(const float *X, int64_t n, int32_t d, int32_t metric, const float *Q, int32_t nq, int32_t k,
+                         uint32_t *out_ids, double *out_dist) {
+  struct Hit {
+    double dist;
+    uint32_t id;
+  };
+  auto less = [](const Hit &a, const Hit &b) { return a.dist < b.dist || (a.dist == b.dist && a.id < b.id); };
+  std::vector<Hit> best;
+  for (int32_t qi = 0; qi < nq; ++qi) {
+    const float *q = Q + (int64_t)qi * d;
+    best.clear();
+    for (int64_t i = 0; i < n; ++i) {
+      const float *x = X + i * (int64_t)d;
+      double acc = 0.0;
+      for (int j = 0; j < d; ++j) {
+        if (metric == 0) {
+          double t = (double)q[j] - (double)x[j];
+          acc += t * t;
+        } else {
+          acc += (double)q[j] * (double)x[j];
+        }
+      }
+      Hit h{metric == 0 ? acc : -acc, (uint32_t)i};
+      if ((int)best.size() >= k && !less(h, best.back())) continue;
+      best.insert(std::upper_bound(best.begin(), best.end(), h, less), h);
+      if ((int)best.size() > k) best.pop_back();
+    }
+    for (int p = 0; p < k; ++p) {
+      bool have = p < (int)best.size();
+      out_ids[(int64_t)qi * k + p] = have ? best[p].id : kPad;
+      out_dist[(int64_t)qi * k + p] = have ? best[p].dist : INFINITY;
+    }
+  }
+}
+
+}  // extern "C"

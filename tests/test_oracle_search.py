@@ -1,0 +1,191 @@
+"""Pins for the oracle's Algorithm-1 control flow, rerank and exact kNN."""
+import numpy as np
+import pytest
+
+import inputs
+import oracle
+from conftest import read_golden, small_case
+from naive_search import naive_search
+
+PAD = 0xFFFFFFFF
+
+
+def all_keys(lv, d, q, metric):
+    t, s, qlo = oracle.query_prep(q, lv.lo, lv.delta)
+    return np.array([oracle.key(metric, s, qlo, oracle.idot(t, lv.codes[v], d, lv.bits), lv.norm_term[v])
+                     for v in range(lv.codes.shape[0])], np.float32)
+
+
+def test_ring_hand_trace():
+    g = read_golden("ring12_trace.txt")
+    n = int(g["n"][0])
+    X = np.zeros((n, 2), np.float32)
+    X[:, 0] = np.arange(n)
+    adj = np.stack([(np.arange(n) + 1) % n, (np.arange(n) - 1) % n], 1).astype(np.uint32)
+    q = np.array([[float(v) for v in g["query"]]], np.float32)
+    lv = oracle.sq_fit(X, 8)
+    ids, keys, dots, cnt = oracle.search_batch(lv, 2, adj, int(g["entry"][0]), q, int(g["ef"][0]))
+    assert ids[0].tolist() == [int(v) for v in g["final_pool"]]
+    assert cnt[0, 0] == int(g["n_expansions"][0])
+    assert cnt[0, 1] == int(g["n_distance_evaluations"][0])
+    assert cnt[0, 2] == len(g["final_pool"])
+
+
+def test_label_filter_paper_example():
+    """Section 4.3 worked example: 5 neighbours, m_s=3, alpha_s=1.2, 2nd label 1.4."""
+    g = read_golden("label_filter_example.txt")
+    labels_row = [float(v) for v in g["labels"]]
+    n = 6                                       # node 0 = x_i, nodes 1..5 = its neighbours by distance
+    X = np.zeros((n, 2), np.float32)
+    X[:, 0] = np.arange(n)
+    adj = np.full((n, 5), PAD, np.uint32)
+    adj[0] = [1, 2, 3, 4, 5]
+    labels = np.ones((n, 5), np.float32)
+    labels[0] = labels_row
+    lv = oracle.sq_fit(X, 8)
+    q = np.array([[0.0, 0.0]], np.float32)
+    ids, _, _, cnt = oracle.search_batch(lv, 2, adj, 0, q, 8, labels=labels, alpha_s=float(g["alpha_s"][0]),
+                                         m_s=int(g["m_s"][0]))
+    got = sorted(int(v) for v in ids[0] if v != PAD and v != 0)
+    assert got == [int(v) for v in g["visited"]]
+    assert cnt[0, 1] == 1 + len(g["visited"])
+
+
+@pytest.mark.parametrize("metric,bits", [(oracle.L2, 8), (oracle.IP, 8), (oracle.L2, 4)])
+def test_ef_at_least_n_is_bruteforce_under_tau_l(metric, bits):
+    """With ef >= N on a graph where every node is reachable the final pool is
+    every node, ordered by (key, id)."""
+    w, X, Q, adj = small_case(300, 16, 6, 5, seed=11, bits=bits)
+    assert inputs.count_reachable(adj, 0) == 300
+    lv = oracle.sq_fit(X, bits)
+    ids, keys, dots, cnt = oracle.search_batch(lv, w.d, adj, 0, Q, 320, metric=metric)
+    for qi in range(len(Q)):
+        k = all_keys(lv, w.d, Q[qi], metric)
+        order = np.lexsort((np.arange(300), k))
+        assert ids[qi, :300].tolist() == order.tolist()
+        assert (keys[qi, :300] == k[order]).all()
+        assert (ids[qi, 300:] == PAD).all() and np.isinf(keys[qi, 300:]).all()
+        assert cnt[qi].tolist() == [300, 300, 300, 0]
+
+
+def test_complete_graph_one_expansion_sees_everything():
+    n, ef = 40, 7
+    w = inputs.Workload("cg", n, 8, 3, 0.3, 4, seed=3)
+    X, Q = inputs.base_vectors(w), inputs.queries(w)
+    adj = np.array([[j for j in range(n) if j != i] for i in range(n)], np.uint32)
+    lv = oracle.sq_fit(X, 8)
+    ids, keys, dots, cnt = oracle.search_batch(lv, w.d, adj, 5, Q, ef)
+    for qi in range(len(Q)):
+        k = all_keys(lv, w.d, Q[qi], oracle.L2)
+        order = np.lexsort((np.arange(n), k))[:ef]
+        assert ids[qi].tolist() == order.tolist()
+        assert cnt[qi, 1] == n                  # everything evaluated once
+        assert cnt[qi, 0] in (ef, ef + 1)       # entry + survivors (entry may or may not survive)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_matches_naive_python_search_with_heavy_ties(seed):
+    """Few quantization levels and low d make equal keys common: the (key, id)
+    tie-break, eviction and termination must agree with the naive version."""
+    n = 64
+    rng = np.random.default_rng(seed)
+    X = rng.integers(0, 3, size=(n, 4)).astype(np.float32)
+    Q = rng.integers(0, 3, size=(6, 4)).astype(np.float32)
+    _, _, _, adj = small_case(n, 4, 5, 1, seed=seed + 100)
+    lv = oracle.sq_fit(X, 4)
+    labels = rng.choice([1.0, 1.2, 1.4], size=adj.shape).astype(np.float32)
+    for ef in (1, 3, 10, 70):
+        for metric in (oracle.L2, oracle.IP):
+            entries = rng.integers(0, n, size=(len(Q), 3)).astype(np.uint32)
+            entries[:, 2] = entries[:, 0]       # duplicate entry
+            for use_labels in (False, True):
+                kw = dict(labels=labels, alpha_s=1.2, m_s=3) if use_labels else {}
+                ids, keys, dots, cnt = oracle.search_batch(lv, 4, adj, 0, Q, ef, metric=metric, entries=entries,
+                                                           **kw)
+                for qi in range(len(Q)):
+                    k = all_keys(lv, 4, Q[qi], metric)
+                    pool, n_exp, n_dist = naive_search(k, adj, entries[qi], ef, **kw)
+                    m = len(pool)
+                    assert ids[qi, :m].tolist() == [v for _, v in pool]
+                    assert (ids[qi, m:] == PAD).all()
+                    assert cnt[qi, :3].tolist() == [n_exp, n_dist, m]
+
+
+def test_sequential_insertion_equals_sort_and_truncate():
+    """The pool is 'the ef smallest seen' once the pool's maximum only shrinks:
+    inserting one by one (dropping the farthest) equals sorting the union."""
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        ef = int(rng.integers(1, 12))
+        items = [(int(rng.integers(0, 5)), i) for i in range(int(rng.integers(1, 40)))]
+        rng.shuffle(items)
+        pool = []
+        for it in items:
+            if len(pool) >= ef and not it < pool[-1]:
+                continue
+            pool.append(it)
+            pool.sort()
+            del pool[ef:]
+        assert pool == sorted(items)[:ef]
+
+
+def test_c1_invariants_and_recall(c1):
+    w, X, Q, adj, entry, lv = (c1[k] for k in ("w", "X", "Q", "adj", "entry", "level"))
+    assert inputs.count_reachable(adj, entry) == w.n
+    ef = 64
+    ids, keys, dots, cnt = oracle.search_batch(lv, w.d, adj, entry, Q, ef)
+    again = oracle.search_batch(lv, w.d, adj, entry, Q, ef)
+    assert all((a == b).all() for a, b in zip((ids, keys, dots, cnt), again))
+    for qi in range(len(Q)):
+        m = cnt[qi, 2]
+        assert m == ef
+        row = ids[qi, :m]
+        assert len(set(row.tolist())) == m and row.max() < w.n
+        pairs = list(zip(keys[qi, :m].tolist(), row.tolist()))
+        assert pairs == sorted(pairs)
+        assert cnt[qi, 1] <= 1 + cnt[qi, 0] * w.degree
+        assert cnt[qi, 0] >= m                  # every surviving pool entry was expanded
+    gt, _ = oracle.bruteforce_topk(X, Q, w.k)
+    rid, rdist = oracle.rerank_batch(X, Q, ids[:, :2 * w.k], w.k)
+    assert oracle.recall(rid, gt) >= 0.97
+    assert oracle.recall(ids, gt) >= 0.90
+
+
+@pytest.mark.parametrize("metric", [oracle.L2, oracle.IP])
+def test_rerank_of_whole_base_is_exact_knn(metric):
+    w, X, Q, adj = small_case(200, 24, 5, 6, seed=21, normalize=(metric == oracle.IP))
+    lv = oracle.sq_fit(X, 8)
+    ids, *_ = oracle.search_batch(lv, w.d, adj, 0, Q, 200, metric=metric)
+    rid, rdist = oracle.rerank_batch(X, Q, ids, 10, metric=metric)
+    X64, Q64 = X.astype(np.float64), Q.astype(np.float64)
+    if metric == oracle.L2:
+        D = ((Q64[:, None, :] - X64[None, :, :]) ** 2).sum(2)
+    else:
+        D = -(Q64 @ X64.T)
+    for qi in range(len(Q)):
+        order = np.lexsort((np.arange(200), D[qi].astype(np.float32)))[:10]
+        assert rid[qi].tolist() == order.tolist()
+        np.testing.assert_allclose(rdist[qi], D[qi][order], rtol=1e-6, atol=1e-7)
+    bid, bdist = oracle.bruteforce_topk(X, Q, 10, metric=metric)
+    for qi in range(len(Q)):
+        order = np.lexsort((np.arange(200), D[qi]))[:10]
+        assert bid[qi].tolist() == order.tolist()
+        np.testing.assert_allclose(bdist[qi], D[qi][order], rtol=1e-12, atol=1e-12)
+
+
+def test_rescore_resorts_with_finer_codes():
+    w, X, Q, adj = small_case(300, 32, 6, 4, seed=31, bits=4)
+    l4, l8 = oracle.sq_fit(X, 4), oracle.sq_fit(X, 8)
+    ids, *_ = oracle.search_batch(l4, w.d, adj, 0, Q, 50, metric=oracle.IP)
+    rid, rkeys, rdots = oracle.rescore_batch(l8, w.d, Q, ids, metric=oracle.IP)
+    for qi in range(len(Q)):
+        k8 = all_keys(l8, w.d, Q[qi], oracle.IP)
+        cand = ids[qi][ids[qi] != PAD]
+        order = sorted((float(k8[v]), int(v)) for v in cand)
+        assert rid[qi, :len(order)].tolist() == [v for _, v in order]
+        assert rkeys[qi, :len(order)].tolist() == [k for k, _ in order]
+
+
+def test_recall_definition():
+    assert oracle.recall(np.array([[1, 2, 3, 4]]), np.array([[4, 3, 9, 8]])) == 0.5
+    assert oracle.recall(np.array([[1, 2, PAD, PAD]]), np.array([[1, 2, 3, 4]])) == 0.5
