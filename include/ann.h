@@ -1,0 +1,222 @@
+/*
+ * ann.h - C ABI of the MI355X (gfx950) batched graph-ANN search library.
+ *
+ * The library implements the data-parallel hot path of the VSAG search method
+ * (arXiv 2503.17911): best-first search over a fixed-degree proximity graph
+ * with scalar-quantized traversal distances, an exact fp32 rerank, and an
+ * exhaustive exact top-k used as ground truth for recall.
+ *
+ * Conventions that hold for every call
+ *   - All array arguments are DEVICE pointers unless a comment says "host".
+ *     The caller owns every input and output buffer; the library owns only the
+ *     packed index it builds in ann_upload_index and a per-index workspace.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return without waiting, except where noted.
+ *   - Ids are uint32_t < 2^31.  ANN_PAD_ID marks "no entry"; result lists
+ *     shorter than requested are padded with ANN_PAD_ID and +infinity.
+ *   - A "distance" is smaller-is-better: squared L2, or the NEGATED inner
+ *     product for ANN_IP.
+ *   - Every function returns an ann_status.  Argument errors are detected on
+ *     the host before anything is launched; ann_last_error() then returns a
+ *     message (thread-local, valid until the next call on that thread).
+ *   - No C++ exception crosses this boundary.
+ */
+#ifndef ANN_H_
+#define ANN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ANN_PAD_ID 0xFFFFFFFFu
+#define ANN_MAX_LEVELS 2
+#define ANN_MAX_EF 512u
+#define ANN_MAX_DEGREE 64u
+#define ANN_MAX_ENTRIES 64u
+
+typedef struct ann_index ann_index; /* opaque; device memory owned by the library */
+
+typedef enum {
+  ANN_OK = 0,
+  ANN_EINVAL = 1,       /* bad argument; nothing was launched                 */
+  ANN_ENOMEM = 2,       /* device or host allocation failed                   */
+  ANN_EDEVICE = 3,      /* a HIP call failed (message has the HIP error)      */
+  ANN_EUNSUPPORTED = 4, /* valid request outside the built kernel variants    */
+  ANN_ECAPACITY = 5     /* a size exceeds a documented maximum                */
+} ann_status;
+
+typedef enum { ANN_L2 = 0, ANN_IP = 1 } ann_metric;
+
+/* ann_index_desc.flags */
+#define ANN_DESC_HOST_POINTERS 1u /* every array in the descriptor is in HOST memory */
+
+/*
+ * One scalar-quantization level (paper Appendix G, SQ-b with b = bits).
+ *   codes     [n][row_bytes], row_bytes = d (bits 8) or d/2 (bits 4, d even;
+ *             dimension 2i in the low nibble of byte i, 2i+1 in the high one);
+ *             code c of dimension j decodes to lo[j] + delta[j] * c.
+ *   lo, delta [d] per-dimension minimum and step.
+ *   norm_term [n] squared norm of the decoded vector: the one extra fp32 per
+ *             base vector of the paper's distance decomposition (Section 5.2).
+ *             May be NULL for ANN_IP.
+ */
+typedef struct {
+  uint32_t bits;
+  const uint8_t *codes;
+  const float *lo;
+  const float *delta;
+  const float *norm_term;
+} ann_sq_level;
+
+/*
+ * Everything ann_upload_index needs (the G, D and I of Algorithm 1).
+ *   vectors   [n][d] fp32 base vectors for the rerank; NULL disables ann_rerank.
+ *   level[0]  codes used during traversal; level[1] (optional) a finer level
+ *             for ann_rescore.
+ *   adjacency fixed-degree form (csr_offsets == NULL): [n][degree], unused
+ *             slots ANN_PAD_ID.  CSR form: csr_offsets is [n+1] and adjacency
+ *             holds csr_offsets[n] neighbour ids; rows longer than `degree` are
+ *             an error.  degree <= ANN_MAX_DEGREE.
+ *   entry_point  default initial node of every search.
+ */
+typedef struct {
+  uint64_t n;
+  uint32_t d;
+  uint32_t degree;
+  uint32_t metric; /* ann_metric */
+  uint32_t n_levels;
+  const float *vectors;
+  ann_sq_level level[ANN_MAX_LEVELS];
+  const uint32_t *adjacency;
+  const uint64_t *csr_offsets;
+  uint32_t entry_point;
+  uint32_t flags;
+} ann_index_desc;
+
+/*
+ * Search parameters (k and ef_s of Algorithm 1 plus launch knobs that change
+ * speed only).
+ *   ef            pool size, k <= ef <= ANN_MAX_EF.
+ *   mode          0: one expansion per step, results identical to a sequential
+ *                    execution of Algorithm 1 with (key, id) tie-breaking;
+ *                 1: several expansions per step (faster, approximate order of
+ *                    expansion; same pool/visited semantics).
+ *   expansions_per_step   mode 1 only, 1..8 (0 = library default).
+ *   visited_slots number of slots of the per-query visited hash table in LDS,
+ *                 a power of two, 0 = chosen from ef and degree.  When the
+ *                 table fills it is rebuilt from the current pool; this costs
+ *                 repeated distance evaluations, never a different result.
+ */
+typedef struct {
+  uint32_t k;
+  uint32_t ef;
+  uint32_t mode;
+  uint32_t expansions_per_step;
+  uint32_t visited_slots;
+  uint32_t reserved[3]; /* must be zero */
+} ann_search_params;
+
+/*
+ * Scalar-quantization codebook and encoder (paper Appendix G; per-dimension
+ * range reading).  ann_sq_train writes lo[j] = min_i x[i][j] and delta[j] =
+ * (max - min) / (2^bits - 1) (1 if the range is empty).  ann_sq_encode writes
+ * codes = clamp(floor((x - lo) / delta + 0.5), 0, 2^bits - 1) in the layout of
+ * ann_sq_level and, if norm_term != NULL, the squared norms of the decoded rows
+ * (fp64 accumulation in dimension order, rounded once).
+ *   x [n][d] fp32; bits 8 or 4 (d even for 4).  Both calls allocate a small
+ *   temporary and synchronise the stream before returning.
+ */
+ann_status ann_sq_train(const float *x, uint64_t n, uint32_t d, uint32_t bits, float *lo, float *delta,
+                        void *stream);
+ann_status ann_sq_encode(const float *x, uint64_t n, uint32_t d, uint32_t bits, const float *lo,
+                         const float *delta, uint8_t *codes, float *norm_term, void *stream);
+
+/*
+ * Build the device index: copy (or upload) the arrays of `desc`, repack codes
+ * into 16-byte aligned rows and the adjacency into [n][degree].  Synchronous;
+ * the descriptor's arrays may be released afterwards.  *out receives the index.
+ * Errors: ANN_EINVAL (NULL arrays, n == 0 or n >= 2^31, degree == 0, bits not
+ * 4/8, odd d with 4 bits, entry_point >= n, neighbour id >= n), ANN_ECAPACITY
+ * (degree > ANN_MAX_DEGREE, d > 2048), ANN_ENOMEM, ANN_EDEVICE.
+ */
+ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index **out);
+ann_status ann_free_index(ann_index *index); /* synchronises the device; NULL is a no-op */
+
+/*
+ * Query folding for one code level (the query side of the low-precision
+ * distance; paper Section 5.2 precomputes the query terms before the search):
+ * a_j = delta_j * q_j, s = max|a| / 127, t_j = rint(a_j * 127 / max|a|) as
+ * int8, qlo = sum_j q_j * lo_j.  Outputs (any may be NULL): t [nq][d] int8,
+ * s [nq], qlo [nq].  ann_search_batch does this internally; the entry point
+ * exists so the folded query can be inspected.
+ */
+ann_status ann_query_prep(ann_index *index, uint32_t level, const float *q, uint32_t nq, int8_t *t, float *s,
+                          float *qlo, void *stream);
+
+/*
+ * Algorithm 1 ("Deterministic Access Greedy Search") for a batch of queries,
+ * up to but excluding the final rerank: returns the whole final pool.
+ *   q          [nq][d] fp32.
+ *   entry_ids  NULL: every query starts from the index entry point; otherwise
+ *              [nq][n_entry] initial nodes per query (ANN_PAD_ID and duplicates
+ *              are skipped), n_entry <= ANN_MAX_ENTRIES.
+ *   out_ids    [nq][ef] pool ids in ascending (key, id) order.
+ *   out_keys   [nq][ef] traversal keys (NULL allowed).  L2: ||x^||^2 - 2 q.x^
+ *              (the squared distance to the decoded vector minus ||q||^2);
+ *              IP: -(q.x^); both with the query folded to int8.
+ *   out_idot   [nq][ef] the int32 code/query dot products (NULL allowed; asking
+ *              for them costs one more pass over the pool's code rows).
+ *   out_counts [nq][4] (NULL allowed): expansions, distance evaluations,
+ *              pool size, visited-table rebuilds.
+ * Errors: ANN_EINVAL (NULL q/out_ids/params, nq == 0, k == 0, ef < k, reserved
+ * fields non-zero, visited_slots not a power of two or too small for ef),
+ * ANN_ECAPACITY (ef > ANN_MAX_EF, n_entry > ANN_MAX_ENTRIES), ANN_ENOMEM when
+ * the per-index workspace has to grow for a larger nq (the only allocation on
+ * this path), ANN_EDEVICE.
+ */
+ann_status ann_search_batch(ann_index *index, const float *q, uint32_t nq, const ann_search_params *params,
+                            const uint32_t *entry_ids, uint32_t n_entry, uint32_t *out_ids, float *out_keys,
+                            int32_t *out_idot, uint32_t *out_counts, void *stream);
+
+/*
+ * Re-evaluate candidates with code level `level` and sort them by (key, id):
+ * the middle stage of a low -> higher -> full precision cascade.
+ *   cand_ids [nq][cand_stride], the first n_cand of each row are used
+ *   (ANN_PAD_ID skipped); outputs [nq][n_cand].  n_cand <= 4096.
+ */
+ann_status ann_rescore(ann_index *index, uint32_t level, const float *q, uint32_t nq, const uint32_t *cand_ids,
+                       uint32_t n_cand, uint32_t cand_stride, uint32_t *out_ids, float *out_keys,
+                       int32_t *out_idot, void *stream);
+
+/*
+ * Final line of Algorithm 1 with a fixed-length prefix in place of the
+ * paper's selective rerank: exact distance tau_h on the fp32 base vectors for
+ * the first n_cand candidates of each row of cand_ids [nq][cand_stride], sorted
+ * by (distance, id); the best k go to out_ids / out_dist [nq][k].
+ * Distances are accumulated in fp64 and rounded once to fp32.
+ * n_cand <= 4096, k <= n_cand.  ANN_EINVAL if the index holds no fp32 vectors.
+ */
+ann_status ann_rerank(ann_index *index, const float *q, uint32_t nq, const uint32_t *cand_ids, uint32_t n_cand,
+                      uint32_t cand_stride, uint32_t k, uint32_t *out_ids, float *out_dist, void *stream);
+
+/*
+ * Exact k nearest neighbours NN_k of every query by exhaustive search (the
+ * ground truth of the paper's recall, Section 6.1): a dense Q.X^T contraction
+ * on the matrix cores selects k + margin candidates per query, which are then
+ * re-evaluated directly in fp64 and sorted by (distance, id).
+ *   x [n][d], q [nq][d] fp32; out_ids/out_dist [nq][k]; k <= 256.
+ * Allocates temporaries and synchronises the stream before returning.
+ */
+ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d, const float *q, uint32_t nq, uint32_t k,
+                               uint32_t metric, uint32_t *out_ids, float *out_dist, void *stream);
+
+const char *ann_last_error(void);
+const char *ann_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ANN_H_ */

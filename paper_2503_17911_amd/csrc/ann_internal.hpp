@@ -1,0 +1,65 @@
+// Internal declarations shared by the translation units of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ann.h"
+
+namespace ann {
+
+constexpr int kWave = 64;
+
+// Device copy of one code level, in the layout the kernels read.
+struct LevelDev {
+  uint32_t bits = 0;
+  uint32_t row_bytes = 0;    // d or d/2: the bytes that carry codes
+  uint32_t row_stride = 0;   // row_bytes rounded up to 16
+  uint32_t lanes_per_row = 0;  // power of two >= row_stride/16, in {8,16,32,64}
+  uint8_t *codes = nullptr;  // [n][row_stride]; 8-bit codes stored as (c ^ 0x80), 4-bit codes as given
+  float *lo = nullptr;       // [d]
+  float *delta = nullptr;    // [d]
+  float *norm_term = nullptr;  // [n] or nullptr
+};
+
+// Per-index scratch for the folded queries of one batch.
+struct Workspace {
+  uint32_t nq_cap = 0;
+  uint8_t *tq = nullptr;   // [nq_cap][tq_stride] folded query in kernel layout
+  float *s = nullptr;      // [nq_cap]
+  float *qlo = nullptr;    // [nq_cap]
+  int32_t *sum_t = nullptr;  // [nq_cap]
+  uint32_t tq_stride = 0;
+};
+
+}  // namespace ann
+
+struct ann_index {
+  uint64_t n = 0;
+  uint32_t d = 0, degree = 0, metric = 0, n_levels = 0, entry_point = 0;
+  float *vectors = nullptr;    // [n][d] or nullptr
+  uint32_t *adjacency = nullptr;  // [n][degree]
+  ann::LevelDev level[ANN_MAX_LEVELS];
+  ann::Workspace ws[ANN_MAX_LEVELS];
+  int device = 0;
+};
+
+namespace ann {
+
+// Error reporting (thread-local message behind ann_last_error()).
+ann_status fail(ann_status code, const char *fmt, ...);
+ann_status hip_fail(hipError_t e, const char *what);
+#define ANN_HIP(call)                                        \
+  do {                                                       \
+    hipError_t e_ = (call);                                  \
+    if (e_ != hipSuccess) return ::ann::hip_fail(e_, #call); \
+  } while (0)
+
+// Kernel-layout length of a folded query for a level: one 16-byte chunk of
+// codes per lane needs 16 (8-bit) or 32 (4-bit) query bytes.
+inline uint32_t tq_stride_for(const LevelDev &L) { return L.lanes_per_row * (L.bits == 8 ? 16u : 32u); }
+
+ann_status ensure_workspace(ann_index *index, uint32_t level, uint32_t nq);
+ann_status launch_query_prep(ann_index *index, uint32_t level, const float *q, uint32_t nq, int8_t *t_plain,
+                             float *s_out, float *qlo_out, hipStream_t stream);
+
+}  // namespace ann

@@ -1,0 +1,263 @@
+// Host side of the library: error reporting, index upload/packing, workspace.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "ann_internal.hpp"
+
+namespace ann {
+
+static thread_local char g_err[512] = "";
+
+ann_status fail(ann_status code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+ann_status hip_fail(hipError_t e, const char *what) {
+  ann_status code = (e == hipErrorOutOfMemory) ? ANN_ENOMEM : ANN_EDEVICE;
+  return fail(code, "%s: %s", what, hipGetErrorString(e));
+}
+
+// ---------------------------------------------------------------- pack kernels
+// codes [n][row_bytes] -> [n][row_stride]; 8-bit codes are stored biased by
+// 128 (c ^ 0x80 read as int8 is c - 128) so the signed packed-dot instruction
+// applies; padding bytes are never multiplied by a non-zero query byte.
+__global__ void pack_codes_kernel(const uint8_t *__restrict__ in, uint8_t *__restrict__ out, uint64_t n,
+                                  uint32_t row_bytes, uint32_t row_stride, uint32_t flip) {
+  uint64_t total = n * row_stride;
+  for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < total; e += (uint64_t)gridDim.x * blockDim.x) {
+    uint64_t i = e / row_stride;
+    uint32_t b = (uint32_t)(e - i * row_stride);
+    uint8_t v = (b < row_bytes) ? in[i * row_bytes + b] : 0;
+    out[e] = (uint8_t)(v ^ flip);
+  }
+}
+
+// CSR -> [n][degree] with padding; sets *bad if a row is too long.
+__global__ void pack_csr_kernel(const uint32_t *__restrict__ cols, const uint64_t *__restrict__ offsets,
+                                uint32_t *__restrict__ out, uint64_t n, uint32_t degree, uint32_t *bad) {
+  uint64_t total = n * degree;
+  for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < total; e += (uint64_t)gridDim.x * blockDim.x) {
+    uint64_t i = e / degree;
+    uint32_t t = (uint32_t)(e - i * degree);
+    uint64_t b = offsets[i], len = offsets[i + 1] - b;
+    if (t == 0 && len > degree) atomicOr(bad, 1u);
+    out[e] = (t < len) ? cols[b + t] : ANN_PAD_ID;
+  }
+}
+
+__global__ void check_adjacency_kernel(const uint32_t *__restrict__ adj, uint64_t total, uint64_t n, uint32_t *bad) {
+  for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < total; e += (uint64_t)gridDim.x * blockDim.x) {
+    uint32_t v = adj[e];
+    if (v != ANN_PAD_ID && v >= n) atomicOr(bad, 2u);
+  }
+}
+
+namespace {
+
+// Device buffer holding a copy of `count` elements from host or device memory.
+template <typename T>
+ann_status dev_copy(T **dst, const T *src, size_t count, bool src_on_host, hipStream_t st) {
+  *dst = nullptr;
+  if (count == 0) return ANN_OK;
+  ANN_HIP(hipMalloc((void **)dst, count * sizeof(T)));
+  ANN_HIP(hipMemcpyAsync(*dst, src, count * sizeof(T), src_on_host ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice,
+                         st));
+  return ANN_OK;
+}
+
+void free_workspace(Workspace &w) {
+  (void)hipFree(w.tq);
+  (void)hipFree(w.s);
+  (void)hipFree(w.qlo);
+  (void)hipFree(w.sum_t);
+  w = Workspace{};
+}
+
+void destroy(ann_index *ix) {
+  if (!ix) return;
+  (void)hipFree(ix->vectors);
+  (void)hipFree(ix->adjacency);
+  for (int l = 0; l < ANN_MAX_LEVELS; ++l) {
+    (void)hipFree(ix->level[l].codes);
+    (void)hipFree(ix->level[l].lo);
+    (void)hipFree(ix->level[l].delta);
+    (void)hipFree(ix->level[l].norm_term);
+    free_workspace(ix->ws[l]);
+  }
+  delete ix;
+}
+
+inline int grid_for(uint64_t total, int block) {
+  uint64_t g = (total + block - 1) / block;
+  return (int)(g > 65535 * 16 ? 65535 * 16 : (g ? g : 1));
+}
+
+}  // namespace
+
+ann_status ensure_workspace(ann_index *ix, uint32_t level, uint32_t nq) {
+  Workspace &w = ix->ws[level];
+  if (nq <= w.nq_cap) return ANN_OK;
+  // growth is the only allocation on the search path; it waits for work that
+  // may still be using the old buffers
+  ANN_HIP(hipDeviceSynchronize());
+  free_workspace(w);
+  uint32_t cap = nq < 1024 ? 1024 : nq;
+  w.tq_stride = tq_stride_for(ix->level[level]);
+  ANN_HIP(hipMalloc((void **)&w.tq, (size_t)cap * w.tq_stride));
+  ANN_HIP(hipMalloc((void **)&w.s, (size_t)cap * sizeof(float)));
+  ANN_HIP(hipMalloc((void **)&w.qlo, (size_t)cap * sizeof(float)));
+  ANN_HIP(hipMalloc((void **)&w.sum_t, (size_t)cap * sizeof(int32_t)));
+  w.nq_cap = cap;
+  return ANN_OK;
+}
+
+}  // namespace ann
+
+using namespace ann;
+
+extern "C" {
+
+const char *ann_last_error(void) { return g_err; }
+const char *ann_version(void) { return "ann-gfx950 0.1"; }
+
+ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index **out) {
+  hipStream_t st = (hipStream_t)stream;
+  if (!out) return fail(ANN_EINVAL, "ann_upload_index: out is NULL");
+  *out = nullptr;
+  if (!desc) return fail(ANN_EINVAL, "ann_upload_index: desc is NULL");
+  if (desc->n == 0 || desc->n >= (1ull << 31)) return fail(ANN_EINVAL, "n must be in [1, 2^31), got %llu", (unsigned long long)desc->n);
+  if (desc->d == 0) return fail(ANN_EINVAL, "d must be positive");
+  if (desc->d > 2048) return fail(ANN_ECAPACITY, "d = %u exceeds the supported maximum 2048", desc->d);
+  if (desc->degree == 0) return fail(ANN_EINVAL, "degree must be positive");
+  if (desc->degree > ANN_MAX_DEGREE) return fail(ANN_ECAPACITY, "degree = %u exceeds ANN_MAX_DEGREE = %u", desc->degree, ANN_MAX_DEGREE);
+  if (desc->metric != ANN_L2 && desc->metric != ANN_IP) return fail(ANN_EINVAL, "unknown metric %u", desc->metric);
+  if (desc->n_levels < 1 || desc->n_levels > ANN_MAX_LEVELS) return fail(ANN_EINVAL, "n_levels must be 1..%d", ANN_MAX_LEVELS);
+  if (!desc->adjacency) return fail(ANN_EINVAL, "adjacency is NULL");
+  if (desc->entry_point >= desc->n) return fail(ANN_EINVAL, "entry_point %u is not a node", desc->entry_point);
+  for (uint32_t l = 0; l < desc->n_levels; ++l) {
+    const ann_sq_level &L = desc->level[l];
+    if (L.bits != 8 && L.bits != 4) return fail(ANN_EINVAL, "level %u: bits must be 4 or 8, got %u", l, L.bits);
+    if (L.bits == 4 && (desc->d & 1)) return fail(ANN_EINVAL, "level %u: 4-bit codes need an even d", l);
+    if (!L.codes || !L.lo || !L.delta) return fail(ANN_EINVAL, "level %u: codes, lo and delta must be given", l);
+    if (desc->metric == ANN_L2 && !L.norm_term) return fail(ANN_EINVAL, "level %u: norm_term is required for ANN_L2", l);
+  }
+  const bool host = (desc->flags & ANN_DESC_HOST_POINTERS) != 0;
+  const uint64_t n = desc->n;
+
+  ann_index *ix = new (std::nothrow) ann_index();
+  if (!ix) return fail(ANN_ENOMEM, "host allocation failed");
+  ix->n = n;
+  ix->d = desc->d;
+  ix->degree = desc->degree;
+  ix->metric = desc->metric;
+  ix->n_levels = desc->n_levels;
+  ix->entry_point = desc->entry_point;
+  (void)hipGetDevice(&ix->device);
+
+  ann_status rc = ANN_OK;
+  uint32_t *bad_dev = nullptr;
+  uint8_t *raw_codes = nullptr;
+  uint32_t *raw_cols = nullptr;
+  uint64_t *raw_offs = nullptr;
+  auto cleanup = [&](ann_status r) {
+    (void)hipFree(bad_dev);
+    (void)hipFree(raw_codes);
+    (void)hipFree(raw_cols);
+    (void)hipFree(raw_offs);
+    if (r != ANN_OK) destroy(ix);
+    return r;
+  };
+#define ANN_TRY(expr)                      \
+  do {                                     \
+    rc = (expr);                           \
+    if (rc != ANN_OK) return cleanup(rc);  \
+  } while (0)
+#define ANN_TRY_HIP(call)                                         \
+  do {                                                            \
+    hipError_t e_ = (call);                                       \
+    if (e_ != hipSuccess) return cleanup(hip_fail(e_, #call));    \
+  } while (0)
+
+  ANN_TRY_HIP(hipMalloc((void **)&bad_dev, sizeof(uint32_t)));
+  ANN_TRY_HIP(hipMemsetAsync(bad_dev, 0, sizeof(uint32_t), st));
+
+  if (desc->vectors) ANN_TRY(dev_copy(&ix->vectors, desc->vectors, (size_t)n * desc->d, host, st));
+
+  for (uint32_t l = 0; l < desc->n_levels; ++l) {
+    const ann_sq_level &S = desc->level[l];
+    LevelDev &L = ix->level[l];
+    L.bits = S.bits;
+    L.row_bytes = S.bits == 8 ? desc->d : desc->d / 2;
+    L.row_stride = (L.row_bytes + 15u) & ~15u;
+    uint32_t chunks = L.row_stride / 16u, lpr = 8;
+    while (lpr < chunks) lpr <<= 1;
+    if (lpr > 64) return cleanup(fail(ANN_ECAPACITY, "level %u: code rows of %u bytes exceed 1024", l, L.row_bytes));
+    L.lanes_per_row = lpr;
+    ANN_TRY(dev_copy(&L.lo, S.lo, desc->d, host, st));
+    ANN_TRY(dev_copy(&L.delta, S.delta, desc->d, host, st));
+    if (S.norm_term) ANN_TRY(dev_copy(&L.norm_term, S.norm_term, (size_t)n, host, st));
+    const uint8_t *src = S.codes;
+    if (host) {
+      ANN_TRY(dev_copy(&raw_codes, S.codes, (size_t)n * L.row_bytes, true, st));
+      src = raw_codes;
+    }
+    ANN_TRY_HIP(hipMalloc((void **)&L.codes, (size_t)n * L.row_stride));
+    uint64_t total = n * L.row_stride;
+    pack_codes_kernel<<<grid_for(total, 256), 256, 0, st>>>(src, L.codes, n, L.row_bytes, L.row_stride,
+                                                            S.bits == 8 ? 0x80u : 0u);
+    ANN_TRY_HIP(hipGetLastError());
+    if (host) {
+      ANN_TRY_HIP(hipStreamSynchronize(st));
+      (void)hipFree(raw_codes);
+      raw_codes = nullptr;
+    }
+  }
+
+  const uint64_t total_adj = n * desc->degree;
+  if (desc->csr_offsets) {
+    const uint64_t *offs = desc->csr_offsets;
+    const uint32_t *cols = desc->adjacency;
+    uint64_t nnz = 0;
+    if (host) {
+      nnz = desc->csr_offsets[n];
+      ANN_TRY(dev_copy(&raw_offs, desc->csr_offsets, (size_t)n + 1, true, st));
+      ANN_TRY(dev_copy(&raw_cols, desc->adjacency, (size_t)nnz, true, st));
+      offs = raw_offs;
+      cols = raw_cols;
+    }
+    ANN_TRY_HIP(hipMalloc((void **)&ix->adjacency, total_adj * sizeof(uint32_t)));
+    pack_csr_kernel<<<grid_for(total_adj, 256), 256, 0, st>>>(cols, offs, ix->adjacency, n, desc->degree, bad_dev);
+    ANN_TRY_HIP(hipGetLastError());
+  } else {
+    ANN_TRY(dev_copy(&ix->adjacency, desc->adjacency, (size_t)total_adj, host, st));
+  }
+  check_adjacency_kernel<<<grid_for(total_adj, 256), 256, 0, st>>>(ix->adjacency, total_adj, n, bad_dev);
+  ANN_TRY_HIP(hipGetLastError());
+  uint32_t bad = 0;
+  ANN_TRY_HIP(hipMemcpyAsync(&bad, bad_dev, sizeof(bad), hipMemcpyDeviceToHost, st));
+  ANN_TRY_HIP(hipStreamSynchronize(st));
+  if (bad & 1u) return cleanup(fail(ANN_EINVAL, "a CSR row has more than degree = %u neighbours", desc->degree));
+  if (bad & 2u) return cleanup(fail(ANN_EINVAL, "adjacency holds a neighbour id >= n"));
+#undef ANN_TRY
+#undef ANN_TRY_HIP
+  cleanup(ANN_OK);
+  *out = ix;
+  return ANN_OK;
+}
+
+ann_status ann_free_index(ann_index *index) {
+  if (!index) return ANN_OK;
+  (void)hipDeviceSynchronize();
+  destroy(index);
+  return ANN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,245 @@
+// Candidate re-evaluation: the exact fp32 rerank that ends Algorithm 1 (the
+// paper's line "re-rank C with tau_l and tau_h", here over a fixed-length
+// prefix of the pool) and the rescore with a finer code level.  One query per
+// wavefront; candidates are ordered by ranking every (value, id) pair against
+// all others in LDS.
+#include "ann_internal.hpp"
+#include "device_utils.hpp"
+
+namespace ann {
+
+constexpr uint32_t kNone = 0xFFFFFFFFu;
+
+__device__ __forceinline__ uint64_t pack_vi(uint32_t hi, uint32_t lo) { return ((uint64_t)hi << 32) | lo; }
+
+// Rank of every element of list[0..n) under (value, position) order, written
+// to out positions; elements equal to the all-ones sentinel sort last.
+// `emit(rank, index)` is called for every element by the lane that owns it.
+template <typename Emit>
+__device__ __forceinline__ void rank_all(const uint64_t *list, uint32_t n, int lane, Emit emit) {
+  for (uint32_t i = lane; i < n; i += kWave) {
+    const uint64_t e = list[i];
+    uint32_t rank = 0;
+    for (uint32_t j = 0; j < n; ++j) {
+      const uint64_t o = list[j];
+      rank += (o < e || (o == e && j < i)) ? 1u : 0u;
+    }
+    emit(rank, i, e);
+  }
+}
+
+// ------------------------------------------------------------------ rerank
+// tau_h on the original vectors.  L2: sum (q - x)^2; IP: -(q . x).  Products
+// and sums in fp64 (each lane sums a strided share, then a butterfly), one
+// rounding to fp32 at the end.
+template <int LPR, bool VEC4>
+__global__ __launch_bounds__(64) void rerank_kernel(const float *__restrict__ X, uint32_t d, uint32_t metric,
+                                                    const float *__restrict__ Q, uint32_t nq, uint64_t n,
+                                                    const uint32_t *__restrict__ cand_ids, uint32_t n_cand,
+                                                    uint32_t cand_stride, uint32_t k, uint32_t *__restrict__ out_ids,
+                                                    float *__restrict__ out_dist) {
+  extern __shared__ uint64_t smem64[];
+  float *qs = reinterpret_cast<float *>(smem64);             // [d], 16-byte aligned
+  uint64_t *list = smem64 + ((d + 3) / 4) * 2;               // [n_cand]
+  const uint32_t qi = blockIdx.x;
+  if (qi >= nq) return;
+  const int lane = threadIdx.x, chunk = lane % LPR, grp = lane / LPR;
+  constexpr int G = kWave / LPR;
+  for (uint32_t j = lane; j < d; j += kWave) qs[j] = Q[(uint64_t)qi * d + j];
+  __syncthreads();
+  const uint32_t *cand = cand_ids + (uint64_t)qi * cand_stride;
+  for (uint32_t base = 0; base < n_cand; base += G) {
+    const uint32_t ci = base + grp;
+    uint32_t v = ci < n_cand ? cand[ci] : kNone;
+    if (v != kNone && v >= n) v = kNone;
+    double acc = 0.0;
+    if (v != kNone) {
+      const float *x = X + (uint64_t)v * d;
+      if constexpr (VEC4) {
+        for (uint32_t c = chunk; c < d / 4; c += LPR) {
+          const float4 xv = *reinterpret_cast<const float4 *>(x + 4 * c);
+          const float4 qv = *reinterpret_cast<const float4 *>(qs + 4 * c);
+          if (metric == ANN_L2) {
+            const double t0 = (double)qv.x - (double)xv.x, t1 = (double)qv.y - (double)xv.y;
+            const double t2 = (double)qv.z - (double)xv.z, t3 = (double)qv.w - (double)xv.w;
+            acc += t0 * t0;
+            acc += t1 * t1;
+            acc += t2 * t2;
+            acc += t3 * t3;
+          } else {
+            acc += (double)qv.x * (double)xv.x;
+            acc += (double)qv.y * (double)xv.y;
+            acc += (double)qv.z * (double)xv.z;
+            acc += (double)qv.w * (double)xv.w;
+          }
+        }
+      } else {
+        for (uint32_t j = chunk; j < d; j += LPR) {
+          if (metric == ANN_L2) {
+            const double t = (double)qs[j] - (double)x[j];
+            acc += t * t;
+          } else {
+            acc += (double)qs[j] * (double)x[j];
+          }
+        }
+      }
+    }
+    acc = group_sum_f64<LPR>(acc);
+    if (chunk == 0 && ci < n_cand) {
+      float dist = (float)(metric == ANN_L2 ? acc : -acc);
+      uint32_t b = __float_as_uint(dist);
+      if ((b & 0x7FFFFFFFu) == 0) dist = 0.0f;
+      list[ci] = v == kNone ? ~0ull : pack_vi(order_u32(dist), v);
+    }
+  }
+  __syncthreads();
+  rank_all(list, n_cand, lane, [&](uint32_t rank, uint32_t, uint64_t e) {
+    if (rank < k) {
+      const bool none = e == ~0ull;
+      out_ids[(uint64_t)qi * k + rank] = none ? kNone : (uint32_t)e;
+      out_dist[(uint64_t)qi * k + rank] = none ? INFINITY : unorder_f32((uint32_t)(e >> 32));
+    }
+  });
+}
+
+// ------------------------------------------------------------------ rescore
+// Keys of the candidates under another code level, then a full sort.
+template <int BITS, int LPR>
+__global__ __launch_bounds__(64) void rescore_kernel(const uint8_t *__restrict__ codes, uint32_t row_stride,
+                                                     uint32_t n_chunks, const float *__restrict__ norm_term,
+                                                     uint32_t metric, uint64_t n, const uint8_t *__restrict__ tq,
+                                                     uint32_t tq_stride, const float *__restrict__ s_arr,
+                                                     const float *__restrict__ qlo_arr,
+                                                     const int32_t *__restrict__ sum_t, uint32_t nq,
+                                                     const uint32_t *__restrict__ cand_ids, uint32_t n_cand,
+                                                     uint32_t cand_stride, uint32_t *__restrict__ out_ids,
+                                                     float *__restrict__ out_keys, int32_t *__restrict__ out_idot) {
+  extern __shared__ uint64_t smem64[];
+  uint64_t *list = smem64;                                     // [n_cand]
+  int32_t *dots = reinterpret_cast<int32_t *>(smem64 + n_cand);  // [n_cand]
+  const uint32_t qi = blockIdx.x;
+  if (qi >= nq) return;
+  const int lane = threadIdx.x, chunk = lane % LPR, grp = lane / LPR;
+  constexpr int G = kWave / LPR;
+  constexpr int TQW = TqRegs<BITS>::kWords;
+  int tqr[TQW];
+  const int *tqp = reinterpret_cast<const int *>(tq + (uint64_t)qi * tq_stride + (uint32_t)chunk * (TQW * 4u));
+#pragma unroll
+  for (int w = 0; w < TQW; ++w) tqr[w] = tqp[w];
+  const float s = s_arr[qi], qlo = qlo_arr[qi];
+  const int bias = BITS == 8 ? 128 * sum_t[qi] : 0;
+  const uint32_t *cand = cand_ids + (uint64_t)qi * cand_stride;
+  for (uint32_t base = 0; base < n_cand; base += G) {
+    const uint32_t ci = base + grp;
+    uint32_t v = ci < n_cand ? cand[ci] : kNone;
+    if (v != kNone && v >= n) v = kNone;
+    uint4 row = make_uint4(0, 0, 0, 0);
+    float nrm = 0.0f;
+    if (v != kNone) {
+      if (chunk < (int)n_chunks)
+        row = *reinterpret_cast<const uint4 *>(codes + (uint64_t)v * row_stride + (uint32_t)chunk * 16u);
+      if (norm_term && chunk == 0) nrm = norm_term[v];
+    }
+    const int dot = group_sum_i32<LPR>(chunk_dot<BITS>(row, tqr)) + bias;
+    if (chunk == 0 && ci < n_cand) {
+      const float key = key_from_idot(metric, s, qlo, dot, nrm);
+      list[ci] = v == kNone ? ~0ull : pack_vi(order_u32(key), v);
+      dots[ci] = v == kNone ? 0 : dot;
+    }
+  }
+  __syncthreads();
+  rank_all(list, n_cand, lane, [&](uint32_t rank, uint32_t i, uint64_t e) {
+    const bool none = e == ~0ull;
+    out_ids[(uint64_t)qi * n_cand + rank] = none ? kNone : (uint32_t)e;
+    if (out_keys) out_keys[(uint64_t)qi * n_cand + rank] = none ? INFINITY : unorder_f32((uint32_t)(e >> 32));
+    if (out_idot) out_idot[(uint64_t)qi * n_cand + rank] = dots[i];
+  });
+}
+
+template <bool VEC4>
+static void launch_rerank(uint32_t lpr, const float *X, uint32_t d, uint32_t metric, const float *Q, uint32_t nq,
+                          uint64_t n, const uint32_t *cand, uint32_t n_cand, uint32_t stride, uint32_t k,
+                          uint32_t *out_ids, float *out_dist, size_t smem, hipStream_t st) {
+#define ANN_RR(L) rerank_kernel<L, VEC4><<<nq, 64, smem, st>>>(X, d, metric, Q, nq, n, cand, n_cand, stride, k, out_ids, out_dist)
+  switch (lpr) {
+    case 8: ANN_RR(8); break;
+    case 16: ANN_RR(16); break;
+    case 32: ANN_RR(32); break;
+    default: ANN_RR(64); break;
+  }
+#undef ANN_RR
+}
+
+// Shared by ann_rerank and the final stage of ann_bruteforce_topk.
+ann_status rerank_device(const float *X, uint64_t n, uint32_t d, uint32_t metric, const float *Q, uint32_t nq,
+                         const uint32_t *cand, uint32_t n_cand, uint32_t stride, uint32_t k, uint32_t *out_ids,
+                         float *out_dist, hipStream_t st) {
+  uint32_t chunks = (d + 3) / 4, lpr = 8;
+  while (lpr < chunks && lpr < 64) lpr <<= 1;
+  const size_t smem = (size_t)n_cand * sizeof(uint64_t) + (size_t)((d + 3) / 4) * 16;
+  if (d % 4 == 0)
+    launch_rerank<true>(lpr, X, d, metric, Q, nq, n, cand, n_cand, stride, k, out_ids, out_dist, smem, st);
+  else
+    launch_rerank<false>(lpr, X, d, metric, Q, nq, n, cand, n_cand, stride, k, out_ids, out_dist, smem, st);
+  ANN_HIP(hipGetLastError());
+  return ANN_OK;
+}
+
+}  // namespace ann
+
+using namespace ann;
+
+extern "C" {
+
+ann_status ann_rerank(ann_index *index, const float *q, uint32_t nq, const uint32_t *cand_ids, uint32_t n_cand,
+                      uint32_t cand_stride, uint32_t k, uint32_t *out_ids, float *out_dist, void *stream) {
+  if (!index || !q || !cand_ids || !out_ids || !out_dist) return fail(ANN_EINVAL, "ann_rerank: NULL argument");
+  if (!index->vectors) return fail(ANN_EINVAL, "ann_rerank: the index was uploaded without fp32 vectors");
+  if (nq == 0 || n_cand == 0 || k == 0) return fail(ANN_EINVAL, "ann_rerank: nq, n_cand and k must be positive");
+  if (k > n_cand) return fail(ANN_EINVAL, "ann_rerank: k = %u > n_cand = %u", k, n_cand);
+  if (cand_stride < n_cand) return fail(ANN_EINVAL, "ann_rerank: cand_stride = %u < n_cand = %u", cand_stride, n_cand);
+  if (n_cand > 4096) return fail(ANN_ECAPACITY, "ann_rerank: n_cand = %u exceeds 4096", n_cand);
+  return rerank_device(index->vectors, index->n, index->d, index->metric, q, nq, cand_ids, n_cand, cand_stride, k,
+                       out_ids, out_dist, (hipStream_t)stream);
+}
+
+ann_status ann_rescore(ann_index *index, uint32_t level, const float *q, uint32_t nq, const uint32_t *cand_ids,
+                       uint32_t n_cand, uint32_t cand_stride, uint32_t *out_ids, float *out_keys, int32_t *out_idot,
+                       void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  if (!index || !q || !cand_ids || !out_ids) return fail(ANN_EINVAL, "ann_rescore: NULL argument");
+  if (level >= index->n_levels) return fail(ANN_EINVAL, "ann_rescore: level %u not in the index", level);
+  if (nq == 0 || n_cand == 0) return fail(ANN_EINVAL, "ann_rescore: nq and n_cand must be positive");
+  if (cand_stride < n_cand) return fail(ANN_EINVAL, "ann_rescore: cand_stride = %u < n_cand = %u", cand_stride, n_cand);
+  if (n_cand > 4096) return fail(ANN_ECAPACITY, "ann_rescore: n_cand = %u exceeds 4096", n_cand);
+  ann_status rc = launch_query_prep(index, level, q, nq, nullptr, nullptr, nullptr, st);
+  if (rc != ANN_OK) return rc;
+  const LevelDev &L = index->level[level];
+  const Workspace &w = index->ws[level];
+  const float *norm = index->metric == ANN_L2 ? L.norm_term : nullptr;
+  const size_t smem = (size_t)n_cand * (sizeof(uint64_t) + sizeof(int32_t));
+#define ANN_RS(B, P)                                                                                              \
+  rescore_kernel<B, P><<<nq, 64, smem, st>>>(L.codes, L.row_stride, L.row_stride / 16, norm, index->metric,       \
+                                             index->n, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t, nq, cand_ids,     \
+                                             n_cand, cand_stride, out_ids, out_keys, out_idot)
+  if (L.bits == 8) {
+    switch (L.lanes_per_row) {
+      case 8: ANN_RS(8, 8); break;
+      case 16: ANN_RS(8, 16); break;
+      case 32: ANN_RS(8, 32); break;
+      default: ANN_RS(8, 64); break;
+    }
+  } else {
+    switch (L.lanes_per_row) {
+      case 8: ANN_RS(4, 8); break;
+      case 16: ANN_RS(4, 16); break;
+      case 32: ANN_RS(4, 32); break;
+      default: ANN_RS(4, 64); break;
+    }
+  }
+#undef ANN_RS
+  ANN_HIP(hipGetLastError());
+  return ANN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,203 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Integer and index work must match bit for bit."""
+import numpy as np
+import pytest
+
+import inputs
+import oracle
+from conftest import small_case
+
+pytestmark = pytest.mark.gpu
+PAD = 0xFFFFFFFF
+
+
+@pytest.fixture(scope="module")
+def H():
+    import gpu_harness
+    return gpu_harness
+
+
+def metric_id(name):
+    return oracle.L2 if name == "l2" else oracle.IP
+
+
+def assert_search_equal(gpu, orc, check_counts=True):
+    gi, gk, gd, gc = gpu
+    oi, ok, od, oc = orc
+    assert (gi == oi).all(), f"ids differ at {np.argwhere(gi != oi)[:5]}"
+    assert (gk.view(np.uint32) == ok.view(np.uint32)).all(), "keys differ bitwise"
+    if gd is not None:
+        assert (gd == od).all(), "integer dot products differ"
+    assert (gc[:, 0] == oc[:, 0]).all() and (gc[:, 2] == oc[:, 2]).all()
+    if check_counts:
+        assert (gc[:, 3] == 0).all()
+        assert (gc[:, 1] == oc[:, 1]).all()
+
+
+@pytest.mark.parametrize("n,d,bits", [(3000, 128, 8), (1000, 960, 4), (2500, 96, 8), (777, 100, 8), (513, 30, 4),
+                                      (1, 8, 8)])
+def test_sq_train_encode_bitwise(H, n, d, bits):
+    w = inputs.Workload("sq", n, d, 7, 0.3, 1, seed=n + d, aniso_sigma=0.5)
+    X = inputs.base_vectors(w)
+    if n > 10:
+        X[:, 1] = 0.25                          # empty range
+    lv = oracle.sq_fit(X, bits)
+    lo, delta, codes, norm = H.gpu_sq_fit(X, bits)
+    assert (lo.view(np.uint32) == lv.lo.view(np.uint32)).all()
+    assert (delta.view(np.uint32) == lv.delta.view(np.uint32)).all()
+    assert (codes == lv.codes).all()
+    assert (norm.view(np.uint32) == lv.norm_term.view(np.uint32)).all()
+
+
+@pytest.mark.parametrize("d,bits", [(128, 8), (960, 4), (96, 8), (100, 8), (30, 4), (768, 8)])
+def test_query_prep_bitwise(H, d, bits):
+    w, X, Q, adj = small_case(400, d, 8, 33, seed=d + bits, bits=bits)
+    Q[3] = 0.0                                  # all-zero query: s = 1, t = 0
+    lv = oracle.sq_fit(X, bits)
+    ix = H.GpuIndex(X, adj, 0, [lv], oracle.L2)
+    t, s, qlo = ix.query_prep(Q)
+    for qi in range(len(Q)):
+        ot, os_, oq = oracle.query_prep(Q[qi], lv.lo, lv.delta)
+        assert (t[qi] == ot).all()
+        assert s[qi].view(np.uint32) == os_.view(np.uint32)
+        assert qlo[qi].view(np.uint32) == oq.view(np.uint32)
+    ix.close()
+
+
+def test_c1_search_bit_exact(H, c1):
+    """Config 1: 10k x 128, SQ8, R=32, L2, ef=64, one expansion per step."""
+    w, X, Q, adj, entry, lv = (c1[k] for k in ("w", "X", "Q", "adj", "entry", "level"))
+    ix = H.GpuIndex(X, adj, entry, [lv], oracle.L2)
+    for ef in (64, 10, 200):
+        orc = oracle.search_batch(lv, w.d, adj, entry, Q, ef)
+        gpu = ix.search(Q, ef)
+        assert_search_equal(gpu, orc)
+    again = ix.search(Q, 64)
+    first = ix.search(Q, 64)
+    assert all((a == b).all() for a, b in zip(again, first))
+    # end to end with the library's own encoder and rerank
+    lo, delta, codes, norm = H.gpu_sq_fit(X, 8)
+    ix2 = H.GpuIndex(X, adj, entry, [oracle.SQLevel(8, lo, delta, codes, norm)], oracle.L2)
+    orc = oracle.search_batch(lv, w.d, adj, entry, Q, 64)
+    gpu = ix2.search(Q, 64)
+    assert_search_equal(gpu, orc)
+    rid, rdist = ix2.rerank(Q, gpu[0], 2 * w.k, w.k)
+    oid, odist = oracle.rerank_batch(X, Q, orc[0][:, :2 * w.k], w.k)
+    H.check_rerank(rid, rdist, oid, odist)
+    gt, _ = oracle.bruteforce_topk(X, Q, w.k)
+    assert oracle.recall(rid, gt) == oracle.recall(oid, gt) >= 0.97
+    ix.close()
+    ix2.close()
+
+
+CASES = [
+    # n, d, R, nq, metric, bits, ef list
+    (2000, 128, 32, 40, "l2", 8, (1, 32, 100, 256)),
+    (1500, 960, 32, 12, "l2", 4, (64, 128)),
+    (3000, 96, 32, 30, "ip", 8, (64, 128)),
+    (1200, 768, 48, 10, "ip", 4, (128, 512)),
+    (1200, 768, 48, 10, "ip", 8, (100,)),
+    (900, 100, 20, 20, "l2", 8, (48,)),
+    (700, 30, 7, 20, "l2", 4, (16, 65)),
+    (600, 256, 64, 10, "l2", 8, (300,)),
+    (5, 16, 3, 4, "l2", 8, (8,)),
+    (1, 16, 2, 3, "ip", 8, (4,)),
+]
+
+
+@pytest.mark.parametrize("n,d,R,nq,metric,bits,efs", CASES)
+def test_search_bit_exact_small_cases(H, n, d, R, nq, metric, bits, efs):
+    """Ragged dimensions, both code widths, both metrics, padded adjacency rows,
+    ef below / above n, degrees up to the maximum."""
+    w, X, Q, adj = small_case(n, d, R, nq, seed=n + d + R, metric=metric, bits=bits, normalize=(metric == "ip"))
+    m = metric_id(metric)
+    lv = oracle.sq_fit(X, bits)
+    ix = H.GpuIndex(X, adj, 0, [lv], m)
+    for ef in efs:
+        orc = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m)
+        gpu = ix.search(Q, ef)
+        assert_search_equal(gpu, orc)
+    ix.close()
+
+
+def test_search_with_per_query_entries_and_csr_upload(H):
+    n, d, R, nq = 2000, 64, 16, 25
+    w, X, Q, adj = small_case(n, d, R, nq, seed=77)
+    lv = oracle.sq_fit(X, 8)
+    rng = np.random.default_rng(5)
+    entries = rng.integers(0, n, size=(nq, 9)).astype(np.uint32)
+    entries[:, 4] = entries[:, 1]               # duplicates
+    entries[::3, 7] = PAD                       # padding
+    offsets = np.zeros(n + 1, np.uint64)
+    cols = []
+    for i in range(n):
+        row = adj[i][adj[i] != PAD]
+        cols.extend(row.tolist())
+        offsets[i + 1] = len(cols)
+    cols = np.array(cols, np.uint32)
+    for host in (False, True):
+        ix = H.GpuIndex(X, adj, 3, [lv], oracle.L2, csr=(offsets, cols, R), host_pointers=host)
+        orc = oracle.search_batch(lv, d, adj, 3, Q, 40, entries=entries)
+        gpu = ix.search(Q, 40, entries=entries)
+        assert_search_equal(gpu, orc)
+        orc = oracle.search_batch(lv, d, adj, 3, Q, 40)
+        gpu = ix.search(Q, 40)
+        assert_search_equal(gpu, orc)
+        ix.close()
+
+
+def test_small_visited_table_rebuilds_without_changing_results(H, c1):
+    """The visited table is an efficiency knob (like the paper's environment
+    parameters): a table too small to hold every visited node is rebuilt from
+    the pool, distances get re-evaluated, the pool stays identical."""
+    w, X, Q, adj, entry, lv = (c1[k] for k in ("w", "X", "Q", "adj", "entry", "level"))
+    ix = H.GpuIndex(X, adj, entry, [lv], oracle.L2)
+    orc = oracle.search_batch(lv, w.d, adj, entry, Q, 32)
+    gpu = ix.search(Q, 32, visited_slots=256)
+    assert_search_equal(gpu, orc, check_counts=False)
+    assert gpu[3][:, 3].max() >= 1              # rebuilds happened
+    assert (gpu[3][:, 1] >= orc[3][:, 1]).all()  # never fewer evaluations than the oracle
+    big = ix.search(Q, 32, visited_slots=8192)
+    assert_search_equal(big, orc)
+    ix.close()
+
+
+@pytest.mark.parametrize("metric", ["l2", "ip"])
+def test_rerank_and_rescore(H, metric):
+    n, d, R, nq = 3000, 768, 48, 16
+    w, X, Q, adj = small_case(n, d, R, nq, seed=91, metric=metric, bits=4, normalize=(metric == "ip"))
+    m = metric_id(metric)
+    l4, l8 = oracle.sq_fit(X, 4), oracle.sq_fit(X, 8)
+    ix = H.GpuIndex(X, adj, 0, [l4, l8], m)
+    ef, k = 128, 100
+    orc = oracle.search_batch(l4, d, adj, 0, Q, ef, metric=m)
+    gpu = ix.search(Q, ef)
+    assert_search_equal(gpu, orc)
+    oid, okeys, odots = oracle.rescore_batch(l8, d, Q, orc[0], metric=m)
+    gid, gkeys, gdots = ix.rescore(Q, gpu[0], level=1)
+    assert (gid == oid).all() and (gdots == odots).all()
+    assert (gkeys.view(np.uint32) == okeys.view(np.uint32)).all()
+    rid, rdist = ix.rerank(Q, gid, ef, k)
+    roid, rodist = oracle.rerank_batch(X, Q, oid, k, metric=m)
+    H.check_rerank(rid, rdist, roid, rodist)
+    # prefix shorter than the row stride, with padding inside the prefix
+    cand = oid.copy()
+    cand[:, 5] = PAD
+    rid, rdist = ix.rerank(Q, cand, 20, 10)
+    roid, rodist = oracle.rerank_batch(X, Q, cand[:, :20], 10, metric=m)
+    H.check_rerank(rid, rdist, roid, rodist)
+    ix.close()
+
+
+@pytest.mark.parametrize("n,d,nq,k,metric", [(4000, 64, 70, 10, "l2"), (3001, 128, 33, 10, "ip"),
+                                              (2500, 100, 5, 100, "l2"), (130, 960, 40, 10, "l2"),
+                                              (50, 16, 3, 64, "ip")])
+def test_bruteforce_matches_fp64_exhaustive_search(H, n, d, nq, k, metric):
+    w = inputs.Workload("bf", n, d, 9, 0.3, nq, seed=n + d, normalize=(metric == "ip"))
+    X, Q = inputs.base_vectors(w), inputs.queries(w)
+    m = metric_id(metric)
+    gid, gdist = H.gpu_bruteforce(X, Q, k, m)
+    oid, odist = oracle.bruteforce_topk(X, Q, min(k, n), metric=m)
+    kk = min(k, n)
+    H.check_rerank(gid[:, :kk], gdist[:, :kk], oid, odist.astype(np.float32), rel=1e-6)
+    assert (gid[:, kk:] == PAD).all() and np.isinf(gdist[:, kk:]).all()
