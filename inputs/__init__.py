@@ -137,7 +137,7 @@ def medoid(X: np.ndarray) -> int:
     return int(_load().inp_medoid(_f32p(X), X.shape[0], X.shape[1], n_threads()))
 
 
-def build_graph(X: np.ndarray, degree: int, ef_c: int = 128, entry: int | None = None, backfill: bool = True,
+def build_graph(X: np.ndarray, degree: int, ef_c: int = 128, entry: int | None = None, backfill: bool = False,
                 max_batch: int = 2048) -> tuple[np.ndarray, int]:
     """Return (adjacency [n][degree] uint32 with 0xFFFFFFFF padding, entry point)."""
     X = np.ascontiguousarray(X, dtype=np.float32)
@@ -164,7 +164,7 @@ def cache_dir() -> Path:
 def graph(w: Workload, X: np.ndarray | None = None, use_cache: bool = True) -> tuple[np.ndarray, int]:
     """Graph + entry point of a workload, cached on disk by its parameters."""
     key = f"{w.n}_{w.d}_{w.n_clusters}_{w.sigma}_{w.aniso_sigma}_{w.noise_frac}_{int(w.normalize)}_{w.seed}_" \
-          f"{w.degree}_{w.ef_c}_v1"
+          f"{w.degree}_{w.ef_c}_nobackfill_v2"
     tag = hashlib.sha1((key + hashlib.sha1(_SRC.read_bytes()).hexdigest()).encode()).hexdigest()[:16]
     path = cache_dir() / f"graph_{w.name.replace('@', '_')}_{tag}.npz"
     if use_cache and path.exists():
