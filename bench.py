@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--nq", type=int, default=0)
     ap.add_argument("--ef", type=int, default=0, help="skip the sweep and use this ef")
     ap.add_argument("--mode", type=int, default=-1, help="0 exact, 1 multi-expansion; -1: fastest that meets recall")
+    ap.add_argument("--visited-slots", type=int, default=0, help="LDS visited-table slots (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -111,7 +112,8 @@ def main():
     out_dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
 
     def run_step(ef, mode, pool, counts=None):
-        ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=mode, out_ids=pool, out_counts=counts, stream=st)
+        ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=mode, out_ids=pool, out_counts=counts,
+                             visited_slots=args.visited_slots, stream=st)
         ann.ann_rerank(index, qd, nq, pool, min(n_rerank, ef), ef, k, out_ids, out_dist, st)
 
     # recall sweep
@@ -168,7 +170,8 @@ def main():
     t_wall = time.perf_counter()
     for i in range(args.steps):
         e_begin[i].record()
-        ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=mode, out_ids=pool, stream=st)
+        ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=mode, out_ids=pool,
+                             visited_slots=args.visited_slots, stream=st)
         e_mid[i].record()
         ann.ann_rerank(index, qd, nq, pool, min(n_rerank, ef), ef, k, out_ids, out_dist, st)
     e_end.record()

@@ -104,7 +104,8 @@ typedef struct {
  *                    execution of Algorithm 1 with (key, id) tie-breaking;
  *                 1: several expansions per step (faster, approximate order of
  *                    expansion; same pool/visited semantics).
- *   expansions_per_step   mode 1 only, 1..8 (0 = library default).
+ *   expansions_per_step   mode 1 only, 1..4 (0 = library default, 4): the closest
+ *                 un-expanded entries expanded together in one step.
  *   visited_slots number of slots of the per-query visited hash table in LDS,
  *                 a power of two, 0 = chosen from ef and degree.  When the
  *                 table fills it is rebuilt from the current pool; this costs

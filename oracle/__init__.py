@@ -48,7 +48,7 @@ def _load():
         lib.orc_key.argtypes = [_i32, _f32, _f32, _i32, _f32]
         lib.orc_key.restype = _f32
         lib.orc_search_batch.argtypes = [_i64, _i32, _i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _u32p, _u32,
-                                         _f32p, _i32, _u32p, _i32, _i32, _f32p, _f32, _i32, _u32p, _f32p, _i32p, _u32p]
+                                         _f32p, _i32, _u32p, _i32, _i32, _f32p, _f32, _i32, _i32, _u32p, _f32p, _i32p, _u32p]
         lib.orc_rescore_batch.argtypes = [_i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _f32p, _i32, _u32p, _i32,
                                           _u32p, _f32p, _i32p]
         lib.orc_rerank_batch.argtypes = [_f32p, _i32, _i32, _f32p, _i32, _u32p, _i32, _i32, _u32p, _f32p]
@@ -132,7 +132,7 @@ def key(metric, s, qlo, idot_value, norm_term) -> np.float32:
 
 
 def search_batch(level: SQLevel, d, adjacency, entry_point, Q, ef, metric=L2, entries=None, labels=None,
-                 alpha_s=float("inf"), m_s=0):
+                 alpha_s=float("inf"), m_s=0, expansions_per_step=1):
     """Algorithm 1 per query.  Returns (ids, keys, idot, counts), pools padded to ef."""
     adjacency, Q = _c(adjacency, np.uint32), _c(Q, np.float32)
     n, degree = adjacency.shape
@@ -150,7 +150,7 @@ def search_batch(level: SQLevel, d, adjacency, entry_point, Q, ef, metric=L2, en
     _load().orc_search_batch(n, d, degree, metric, level.bits, _p(level.codes, _u8p), _p(level.lo, _f32p),
                              _p(level.delta, _f32p), _p(level.norm_term, _f32p), _p(adjacency, _u32p),
                              int(entry_point), _p(Q, _f32p), nq, _p(entries, _u32p), n_entry, ef, _p(labels, _f32p),
-                             float(alpha_s), int(m_s), _p(ids, _u32p),
+                             float(alpha_s), int(m_s), int(expansions_per_step), _p(ids, _u32p),
                              _p(keys, _f32p), _p(dots, _i32p), _p(counts, _u32p))
     return ids, keys, dots, counts
 

@@ -175,6 +175,11 @@ float orc_key(int32_t metric, float s, float qlo, int32_t idot, float norm_term)
 //   labels: NULL -> every edge passes; otherwise [n][degree] edge labels, an
 //            edge is usable when label <= alpha_s (Section 4.3).
 //   m_s:    at most m_s neighbours are taken per expansion (<= 0: no cap).
+//   expansions_per_step: 1 is Algorithm 1.  P > 1 is the batched variant used
+//            by the GPU's fast mode (not in the paper): each step takes the P
+//            closest un-expanded pool entries, marks them expanded, collects
+//            their unvisited neighbours (entries in pool order, rows in stored
+//            order) and only then evaluates and inserts them.
 //   entries: NULL -> every query starts from `entry_point`; otherwise
 //            [nq][n_entry] per-query initial nodes I (duplicates skipped).
 //   out_ids/out_keys/out_idot: [nq][ef], final pool in (key, id) order, padded
@@ -183,7 +188,8 @@ float orc_key(int32_t metric, float s, float qlo, int32_t idot, float norm_term)
 void orc_search_batch(int64_t n, int32_t d, int32_t degree, int32_t metric, int32_t bits, const uint8_t *codes,
                       const float *lo, const float *delta, const float *norm_term, const uint32_t *adjacency,
                       uint32_t entry_point, const float *Q, int32_t nq, const uint32_t *entries, int32_t n_entry,
-                      int32_t ef, const float *labels, float alpha_s, int32_t m_s, uint32_t *out_ids,
+                      int32_t ef, const float *labels, float alpha_s, int32_t m_s, int32_t expansions_per_step,
+                      uint32_t *out_ids,
                       float *out_keys, int32_t *out_idot, uint32_t *out_counts) {
   const int rb = row_bytes(d, bits);
   if (m_s <= 0) m_s = degree;
@@ -219,27 +225,30 @@ void orc_search_batch(int64_t n, int32_t d, int32_t degree, int32_t metric, int3
       evaluate_and_insert(v);
     }
 
+    const int P = expansions_per_step > 1 ? expansions_per_step : 1;
     for (;;) {
-      // closest un-expanded pool entry
-      int u = -1;
-      for (size_t p = 0; p < pool.size(); ++p)
+      // the P closest un-expanded pool entries (P = 1: the closest)
+      std::vector<uint32_t> expand;
+      for (size_t p = 0; p < pool.size() && (int)expand.size() < P; ++p)
         if (!pool[p].expanded) {
-          u = (int)p;
-          break;
+          pool[p].expanded = true;
+          expand.push_back(pool[p].id);
         }
-      if (u < 0) break;
-      pool[u].expanded = true;
-      ++n_exp;
-      const uint32_t uid = pool[u].id;
+      if (expand.empty()) break;
+      n_exp += (uint32_t)expand.size();
       // first pass over ids only: collect the unvisited neighbours N and mark them
       std::vector<uint32_t> N;
-      for (int slot = 0; slot < degree; ++slot) {
-        uint32_t v = adjacency[(int64_t)uid * degree + slot];
-        if (v == kPad || visited[v]) continue;
-        if (labels && !(labels[(int64_t)uid * degree + slot] <= alpha_s)) continue;
-        if (!((int)N.size() < m_s)) continue;
-        visited[v] = 1;
-        N.push_back(v);
+      for (uint32_t uid : expand) {
+        int taken = 0;
+        for (int slot = 0; slot < degree; ++slot) {
+          uint32_t v = adjacency[(int64_t)uid * degree + slot];
+          if (v == kPad || visited[v]) continue;
+          if (labels && !(labels[(int64_t)uid * degree + slot] <= alpha_s)) continue;
+          if (!(taken < m_s)) continue;
+          visited[v] = 1;
+          N.push_back(v);
+          ++taken;
+        }
       }
       // second pass: touch the vectors of N only
       for (uint32_t v : N) evaluate_and_insert(v);

@@ -2,9 +2,9 @@
 // Access Greedy Search"), one query per wavefront.
 //
 // Mapping of the algorithm's steps onto a 64-lane wavefront:
-//   pool C          sorted array of (key, id) pairs spread over the lanes'
-//                   registers (lane l holds entries l*M .. l*M+M-1); the
-//                   "expanded" mark is bit 31 of the id.
+//   pool C          sorted array of (key, id) pairs in registers, striped:
+//                   entry i lives in register i/64 of lane i%64.  The low word
+//                   is (id << 1) | expanded, so pairs compare as plain u64.
 //   visited set V   open-addressing hash table in LDS, test-and-set by CAS.
 //   for j in G_i    one lane per adjacency slot: all ids of the row are
 //                   tested against V first, survivors are compacted (the
@@ -12,19 +12,22 @@
 //                   rows are fetched.
 //   tau_l           LPR lanes share one code row, 16 bytes per lane; packed
 //                   int8 dot products, reduced across the lanes with DPP.
-//   insert          candidates are inserted one at a time, each by a
-//                   wave-wide compare and a one-position shift.
+//   insert          all candidates of a step that beat the pool's last entry
+//                   are merged at once: every pool entry counts the candidates
+//                   below it, every candidate counts the pool entries and
+//                   candidates below it, and both scatter to their final
+//                   positions through LDS.
 // The pool after a step is the ef smallest (key, id) pairs among the old pool
-// and the row's new candidates, which is what sequential insertion in row
-// order gives; so results equal a sequential execution bit for bit.
+// and the step's new candidates, which is what sequential insertion in row
+// order gives; so with one expansion per step results equal a sequential
+// execution bit for bit.  With P > 1 expansions per step the P closest
+// un-expanded entries are expanded together (rows filtered in that order).
 #include "ann_internal.hpp"
 #include "device_utils.hpp"
 
 namespace ann {
 
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
-constexpr uint32_t kFlag = 0x80000000u;
-constexpr uint32_t kIdMask = 0x7FFFFFFFu;
 
 struct SearchArgs {
   const uint8_t *codes;
@@ -40,36 +43,50 @@ struct SearchArgs {
   int32_t *out_idot;
   uint32_t *out_counts;
   uint64_t n;
-  uint32_t row_stride, n_chunks, degree, metric, tq_stride, n_entry, entry_point, ef, vis_log2, nq;
+  uint32_t row_stride, n_chunks, degree, metric, tq_stride, n_entry, entry_point, ef, vis_log2, nq, p;
 };
 
 __device__ __forceinline__ uint64_t pack64(uint32_t hi, uint32_t lo) { return ((uint64_t)hi << 32) | lo; }
 
-template <int BITS, int LPR, int M>
+__device__ __forceinline__ int lanes_below(uint64_t mask) {
+  return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+
+// LDS bytes for one query: merge buffer, qualifying-candidate buffer, visited
+// table, candidate ids.
+__host__ __device__ inline size_t search_smem_bytes(int m, int pmax, uint32_t vis_log2) {
+  return (size_t)(64 * m + 64) * 8 + (size_t)(64 * pmax) * 8 + ((size_t)1 << vis_log2) * 4 + (size_t)(64 * pmax) * 4;
+}
+
+template <int BITS, int LPR, int M, int PMAX>
 struct SearchWave {
   static constexpr int G = kWave / LPR;  // code rows evaluated side by side
   static constexpr int U = 4;            // row loads in flight per lane
   static constexpr int TQW = TqRegs<BITS>::kWords;
 
   const SearchArgs &a;
+  uint64_t *mbuf;  // LDS [64*M + 64] merge scatter buffer
+  uint64_t *qbuf;  // LDS [64*PMAX] candidates that beat the pool's last entry
   uint32_t *vis;   // LDS [cap]
-  uint32_t *cand;  // LDS [64]
+  uint32_t *cand;  // LDS [64*PMAX] unvisited neighbour ids of this step
   int lane, chunk, grp;
   uint32_t vis_mask, vis_shift, vis_limit;
   int tq[TQW];
   float s, qlo;
   int bias;
-  uint32_t pk[M], pid[M];  // pool: ordered key bits, id | expanded flag
-  uint64_t worst;          // (key,id) of pool entry ef-1
+  uint32_t pk[M], pv[M];  // pool: ordered key bits; (id << 1) | expanded
+  uint64_t worst;         // pool entry ef-1 (all ones while the pool is not full)
   uint32_t n_exp = 0, n_dist = 0, n_vis = 0, n_rebuild = 0;
 
-  __device__ SearchWave(const SearchArgs &args, uint32_t *smem) : a(args) {
+  __device__ SearchWave(const SearchArgs &args, uint64_t *smem) : a(args) {
     lane = lane_id();
     chunk = lane % LPR;
     grp = lane / LPR;
     const uint32_t cap = 1u << a.vis_log2;
-    vis = smem;
-    cand = smem + cap;
+    mbuf = smem;
+    qbuf = mbuf + (64 * M + 64);
+    vis = reinterpret_cast<uint32_t *>(qbuf + 64 * PMAX);
+    cand = vis + cap;
     vis_mask = cap - 1;
     vis_shift = 32 - a.vis_log2;
     vis_limit = cap - cap / 4;
@@ -103,7 +120,7 @@ struct SearchWave {
 #pragma unroll
     for (int r = 0; r < M; ++r)
       if (pk[r] != kEmpty) {
-        test_and_set(pid[r] & kIdMask);
+        test_and_set(pv[r] >> 1);
         ++kept;
       }
     n_vis = (uint32_t)group_sum_i32<64>(kept);
@@ -112,101 +129,113 @@ struct SearchWave {
   }
 
   __device__ __forceinline__ void refresh_worst() {
-    const int g = (int)a.ef - 1, rl = g / M, rr = g % M;
-    uint32_t k_ = pk[0], i_ = pid[0];
+    const int g = (int)a.ef - 1, rr = g / kWave, rl = g % kWave;
+    uint32_t k_ = pk[0], v_ = pv[0];
 #pragma unroll
     for (int r = 1; r < M; ++r) {
       k_ = (rr == r) ? pk[r] : k_;
-      i_ = (rr == r) ? pid[r] : i_;
+      v_ = (rr == r) ? pv[r] : v_;
     }
-    worst = pack64(__builtin_amdgcn_readlane(k_, rl), __builtin_amdgcn_readlane(i_, rl) & kIdMask);
+    worst = pack64(__builtin_amdgcn_readlane(k_, rl), __builtin_amdgcn_readlane(v_, rl));
   }
 
-  // Insert (cku, cid), known to be smaller than `worst`; all arguments are
-  // wave-uniform.
-  __device__ __forceinline__ void insert(uint32_t cku, uint32_t cid) {
-    const uint64_t c64 = pack64(cku, cid);
-    int cnt = 0;
+  // Merge up to 64 candidates (one per lane where `have`) into the pool.
+  __device__ __forceinline__ void merge(bool have, uint32_t ck, uint32_t cv) {
+    const uint64_t c64 = pack64(ck, cv);
+    const bool mine = have && c64 < worst;
+    const uint64_t qm = __ballot(mine);
+    if (qm == 0) return;
+    uint64_t e[M];
+    int shift[M];
 #pragma unroll
-    for (int r = 0; r < M; ++r) cnt += (pack64(pk[r], pid[r] & kIdMask) < c64) ? 1 : 0;
-    const uint64_t open = __ballot(cnt < M);  // lanes that hold an entry >= candidate
-    const int L = __builtin_ctzll(open);
-    const int p = L * M + __builtin_amdgcn_readlane(cnt, L);
-    const uint32_t upk = (uint32_t)dpp_i32<kDppWaveShr1>((int)pk[M - 1]);
-    const uint32_t upid = (uint32_t)dpp_i32<kDppWaveShr1>((int)pid[M - 1]);
-#pragma unroll
-    for (int r = M - 1; r >= 0; --r) {
-      const int g = lane * M + r;
-      const uint32_t sk = r > 0 ? pk[r > 0 ? r - 1 : 0] : upk;
-      const uint32_t si = r > 0 ? pid[r > 0 ? r - 1 : 0] : upid;
-      uint32_t nk = g > p ? sk : pk[r];
-      uint32_t ni = g > p ? si : pid[r];
-      nk = g == p ? cku : nk;
-      ni = g == p ? cid : ni;
-      const bool beyond = g >= (int)a.ef;  // the entry pushed past ef is dropped
-      pk[r] = beyond ? kEmpty : nk;
-      pid[r] = beyond ? kEmpty : ni;
+    for (int r = 0; r < M; ++r) {
+      e[r] = pack64(pk[r], pv[r]);
+      shift[r] = 0;
     }
+    int below_c = 0, below_p = 0;  // candidates / pool entries smaller than this lane's candidate
+    for (uint64_t m = qm; m; m &= m - 1) {
+      const int l = __builtin_ctzll(m);
+      const uint64_t s64 = pack64(__builtin_amdgcn_readlane(ck, l), __builtin_amdgcn_readlane(cv, l));
+      int rank = 0;
+#pragma unroll
+      for (int r = 0; r < M; ++r) {
+        const bool lt = e[r] < s64;
+        rank += __popcll(__ballot(lt));
+        shift[r] += lt ? 0 : 1;
+      }
+      below_c += s64 < c64 ? 1 : 0;
+      below_p = lane == l ? rank : below_p;
+    }
+#pragma unroll
+    for (int r = 0; r < M; ++r) mbuf[r * kWave + lane + shift[r]] = e[r];
+    if (mine) mbuf[below_p + below_c] = c64;
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < M; ++r) {
+      const uint64_t v = mbuf[r * kWave + lane];
+      const bool beyond = r * kWave + lane >= (int)a.ef;  // entries pushed past ef are dropped
+      pk[r] = beyond ? kEmpty : (uint32_t)(v >> 32);
+      pv[r] = beyond ? kEmpty : (uint32_t)v;
+    }
+    __syncthreads();
     refresh_worst();
   }
 
-  __device__ __forceinline__ void insert_candidates(bool have, uint32_t ku, uint32_t id) {
-    uint64_t m = __ballot(have && pack64(ku, id) < worst);
-    while (m) {
-      const int l = __builtin_ctzll(m);
-      m &= m - 1;
-      const uint32_t k_ = __builtin_amdgcn_readlane(ku, l), i_ = __builtin_amdgcn_readlane(id, l);
-      if (pack64(k_, i_) < worst) insert(k_, i_);
-    }
-  }
-
-  // Integer dot products for the code rows of up to G*U nodes listed in
-  // cand[base ..]; lane (grp, chunk 0) of each group gets the full sum.
-  __device__ __forceinline__ void row_dots(int base, int count, int (&dot)[U], float (&nrm)[U], uint32_t (&vid)[U]) {
-    uint4 rows[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int ci = base + u * G + grp;
-      vid[u] = ci < count ? cand[ci] : kEmpty;
-      rows[u] = make_uint4(0, 0, 0, 0);
-      nrm[u] = 0.0f;
-      if (vid[u] != kEmpty) {
-        if (chunk < (int)a.n_chunks)
-          rows[u] = *reinterpret_cast<const uint4 *>(a.codes + (uint64_t)vid[u] * a.row_stride + (uint32_t)chunk * 16u);
-        if (a.norm_term && chunk == 0) nrm[u] = a.norm_term[vid[u]];
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) dot[u] = group_sum_i32<LPR>(chunk_dot<BITS>(rows[u], tq)) + bias;
-  }
-
-  // Visited filter, compaction, distance evaluation and pool insertion for one
-  // list of node ids (an adjacency row or the initial nodes), one id per lane.
-  __device__ __forceinline__ void process_ids(uint32_t nb) {
-    bool valid = nb != kEmpty && nb < a.n;
-    const uint32_t incoming = (uint32_t)__popcll(__ballot(valid));
-    if (n_vis + incoming > vis_limit) rebuild_table();
+  // Visited filter and compaction for one list of node ids (one per lane):
+  // unvisited ids are marked and appended to cand[n_cand ..].
+  __device__ __forceinline__ void filter_ids(uint32_t nb, int &n_cand) {
+    const bool valid = nb != kEmpty && nb < a.n;
     const bool fresh = valid && test_and_set(nb);
     const uint64_t fm = __ballot(fresh);
-    const int count = __popcll(fm);
-    if (count == 0) return;
-    n_vis += count;
-    n_dist += count;
-    const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(fm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)fm, 0));
-    if (fresh) cand[rank] = nb;
+    if (fresh) cand[n_cand + lanes_below(fm)] = nb;
+    n_cand += __popcll(fm);
+  }
+
+  // tau_l for the n_cand nodes in cand[], then merge the ones that can enter
+  // the pool.
+  __device__ __forceinline__ void evaluate_and_merge(int n_cand) {
+    if (n_cand == 0) return;
+    n_vis += n_cand;
+    n_dist += n_cand;
     __syncthreads();
-    for (int base = 0; base < count; base += G * U) {
-      int dot[U];
+    int n_q = 0;
+    for (int base = 0; base < n_cand; base += G * U) {
+      uint4 rows[U];
       float nrm[U];
       uint32_t vid[U];
-      row_dots(base, count, dot, nrm, vid);
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const float key = key_from_idot(a.metric, s, qlo, dot[u], nrm[u]);
-        insert_candidates(chunk == 0 && vid[u] != kEmpty, order_u32(key), vid[u]);
+        if (base + u * G < n_cand) {
+          const int ci = base + u * G + grp;
+          vid[u] = ci < n_cand ? cand[ci] : kEmpty;
+          rows[u] = make_uint4(0, 0, 0, 0);
+          nrm[u] = 0.0f;
+          if (vid[u] != kEmpty) {
+            if (chunk < (int)a.n_chunks)
+              rows[u] = *reinterpret_cast<const uint4 *>(a.codes + (uint64_t)vid[u] * a.row_stride + (uint32_t)chunk * 16u);
+            if (a.norm_term && chunk == 0) nrm[u] = a.norm_term[vid[u]];
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (base + u * G < n_cand) {
+          const int dot = group_sum_i32<LPR>(chunk_dot<BITS>(rows[u], tq)) + bias;
+          const float key = key_from_idot(a.metric, s, qlo, dot, nrm[u]);
+          const uint64_t c64 = pack64(order_u32(key), vid[u] << 1);
+          const bool q = chunk == 0 && vid[u] != kEmpty && c64 < worst;
+          const uint64_t bm = __ballot(q);
+          if (q) qbuf[n_q + lanes_below(bm)] = c64;
+          n_q += __popcll(bm);
+        }
       }
     }
     __syncthreads();
+    for (int b = 0; b < n_q; b += kWave) {
+      const bool have = b + lane < n_q;
+      const uint64_t c = have ? qbuf[b + lane] : 0;
+      merge(have, (uint32_t)(c >> 32), (uint32_t)c);
+    }
   }
 
   __device__ void run(uint32_t qi) {
@@ -220,65 +249,101 @@ struct SearchWave {
 #pragma unroll
     for (int r = 0; r < M; ++r) {
       pk[r] = kEmpty;
-      pid[r] = kEmpty;
+      pv[r] = kEmpty;
     }
-    worst = pack64(kEmpty, kIdMask);
+    worst = ~0ull;
     clear_table();
     __syncthreads();
 
     // initial nodes I: into the pool and into V
-    uint32_t nb = kEmpty;
-    if (a.entry_ids) {
-      if (lane < (int)a.n_entry) nb = a.entry_ids[(uint64_t)qi * a.n_entry + lane];
-    } else if (lane == 0) {
-      nb = a.entry_point;
+    {
+      uint32_t nb = kEmpty;
+      if (a.entry_ids) {
+        if (lane < (int)a.n_entry) nb = a.entry_ids[(uint64_t)qi * a.n_entry + lane];
+      } else if (lane == 0) {
+        nb = a.entry_point;
+      }
+      int n_cand = 0;
+      filter_ids(nb, n_cand);
+      evaluate_and_merge(n_cand);
     }
-    process_ids(nb);
 
+    const int p = PMAX == 1 ? 1 : (int)a.p;
+    uint32_t pre_id = kEmpty, pre_row = kEmpty;  // adjacency row fetched ahead (PMAX == 1)
     for (;;) {
-      // closest un-expanded pool entry
-      int first = M;
+      // the p closest un-expanded pool entries; lane e of `picked` gets the e-th
+      uint32_t picked = kEmpty, next_id = kEmpty;
+      int got = 0;
 #pragma unroll
-      for (int r = M - 1; r >= 0; --r) first = (pid[r] & kFlag) ? first : r;
-      const uint64_t has = __ballot(first < M);
-      if (has == 0) break;
-      const int L = __builtin_ctzll(has);
-      const int rr = __builtin_amdgcn_readlane(first, L);
-      uint32_t sel = pid[0];
+      for (int r = 0; r < M; ++r) {
+        uint64_t um = __ballot((pv[r] & 1u) == 0);
+        while (um != 0 && got < p) {
+          const int L = __builtin_ctzll(um);
+          um &= um - 1;
+          picked = lane == got ? (uint32_t)__builtin_amdgcn_readlane(pv[r], L) >> 1 : picked;
+          pv[r] |= lane == L ? 1u : 0u;
+          ++got;
+        }
+        if (PMAX == 1 && got == p && next_id == kEmpty && um != 0)
+          next_id = __builtin_amdgcn_readlane(pv[r], __builtin_ctzll(um)) >> 1;
+      }
+      if (got == 0) break;
+      n_exp += got;
+      if (PMAX > 1 && n_vis + (uint32_t)(got * kWave) > vis_limit) rebuild_table();
+
+      uint32_t rows[PMAX];
 #pragma unroll
-      for (int r = 1; r < M; ++r) sel = (rr == r) ? pid[r] : sel;
-      const uint32_t uid = __builtin_amdgcn_readlane(sel, L);
+      for (int e = 0; e < PMAX; ++e) {
+        rows[e] = kEmpty;
+        if (e < got) {
+          const uint32_t uid = __builtin_amdgcn_readlane(picked, e);
+          if (PMAX == 1 && uid == pre_id)
+            rows[e] = pre_row;
+          else if (lane < (int)a.degree)
+            rows[e] = a.adjacency[(uint64_t)uid * a.degree + lane];
+        }
+      }
+      if (PMAX == 1) {
+        // fetch ahead the row of the entry that is expanded next unless a
+        // candidate of this step overtakes it
+        pre_id = next_id;
+        pre_row = kEmpty;
+        if (next_id != kEmpty && lane < (int)a.degree) pre_row = a.adjacency[(uint64_t)next_id * a.degree + lane];
+      }
+      int n_cand = 0;
 #pragma unroll
-      for (int r = 0; r < M; ++r)
-        if (lane == L && r == rr) pid[r] |= kFlag;
-      ++n_exp;
-      nb = lane < (int)a.degree ? a.adjacency[(uint64_t)uid * a.degree + lane] : kEmpty;
-      process_ids(nb);
+      for (int e = 0; e < PMAX; ++e) {
+        if (e < got) {
+          if (PMAX == 1) {
+            const uint32_t incoming = (uint32_t)__popcll(__ballot(rows[e] != kEmpty));
+            if (n_vis + incoming > vis_limit) rebuild_table();
+          }
+          filter_ids(rows[e], n_cand);
+        }
+      }
+      evaluate_and_merge(n_cand);
     }
 
-    // results: stage the pool through LDS (the visited table is dead now) so
-    // that global writes are coalesced
-    __syncthreads();
-    uint32_t *st_id = vis, *st_key = vis + a.ef;
+    // results (pool index r*64 + lane: coalesced)
     int kept = 0;
 #pragma unroll
     for (int r = 0; r < M; ++r) {
-      const int g = lane * M + r;
-      if (g < (int)a.ef) {
-        st_id[g] = pk[r] == kEmpty ? kEmpty : (pid[r] & kIdMask);
-        st_key[g] = pk[r];
+      const uint32_t i = r * kWave + lane;
+      const bool live = pk[r] != kEmpty;
+      kept += __popcll(__ballot(live));
+      if (i < a.ef) {
+        a.out_ids[(uint64_t)qi * a.ef + i] = live ? (pv[r] >> 1) : kEmpty;
+        if (a.out_keys) a.out_keys[(uint64_t)qi * a.ef + i] = live ? unorder_f32(pk[r]) : INFINITY;
       }
-      kept += pk[r] != kEmpty ? 1 : 0;
-    }
-    kept = group_sum_i32<64>(kept);
-    __syncthreads();
-    for (uint32_t i = lane; i < a.ef; i += kWave) {
-      a.out_ids[(uint64_t)qi * a.ef + i] = st_id[i];
-      if (a.out_keys) a.out_keys[(uint64_t)qi * a.ef + i] = st_key[i] == kEmpty ? INFINITY : unorder_f32(st_key[i]);
     }
     if (a.out_idot) {
+      // same arithmetic as during traversal, over the final pool
+      __syncthreads();
+      uint32_t *st_id = reinterpret_cast<uint32_t *>(mbuf);
+#pragma unroll
+      for (int r = 0; r < M; ++r) st_id[r * kWave + lane] = pk[r] != kEmpty ? (pv[r] >> 1) : kEmpty;
+      __syncthreads();
       for (int base = 0; base < (int)a.ef; base += G * U) {
-        // same arithmetic as during traversal, over the final pool
         uint4 rows[U];
         uint32_t vid[U];
 #pragma unroll
@@ -307,38 +372,41 @@ struct SearchWave {
   }
 };
 
-template <int BITS, int LPR, int M>
-__global__ __launch_bounds__(64) void search_exact_kernel(SearchArgs args) {
-  extern __shared__ uint32_t smem[];
+template <int BITS, int LPR, int M, int PMAX>
+__global__ __launch_bounds__(64) void search_kernel(SearchArgs args) {
+  extern __shared__ uint64_t smem[];
   const uint32_t qi = blockIdx.x;
   if (qi >= args.nq) return;
-  SearchWave<BITS, LPR, M> w(args, smem);
+  SearchWave<BITS, LPR, M, PMAX> w(args, smem);
   w.run(qi);
 }
 
-template <int BITS, int LPR>
-static ann_status launch_m(const SearchArgs &args, int m, size_t smem, hipStream_t st) {
+template <int BITS, int LPR, int PMAX>
+static ann_status launch_m(const SearchArgs &args, int m, hipStream_t st) {
+  const size_t smem = search_smem_bytes(m, PMAX, args.vis_log2);
   switch (m) {
-    case 1: search_exact_kernel<BITS, LPR, 1><<<args.nq, 64, smem, st>>>(args); break;
-    case 2: search_exact_kernel<BITS, LPR, 2><<<args.nq, 64, smem, st>>>(args); break;
-    case 4: search_exact_kernel<BITS, LPR, 4><<<args.nq, 64, smem, st>>>(args); break;
-    case 8: search_exact_kernel<BITS, LPR, 8><<<args.nq, 64, smem, st>>>(args); break;
+    case 1: search_kernel<BITS, LPR, 1, PMAX><<<args.nq, 64, smem, st>>>(args); break;
+    case 2: search_kernel<BITS, LPR, 2, PMAX><<<args.nq, 64, smem, st>>>(args); break;
+    case 4: search_kernel<BITS, LPR, 4, PMAX><<<args.nq, 64, smem, st>>>(args); break;
+    case 8: search_kernel<BITS, LPR, 8, PMAX><<<args.nq, 64, smem, st>>>(args); break;
     default: return fail(ANN_EUNSUPPORTED, "no kernel for pool registers per lane = %d", m);
   }
   ANN_HIP(hipGetLastError());
   return ANN_OK;
 }
 
-template <int BITS>
-static ann_status launch_lpr(const SearchArgs &args, uint32_t lpr, int m, size_t smem, hipStream_t st) {
+template <int BITS, int PMAX>
+static ann_status launch_lpr(const SearchArgs &args, uint32_t lpr, int m, hipStream_t st) {
   switch (lpr) {
-    case 8: return launch_m<BITS, 8>(args, m, smem, st);
-    case 16: return launch_m<BITS, 16>(args, m, smem, st);
-    case 32: return launch_m<BITS, 32>(args, m, smem, st);
-    case 64: return launch_m<BITS, 64>(args, m, smem, st);
+    case 8: return launch_m<BITS, 8, PMAX>(args, m, st);
+    case 16: return launch_m<BITS, 16, PMAX>(args, m, st);
+    case 32: return launch_m<BITS, 32, PMAX>(args, m, st);
+    case 64: return launch_m<BITS, 64, PMAX>(args, m, st);
     default: return fail(ANN_EUNSUPPORTED, "no kernel for %u lanes per code row", lpr);
   }
 }
+
+constexpr int kMaxExpansionsPerStep = 4;
 
 }  // namespace ann
 
@@ -355,17 +423,20 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   if (params->ef > ANN_MAX_EF) return fail(ANN_ECAPACITY, "ann_search_batch: ef = %u exceeds ANN_MAX_EF = %u", params->ef, ANN_MAX_EF);
   if (params->reserved[0] || params->reserved[1] || params->reserved[2]) return fail(ANN_EINVAL, "ann_search_batch: reserved fields must be zero");
   if (params->mode > 1) return fail(ANN_EINVAL, "ann_search_batch: unknown mode %u", params->mode);
-  if (params->mode == 1) return fail(ANN_EUNSUPPORTED, "ann_search_batch: multi-expansion mode is not built yet");
+  if (params->mode == 0 && params->expansions_per_step > 1) return fail(ANN_EINVAL, "ann_search_batch: expansions_per_step needs mode 1");
+  if (params->expansions_per_step > (uint32_t)kMaxExpansionsPerStep) return fail(ANN_ECAPACITY, "ann_search_batch: expansions_per_step = %u exceeds %d", params->expansions_per_step, kMaxExpansionsPerStep);
+  const uint32_t p = params->mode == 0 ? 1u : (params->expansions_per_step ? params->expansions_per_step : (uint32_t)kMaxExpansionsPerStep);
   if (entry_ids && n_entry == 0) return fail(ANN_EINVAL, "ann_search_batch: entry_ids given with n_entry == 0");
   if (entry_ids && n_entry > ANN_MAX_ENTRIES) return fail(ANN_ECAPACITY, "ann_search_batch: n_entry = %u exceeds ANN_MAX_ENTRIES = %u", n_entry, ANN_MAX_ENTRIES);
 
   const uint32_t ef = params->ef;
-  uint32_t need = 2 * (ef + 64), min_log2 = 0;
+  uint32_t need = 2 * (ef + 64 * p), min_log2 = 0;
   while ((1u << min_log2) < need) ++min_log2;
   uint32_t vis_log2;
   if (params->visited_slots == 0) {
-    // default: room for the evaluations a search of this ef typically makes
-    uint32_t want = 16 * ef < 4096 ? 4096 : 16 * ef;
+    // default: a table small enough for many resident queries; rebuilds
+    // repeat some evaluations but never change results
+    uint32_t want = 8 * ef < 2048 ? 2048 : 8 * ef;
     vis_log2 = 0;
     while ((1u << vis_log2) < want) ++vis_log2;
     if (vis_log2 < min_log2) vis_log2 = min_log2;
@@ -407,8 +478,11 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   a.ef = ef;
   a.vis_log2 = vis_log2;
   a.nq = nq;
+  a.p = p;
   int m = 1;
   while (64 * m < (int)ef) m <<= 1;
-  const size_t smem = ((size_t)(1u << vis_log2) + 64) * sizeof(uint32_t);
-  return L.bits == 8 ? launch_lpr<8>(a, L.lanes_per_row, m, smem, st) : launch_lpr<4>(a, L.lanes_per_row, m, smem, st);
+  if (params->mode == 0)
+    return L.bits == 8 ? launch_lpr<8, 1>(a, L.lanes_per_row, m, st) : launch_lpr<4, 1>(a, L.lanes_per_row, m, st);
+  return L.bits == 8 ? launch_lpr<8, kMaxExpansionsPerStep>(a, L.lanes_per_row, m, st)
+                     : launch_lpr<4, kMaxExpansionsPerStep>(a, L.lanes_per_row, m, st);
 }

@@ -105,6 +105,7 @@ class GpuIndex:
         return t.cpu().numpy(), s.cpu().numpy(), qlo.cpu().numpy()
 
     def search(self, Q, ef, k=1, entries=None, want_idot=True, **kw):
+        kw.setdefault("visited_slots", 8192)      # large enough that evaluation counts equal the oracle's
         nq = Q.shape[0]
         qd = dev(Q)
         ids = torch.empty((nq, ef), dtype=torch.int32, device=DEV)

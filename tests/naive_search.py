@@ -4,7 +4,8 @@ the C++ oracle's control flow on tiny inputs.  It consumes precomputed keys, so
 it holds none of the distance arithmetic."""
 
 
-def naive_search(keys, adjacency, entries, ef, pad=0xFFFFFFFF, labels=None, alpha_s=float("inf"), m_s=None):
+def naive_search(keys, adjacency, entries, ef, pad=0xFFFFFFFF, labels=None, alpha_s=float("inf"), m_s=None,
+                 expansions_per_step=1):
     """keys[v] = traversal key of node v.  Returns (sorted pool [(key, id)], n_exp, n_dist)."""
     pool = {}            # id -> expanded?
     visited = set()
@@ -31,23 +32,25 @@ def naive_search(keys, adjacency, entries, ef, pad=0xFFFFFFFF, labels=None, alph
         visited.add(e)
         insert(e)
     while True:
-        todo = [v for v, done in pool.items() if not done]
+        todo = sorted((v for v, done in pool.items() if not done), key=order)[:expansions_per_step]
         if not todo:
             break
-        u = min(todo, key=order)
-        pool[u] = True
-        n_exp += 1
         batch = []
-        for slot in range(degree):
-            v = int(adjacency[u][slot])
-            if v == pad or v in visited:
-                continue
-            if labels is not None and not (labels[u][slot] <= alpha_s):
-                continue
-            if not (len(batch) < m_s):
-                continue
-            visited.add(v)
-            batch.append(v)
+        for u in todo:
+            pool[u] = True
+            n_exp += 1
+            taken = 0
+            for slot in range(degree):
+                v = int(adjacency[u][slot])
+                if v == pad or v in visited:
+                    continue
+                if labels is not None and not (labels[u][slot] <= alpha_s):
+                    continue
+                if not (taken < m_s):
+                    continue
+                visited.add(v)
+                batch.append(v)
+                taken += 1
         for v in batch:
             insert(v)
     return sorted(order(v) for v in pool), n_exp, n_dist

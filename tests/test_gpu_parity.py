@@ -120,6 +120,31 @@ def test_search_bit_exact_small_cases(H, n, d, R, nq, metric, bits, efs):
     ix.close()
 
 
+@pytest.mark.parametrize("n,d,R,nq,metric,bits,ef,P", [
+    (10000, 128, 32, 50, "l2", 8, 64, 4), (10000, 128, 32, 50, "l2", 8, 128, 2), (3000, 96, 32, 20, "ip", 8, 256, 3),
+    (1500, 960, 32, 8, "l2", 4, 100, 4), (1200, 768, 48, 8, "ip", 4, 512, 4), (40, 16, 5, 6, "l2", 8, 16, 4)])
+def test_multi_expansion_matches_the_batched_oracle(H, n, d, R, nq, metric, bits, ef, P):
+    """Fast mode: the P closest un-expanded entries per step.  Same pool and
+    visited semantics, so it too is compared bit for bit, against the oracle
+    run with the same P."""
+    m = metric_id(metric)
+    if n == 10000:
+        w = inputs.WORKLOADS["c1"]
+        X, Q = inputs.base_vectors(w), inputs.queries(w)[:nq]
+        adj, entry = inputs.graph(w, X)
+    else:
+        w, X, Q, adj = small_case(n, d, R, nq, seed=n + P, metric=metric, bits=bits, normalize=(metric == "ip"))
+        entry = 0
+    lv = oracle.sq_fit(X, bits)
+    ix = H.GpuIndex(X, adj, entry, [lv], m)
+    orc = oracle.search_batch(lv, d, adj, entry, Q, ef, metric=m, expansions_per_step=P)
+    gpu = ix.search(Q, ef, mode=1, expansions_per_step=P)
+    assert_search_equal(gpu, orc)
+    small = ix.search(Q, ef, mode=1, expansions_per_step=P, visited_slots=2048)
+    assert_search_equal(small, orc, check_counts=False)
+    ix.close()
+
+
 def test_search_with_per_query_entries_and_csr_upload(H):
     n, d, R, nq = 2000, 64, 16, 25
     w, X, Q, adj = small_case(n, d, R, nq, seed=77)

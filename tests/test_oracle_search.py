@@ -98,8 +98,9 @@ def test_matches_naive_python_search_with_heavy_ties(seed):
         for metric in (oracle.L2, oracle.IP):
             entries = rng.integers(0, n, size=(len(Q), 3)).astype(np.uint32)
             entries[:, 2] = entries[:, 0]       # duplicate entry
-            for use_labels in (False, True):
+            for use_labels, P in ((False, 1), (True, 1), (False, 3), (True, 2)):
                 kw = dict(labels=labels, alpha_s=1.2, m_s=3) if use_labels else {}
+                kw["expansions_per_step"] = P
                 ids, keys, dots, cnt = oracle.search_batch(lv, 4, adj, 0, Q, ef, metric=metric, entries=entries,
                                                            **kw)
                 for qi in range(len(Q)):
