@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--nq", type=int, default=0)
     ap.add_argument("--ef", type=int, default=0, help="skip the sweep and use this ef")
     ap.add_argument("--mode", type=int, default=-1, help="0 exact, 1 multi-expansion; -1: fastest that meets recall")
+    ap.add_argument("--expansions", type=int, default=0, help="expansions per step in mode 1 (0 = library default)")
     ap.add_argument("--visited-slots", type=int, default=0, help="LDS visited-table slots (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -111,21 +112,24 @@ def main():
     out_ids = torch.empty((nq, k), dtype=torch.int32, device=dev)
     out_dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
 
-    def run_step(ef, mode, pool, counts=None):
+    def run_step(ef, mode, pool, counts=None, visited_slots=None):
         ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=mode, out_ids=pool, out_counts=counts,
-                             visited_slots=args.visited_slots, stream=st)
+                             expansions_per_step=args.expansions if mode == 1 else 0,
+                             visited_slots=args.visited_slots if visited_slots is None else visited_slots, stream=st)
         ann.ann_rerank(index, qd, nq, pool, min(n_rerank, ef), ef, k, out_ids, out_dist, st)
 
     # recall sweep
     efs = [args.ef] if args.ef else list(w.ef)
-    modes = [args.mode] if args.mode >= 0 else [0]
+    modes = [args.mode] if args.mode >= 0 else [0, 1]
     sweep = []
     chosen = None
     for ef in efs:
         pool = torch.empty((nq, ef), dtype=torch.int32, device=dev)
         counts = torch.empty((nq, 4), dtype=torch.int32, device=dev)
         for mode in modes:
-            run_step(ef, mode, pool, counts)
+            # counting run with the largest visited table: no rebuilds, so the
+            # evaluation counts are those of the algorithm itself
+            run_step(ef, mode, pool, counts, visited_slots=8192)
             torch.cuda.synchronize()
             rec = recall_at_k(out_ids.cpu().numpy(), gt)
             c = counts.cpu().numpy().astype(np.int64)
@@ -140,17 +144,17 @@ def main():
                               rebuilds=int(c[:, 3].sum())))
             log(f"[bench] ef={ef} mode={mode} recall@{k}={rec:.4f} {ms:.3f} ms/batch n_exp={c[:, 0].mean():.1f} "
                 f"n_dist={c[:, 1].mean():.1f} rebuilds={int(c[:, 3].sum())}")
-            if chosen is None and rec >= 0.95:
-                chosen = (ef, mode, rec, c)
+            if rec >= 0.95 and (chosen is None or ms < chosen[4]):
+                chosen = (ef, mode, rec, c, ms)
     if chosen is None:          # target recall not reached inside the sweep: report the best point, say so
         best = max(sweep, key=lambda r: r["recall"])
         ef, mode = best["ef"], best["mode"]
         pool = torch.empty((nq, ef), dtype=torch.int32, device=dev)
         counts = torch.empty((nq, 4), dtype=torch.int32, device=dev)
-        run_step(ef, mode, pool, counts)
+        run_step(ef, mode, pool, counts, visited_slots=8192)
         torch.cuda.synchronize()
-        chosen = (ef, mode, best["recall"], counts.cpu().numpy().astype(np.int64))
-    ef, mode, rec, c = chosen
+        chosen = (ef, mode, best["recall"], counts.cpu().numpy().astype(np.int64), 0.0)
+    ef, mode, rec, c, _ = chosen
     pool = torch.empty((nq, ef), dtype=torch.int32, device=dev)
 
     # algorithmic bytes of one search launch: adjacency rows + code rows (+ norm
@@ -171,6 +175,7 @@ def main():
     for i in range(args.steps):
         e_begin[i].record()
         ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=mode, out_ids=pool,
+                             expansions_per_step=args.expansions if mode == 1 else 0,
                              visited_slots=args.visited_slots, stream=st)
         e_mid[i].record()
         ann.ann_rerank(index, qd, nq, pool, min(n_rerank, ef), ef, k, out_ids, out_dist, st)
@@ -214,7 +219,7 @@ def main():
                                f"rerank top {min(n_rerank, ef)}",
                    "ef": ef, "mode": "exact" if mode == 0 else "multi-expansion", "recall_at_10": round(rec, 4),
                    "recall_target_met": bool(rec >= 0.95), "sweep": sweep},
-        "roofline": {"bound": "hbm", "kernel": "search_exact_kernel" if mode == 0 else "search_multi_kernel",
+        "roofline": {"bound": "hbm", "kernel": "search_kernel (one expansion per step)" if mode == 0 else "search_kernel (multi-expansion)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "algorithmic_bytes_per_launch": bytes_search, "kernel_ms": round(kernel_ms, 4),

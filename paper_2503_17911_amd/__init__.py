@@ -11,8 +11,12 @@ from __future__ import annotations
 import ctypes
 from pathlib import Path
 
+import os
+
 _PKG = Path(__file__).resolve().parent
-LIB_PATH = _PKG / "lib" / "libann_gfx950.so"
+# ANN_LIBRARY_PATH selects another build of the same library (e.g. one compiled
+# with extra instrumentation); the default is the in-tree build.
+LIB_PATH = Path(os.environ.get("ANN_LIBRARY_PATH") or (_PKG / "lib" / "libann_gfx950.so"))
 
 PAD_ID = 0xFFFFFFFF
 L2, IP = 0, 1

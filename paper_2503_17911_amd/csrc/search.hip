@@ -52,10 +52,15 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
   return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
 
-// LDS bytes for one query: merge buffer, qualifying-candidate buffer, visited
-// table, candidate ids.
+// The merge scatter buffer doubles as the staging area of a step's qualifying
+// candidates (they are back in registers before the scatter starts).
+__host__ __device__ constexpr int merge_buf_entries(int m, int pmax) {
+  return 64 * m + 64 > 64 * pmax ? 64 * m + 64 : 64 * pmax;
+}
+
+// LDS bytes for one query: merge buffer, visited table, candidate ids.
 __host__ __device__ inline size_t search_smem_bytes(int m, int pmax, uint32_t vis_log2) {
-  return (size_t)(64 * m + 64) * 8 + (size_t)(64 * pmax) * 8 + ((size_t)1 << vis_log2) * 4 + (size_t)(64 * pmax) * 4;
+  return (size_t)merge_buf_entries(m, pmax) * 8 + ((size_t)1 << vis_log2) * 4 + (size_t)(64 * pmax) * 4;
 }
 
 template <int BITS, int LPR, int M, int PMAX>
@@ -65,8 +70,7 @@ struct SearchWave {
   static constexpr int TQW = TqRegs<BITS>::kWords;
 
   const SearchArgs &a;
-  uint64_t *mbuf;  // LDS [64*M + 64] merge scatter buffer
-  uint64_t *qbuf;  // LDS [64*PMAX] candidates that beat the pool's last entry
+  uint64_t *mbuf;  // LDS merge scatter buffer, also staging for a step's qualifying candidates
   uint32_t *vis;   // LDS [cap]
   uint32_t *cand;  // LDS [64*PMAX] unvisited neighbour ids of this step
   int lane, chunk, grp;
@@ -84,8 +88,7 @@ struct SearchWave {
     grp = lane / LPR;
     const uint32_t cap = 1u << a.vis_log2;
     mbuf = smem;
-    qbuf = mbuf + (64 * M + 64);
-    vis = reinterpret_cast<uint32_t *>(qbuf + 64 * PMAX);
+    vis = reinterpret_cast<uint32_t *>(mbuf + merge_buf_entries(M, PMAX));
     cand = vis + cap;
     vis_mask = cap - 1;
     vis_shift = 32 - a.vis_log2;
@@ -98,12 +101,15 @@ struct SearchWave {
 
   // true if id was not in the table (and now is)
   __device__ __forceinline__ bool test_and_set(uint32_t id) {
-    uint32_t slot = (id * 0x9E3779B1u) >> vis_shift;
+    // double hashing: the probe stride is odd, so every slot is reached
+    const uint32_t h = id * 0x9E3779B1u;
+    uint32_t slot = h >> vis_shift;
+    const uint32_t stride = ((h >> 4) | 1u) & vis_mask;
     for (;;) {
       uint32_t old = atomicCAS(&vis[slot], kEmpty, id);
       if (old == kEmpty) return true;
       if (old == id) return false;
-      slot = (slot + 1) & vis_mask;
+      slot = (slot + stride) & vis_mask;
     }
   }
 
@@ -225,17 +231,20 @@ struct SearchWave {
           const uint64_t c64 = pack64(order_u32(key), vid[u] << 1);
           const bool q = chunk == 0 && vid[u] != kEmpty && c64 < worst;
           const uint64_t bm = __ballot(q);
-          if (q) qbuf[n_q + lanes_below(bm)] = c64;
+          if (q) mbuf[n_q + lanes_below(bm)] = c64;
           n_q += __popcll(bm);
         }
       }
     }
+    if (n_q == 0) return;
     __syncthreads();
-    for (int b = 0; b < n_q; b += kWave) {
-      const bool have = b + lane < n_q;
-      const uint64_t c = have ? qbuf[b + lane] : 0;
-      merge(have, (uint32_t)(c >> 32), (uint32_t)c);
-    }
+    uint64_t batch[PMAX];
+#pragma unroll
+    for (int b = 0; b < PMAX; ++b) batch[b] = b * kWave + lane < n_q ? mbuf[b * kWave + lane] : 0;
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < PMAX; ++b)
+      if (b * kWave < n_q) merge(b * kWave + lane < n_q, (uint32_t)(batch[b] >> 32), (uint32_t)batch[b]);
   }
 
   __device__ void run(uint32_t qi) {
