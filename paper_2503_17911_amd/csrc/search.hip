@@ -443,9 +443,10 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   while ((1u << min_log2) < need) ++min_log2;
   uint32_t vis_log2;
   if (params->visited_slots == 0) {
-    // default: a table small enough for many resident queries; rebuilds
-    // repeat some evaluations but never change results
-    uint32_t want = 8 * ef < 2048 ? 2048 : 8 * ef;
+    // default: the smallest table that works, so that many queries are
+    // resident per compute unit; rebuilds repeat some evaluations but never
+    // change results (measured fastest on 1M x 128 for ef 64..256)
+    uint32_t want = 1024;
     vis_log2 = 0;
     while ((1u << vis_log2) < want) ++vis_log2;
     if (vis_log2 < min_log2) vis_log2 = min_log2;
