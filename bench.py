@@ -164,6 +164,17 @@ def main():
     bytes_search = int((c[:, 0] * 4 * adj.shape[1] + c[:, 1] * per_eval).sum() + nq * (d + ef * 4))
     bytes_rerank = nq * (min(n_rerank, ef) * (d * 4 + 4) + d * 4 + k * 8)
 
+    # the configuration that is timed repeats some evaluations when its small
+    # visited table is rebuilt; report how many
+    counts = torch.empty((nq, 4), dtype=torch.int32, device=dev)
+    run_step(ef, mode, pool, counts)
+    torch.cuda.synchronize()
+    ca = counts.cpu().numpy().astype(np.int64)
+    evals_timed, rebuilds_timed = float(ca[:, 1].mean()), float((ca[:, 3] & 0x7FFFFFFF).mean())
+    assert (ca[:, 3] < 2 ** 31).all(), "visited table failure flag set"
+    log(f"[bench] timed configuration: {evals_timed:.1f} evaluations/query ({float(c[:, 1].mean()):.1f} needed), "
+        f"{rebuilds_timed:.2f} table rebuilds/query")
+
     # timed region
     for _ in range(args.warmup):
         run_step(ef, mode, pool)
@@ -218,7 +229,8 @@ def main():
         "config": {"workload": f"{w.name}: N={n} d={d} SQ{bits} R={adj.shape[1]} {w.metric} k={k} nq={nq} "
                                f"rerank top {min(n_rerank, ef)}",
                    "ef": ef, "mode": "exact" if mode == 0 else "multi-expansion", "recall_at_10": round(rec, 4),
-                   "recall_target_met": bool(rec >= 0.95), "sweep": sweep},
+                   "recall_target_met": bool(rec >= 0.95), "evaluations_per_query": round(float(c[:, 1].mean()), 1),
+                   "evaluations_per_query_timed": round(evals_timed, 1), "sweep": sweep},
         "roofline": {"bound": "hbm", "kernel": "search_kernel (one expansion per step)" if mode == 0 else "search_kernel (multi-expansion)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
