@@ -14,7 +14,8 @@ struct LevelDev {
   uint32_t bits = 0;
   uint32_t row_bytes = 0;    // d or d/2: the bytes that carry codes
   uint32_t row_stride = 0;   // row_bytes rounded up to 16
-  uint32_t lanes_per_row = 0;  // power of two >= row_stride/16, in {8,16,32,64}
+  uint32_t lanes_per_row = 0;  // rescore kernel: one 16-byte chunk per lane; power of two >= row_stride/16, in {8,..,64}
+  uint32_t search_lanes = 0;   // search kernel: four chunks per lane; power of two >= row_stride/64, in {1,..,16}
   uint8_t *codes = nullptr;  // [n][row_stride]; 8-bit codes stored as (c ^ 0x80), 4-bit codes as given
   float *lo = nullptr;       // [d]
   float *delta = nullptr;    // [d]
@@ -54,9 +55,13 @@ ann_status hip_fail(hipError_t e, const char *what);
     if (e_ != hipSuccess) return ::ann::hip_fail(e_, #call); \
   } while (0)
 
-// Kernel-layout length of a folded query for a level: one 16-byte chunk of
-// codes per lane needs 16 (8-bit) or 32 (4-bit) query bytes.
-inline uint32_t tq_stride_for(const LevelDev &L) { return L.lanes_per_row * (L.bits == 8 ? 16u : 32u); }
+// Kernel-layout length of a folded query for a level: every 16-byte chunk of
+// codes needs 16 (8-bit) or 32 (4-bit) query bytes; zero-padded to the number
+// of chunks the kernels' lanes cover.
+inline uint32_t tq_stride_for(const LevelDev &L) {
+  uint32_t chunks = L.search_lanes * 4 > L.lanes_per_row ? L.search_lanes * 4 : L.lanes_per_row;
+  return chunks * (L.bits == 8 ? 16u : 32u);
+}
 
 ann_status ensure_workspace(ann_index *index, uint32_t level, uint32_t nq);
 ann_status launch_query_prep(ann_index *index, uint32_t level, const float *q, uint32_t nq, int8_t *t_plain,

@@ -201,6 +201,9 @@ ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index 
     while (lpr < chunks) lpr <<= 1;
     if (lpr > 64) return cleanup(fail(ANN_ECAPACITY, "level %u: code rows of %u bytes exceed 1024", l, L.row_bytes));
     L.lanes_per_row = lpr;
+    uint32_t sl = 1;
+    while (sl * 4 < chunks) sl <<= 1;
+    L.search_lanes = sl;
     ANN_TRY(dev_copy(&L.lo, S.lo, desc->d, host, st));
     ANN_TRY(dev_copy(&L.delta, S.delta, desc->d, host, st));
     if (S.norm_term) ANN_TRY(dev_copy(&L.norm_term, S.norm_term, (size_t)n, host, st));

@@ -10,8 +10,11 @@
 //                   tested against V first, survivors are compacted (the
 //                   "deterministic access" batch filter), and only their code
 //                   rows are fetched.
-//   tau_l           LPR lanes share one code row, 16 bytes per lane; packed
-//                   int8 dot products, reduced across the lanes with DPP.
+//   tau_l           LPR lanes share one code row, four 16-byte chunks per lane
+//                   (interleaved, so one load instruction reads LPR*16
+//                   contiguous bytes of each row); packed int8 dot products,
+//                   reduced across the LPR lanes with DPP.  128-byte rows: two
+//                   lanes per row, 32 rows per instruction group.
 //   insert          all candidates of a step that beat the pool's last entry
 //                   are merged at once: every pool entry counts the candidates
 //                   below it, every candidate counts the pool entries and
@@ -65,17 +68,19 @@ __host__ __device__ inline size_t search_smem_bytes(int m, int pmax, uint32_t vi
 
 template <int BITS, int LPR, int M, int PMAX>
 struct SearchWave {
-  static constexpr int G = kWave / LPR;  // code rows evaluated side by side
-  static constexpr int U = 4;            // row loads in flight per lane
+  static constexpr int G = kWave / LPR;      // code rows evaluated side by side
+  static constexpr int CPL = 4;              // 16-byte chunks of a row per lane
+  static constexpr int U = PMAX > 1 ? 2 : 1;  // groups of G rows in flight
   static constexpr int TQW = TqRegs<BITS>::kWords;
 
   const SearchArgs &a;
   uint64_t *mbuf;  // LDS merge scatter buffer, also staging for a step's qualifying candidates
   uint32_t *vis;   // LDS [cap]
   uint32_t *cand;  // LDS [64*PMAX] unvisited neighbour ids of this step
-  int lane, chunk, grp;
+  int lane, sub, grp;
+  uint32_t coff[CPL];  // byte offsets of this lane's chunks inside a code row
   uint32_t vis_mask, vis_shift, vis_limit;
-  int tq[TQW];
+  int tq[CPL][TQW];
   float s, qlo;
   int bias;
   uint32_t pk[M], pv[M];  // pool: ordered key bits; (id << 1) | expanded
@@ -84,8 +89,15 @@ struct SearchWave {
 
   __device__ SearchWave(const SearchArgs &args, uint64_t *smem) : a(args) {
     lane = lane_id();
-    chunk = lane % LPR;
+    sub = lane % LPR;
     grp = lane / LPR;
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) {
+      // chunks past the end of the row are read from the last chunk instead;
+      // their share of the folded query is zero
+      const uint32_t c = (uint32_t)(sub + j * LPR);
+      coff[j] = (c < a.n_chunks ? c : a.n_chunks - 1) * 16u;
+    }
     const uint32_t cap = 1u << a.vis_log2;
     mbuf = smem;
     vis = reinterpret_cast<uint32_t *>(mbuf + merge_buf_entries(M, PMAX));
@@ -206,30 +218,32 @@ struct SearchWave {
     __syncthreads();
     int n_q = 0;
     for (int base = 0; base < n_cand; base += G * U) {
-      uint4 rows[U];
+      uint4 rows[U][CPL];
       float nrm[U];
       uint32_t vid[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         if (base + u * G < n_cand) {
+          // lanes past the end of the list recompute its last node; the
+          // duplicate is ignored below, and no branch is needed around loads
           const int ci = base + u * G + grp;
-          vid[u] = ci < n_cand ? cand[ci] : kEmpty;
-          rows[u] = make_uint4(0, 0, 0, 0);
-          nrm[u] = 0.0f;
-          if (vid[u] != kEmpty) {
-            if (chunk < (int)a.n_chunks)
-              rows[u] = *reinterpret_cast<const uint4 *>(a.codes + (uint64_t)vid[u] * a.row_stride + (uint32_t)chunk * 16u);
-            if (a.norm_term && chunk == 0) nrm[u] = a.norm_term[vid[u]];
-          }
+          vid[u] = cand[ci < n_cand ? ci : n_cand - 1];
+          const uint8_t *rp = a.codes + (uint64_t)vid[u] * a.row_stride;
+#pragma unroll
+          for (int j = 0; j < CPL; ++j) rows[u][j] = *reinterpret_cast<const uint4 *>(rp + coff[j]);
+          nrm[u] = a.norm_term ? a.norm_term[vid[u]] : 0.0f;
         }
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         if (base + u * G < n_cand) {
-          const int dot = group_sum_i32<LPR>(chunk_dot<BITS>(rows[u], tq)) + bias;
+          int dot = 0;
+#pragma unroll
+          for (int j = 0; j < CPL; ++j) dot += chunk_dot<BITS>(rows[u][j], tq[j]);
+          dot = group_sum_i32<LPR>(dot) + bias;
           const float key = key_from_idot(a.metric, s, qlo, dot, nrm[u]);
           const uint64_t c64 = pack64(order_u32(key), vid[u] << 1);
-          const bool q = chunk == 0 && vid[u] != kEmpty && c64 < worst;
+          const bool q = sub == 0 && base + u * G + grp < n_cand && c64 < worst;
           const uint64_t bm = __ballot(q);
           if (q) mbuf[n_q + lanes_below(bm)] = c64;
           n_q += __popcll(bm);
@@ -249,9 +263,12 @@ struct SearchWave {
 
   __device__ void run(uint32_t qi) {
     // this lane's share of the folded query
-    const int *tqp = reinterpret_cast<const int *>(a.tq + (uint64_t)qi * a.tq_stride + (uint32_t)chunk * (TQW * 4u));
 #pragma unroll
-    for (int w = 0; w < TQW; ++w) tq[w] = tqp[w];
+    for (int j = 0; j < CPL; ++j) {
+      const int *tqp = reinterpret_cast<const int *>(a.tq + (uint64_t)qi * a.tq_stride + (uint32_t)(sub + j * LPR) * (TQW * 4u));
+#pragma unroll
+      for (int w = 0; w < TQW; ++w) tq[j][w] = tqp[w];
+    }
     s = a.s[qi];
     qlo = a.qlo[qi];
     bias = BITS == 8 ? 128 * a.sum_t[qi] : 0;
@@ -352,23 +369,17 @@ struct SearchWave {
 #pragma unroll
       for (int r = 0; r < M; ++r) st_id[r * kWave + lane] = pk[r] != kEmpty ? (pv[r] >> 1) : kEmpty;
       __syncthreads();
-      for (int base = 0; base < (int)a.ef; base += G * U) {
-        uint4 rows[U];
-        uint32_t vid[U];
+      for (int base = 0; base < (int)a.ef; base += G) {
+        const int ci = base + grp;
+        const uint32_t v = ci < (int)a.ef ? st_id[ci] : kEmpty;
+        int dot = 0;
+        if (v != kEmpty) {
+          const uint8_t *rp = a.codes + (uint64_t)v * a.row_stride;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int ci = base + u * G + grp;
-          vid[u] = ci < (int)a.ef ? st_id[ci] : kEmpty;
-          rows[u] = make_uint4(0, 0, 0, 0);
-          if (vid[u] != kEmpty && chunk < (int)a.n_chunks)
-            rows[u] = *reinterpret_cast<const uint4 *>(a.codes + (uint64_t)vid[u] * a.row_stride + (uint32_t)chunk * 16u);
+          for (int j = 0; j < CPL; ++j) dot += chunk_dot<BITS>(*reinterpret_cast<const uint4 *>(rp + coff[j]), tq[j]);
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int dot = group_sum_i32<LPR>(chunk_dot<BITS>(rows[u], tq)) + bias;
-          const int ci = base + u * G + grp;
-          if (chunk == 0 && ci < (int)a.ef) a.out_idot[(uint64_t)qi * a.ef + ci] = vid[u] != kEmpty ? dot : 0;
-        }
+        dot = group_sum_i32<LPR>(dot) + bias;
+        if (sub == 0 && ci < (int)a.ef) a.out_idot[(uint64_t)qi * a.ef + ci] = v != kEmpty ? dot : 0;
       }
     }
     if (a.out_counts && lane == 0) {
@@ -407,10 +418,11 @@ static ann_status launch_m(const SearchArgs &args, int m, hipStream_t st) {
 template <int BITS, int PMAX>
 static ann_status launch_lpr(const SearchArgs &args, uint32_t lpr, int m, hipStream_t st) {
   switch (lpr) {
+    case 1: return launch_m<BITS, 1, PMAX>(args, m, st);
+    case 2: return launch_m<BITS, 2, PMAX>(args, m, st);
+    case 4: return launch_m<BITS, 4, PMAX>(args, m, st);
     case 8: return launch_m<BITS, 8, PMAX>(args, m, st);
     case 16: return launch_m<BITS, 16, PMAX>(args, m, st);
-    case 32: return launch_m<BITS, 32, PMAX>(args, m, st);
-    case 64: return launch_m<BITS, 64, PMAX>(args, m, st);
     default: return fail(ANN_EUNSUPPORTED, "no kernel for %u lanes per code row", lpr);
   }
 }
@@ -492,7 +504,7 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   int m = 1;
   while (64 * m < (int)ef) m <<= 1;
   if (params->mode == 0)
-    return L.bits == 8 ? launch_lpr<8, 1>(a, L.lanes_per_row, m, st) : launch_lpr<4, 1>(a, L.lanes_per_row, m, st);
-  return L.bits == 8 ? launch_lpr<8, kMaxExpansionsPerStep>(a, L.lanes_per_row, m, st)
-                     : launch_lpr<4, kMaxExpansionsPerStep>(a, L.lanes_per_row, m, st);
+    return L.bits == 8 ? launch_lpr<8, 1>(a, L.search_lanes, m, st) : launch_lpr<4, 1>(a, L.search_lanes, m, st);
+  return L.bits == 8 ? launch_lpr<8, kMaxExpansionsPerStep>(a, L.search_lanes, m, st)
+                     : launch_lpr<4, kMaxExpansionsPerStep>(a, L.search_lanes, m, st);
 }
