@@ -226,3 +226,40 @@ def test_bruteforce_matches_fp64_exhaustive_search(H, n, d, nq, k, metric):
     kk = min(k, n)
     H.check_rerank(gid[:, :kk], gdist[:, :kk], oid, odist.astype(np.float32), rel=1e-6)
     assert (gid[:, kk:] == PAD).all() and np.isinf(gdist[:, kk:]).all()
+
+
+def test_c2_full_size_sampled_queries(H):
+    """The benchmark workload at full size (1M x 128, SQ8, R=32) in the launch
+    configuration bench.py times (default visited table, both modes): the whole
+    10,000-query batch runs on the GPU, a sample of queries is recomputed by the
+    oracle one by one, and properties that hold at any size are checked for all."""
+    w = inputs.WORKLOADS["c2"]
+    X, Q = inputs.base_vectors(w), inputs.queries(w)
+    adj, entry = inputs.graph(w, X)
+    lo, delta, codes, norm = H.gpu_sq_fit(X, 8)
+    lv = oracle.sq_fit(X, 8)
+    assert (codes == lv.codes).all() and (norm.view(np.uint32) == lv.norm_term.view(np.uint32)).all()
+    ix = H.GpuIndex(X, adj, entry, [oracle.SQLevel(8, lo, delta, codes, norm)], oracle.L2)
+    sample = np.arange(0, w.nq, 97)[:100]
+    for ef, mode, P in ((128, 0, 1), (128, 1, 4), (256, 1, 4)):
+        ids, keys, _, counts = ix.search(Q, ef, k=w.k, want_idot=False, mode=mode, expansions_per_step=P if mode else 0,
+                                         visited_slots=0)
+        oi, ok, _, oc = oracle.search_batch(lv, w.d, adj, entry, Q[sample], ef, expansions_per_step=P)
+        assert (ids[sample] == oi).all()
+        assert (keys[sample].view(np.uint32) == ok.view(np.uint32)).all()
+        assert (counts[sample, 0] == oc[:, 0]).all() and (counts[sample, 2] == oc[:, 2]).all()
+        assert (counts[sample, 1] >= oc[:, 1]).all()        # small table: evaluations may repeat, never go missing
+        # every query: full pool, sorted by (key, id), distinct ids in range
+        assert (counts[:, 2] == ef).all() and ids.max() < w.n
+        assert ((np.diff(keys, axis=1) > 0) | ((np.diff(keys, axis=1) == 0) & (np.diff(ids.astype(np.int64), axis=1) > 0))).all()
+        srt = np.sort(ids, axis=1)
+        assert (np.diff(srt.astype(np.int64), axis=1) > 0).all()
+        rid, rdist = ix.rerank(Q, ids, 2 * w.k, w.k)
+        roid, rodist = oracle.rerank_batch(X, Q[sample], oi[:, :2 * w.k], w.k)
+        H.check_rerank(rid[sample], rdist[sample], roid, rodist)
+    # ground truth on the same sample
+    bid, bdist = H.gpu_bruteforce(X, Q[sample], w.k, oracle.L2)
+    tid, tdist = oracle.bruteforce_topk(X, Q[sample[:20]], w.k)
+    H.check_rerank(bid[:20], bdist[:20], tid, tdist.astype(np.float32), rel=1e-6)
+    assert oracle.recall(rid[sample], bid) >= 0.95
+    ix.close()
