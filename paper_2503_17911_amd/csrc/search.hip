@@ -125,6 +125,42 @@ struct SearchWave {
     }
   }
 
+  // Two ids per lane at once: the two probe sequences advance together, so
+  // the latency of the LDS atomics overlaps.  Bit 0 / bit 1 of the result: id0
+  // / id1 was not in the table (and now is).  A lane's two ids may be equal.
+  __device__ __forceinline__ int test_and_set2(bool v0, uint32_t id0, bool v1, uint32_t id1) {
+    const uint32_t h0 = id0 * 0x9E3779B1u, h1 = id1 * 0x9E3779B1u;
+    uint32_t s0 = h0 >> vis_shift, s1 = h1 >> vis_shift;
+    const uint32_t st0 = ((h0 >> 4) | 1u) & vis_mask, st1 = ((h1 >> 4) | 1u) & vis_mask;
+    int fresh = 0;
+    while (v0 || v1) {
+      uint32_t o0 = 0, o1 = 0;
+      if (v0) o0 = atomicCAS(&vis[s0], kEmpty, id0);
+      if (v1) o1 = atomicCAS(&vis[s1], kEmpty, id1);
+      if (v0) {
+        if (o0 == kEmpty) {
+          fresh |= 1;
+          v0 = false;
+        } else if (o0 == id0) {
+          v0 = false;
+        } else {
+          s0 = (s0 + st0) & vis_mask;
+        }
+      }
+      if (v1) {
+        if (o1 == kEmpty) {
+          fresh |= 2;
+          v1 = false;
+        } else if (o1 == id1) {
+          v1 = false;
+        } else {
+          s1 = (s1 + st1) & vis_mask;
+        }
+      }
+    }
+    return fresh;
+  }
+
   // The table holds every node whose key has been evaluated, as long as it
   // fits.  When it is about to pass 3/4 load it is rebuilt from the pool.  A
   // forgotten node is outside the pool, so it was rejected or evicted by a
@@ -207,6 +243,16 @@ struct SearchWave {
     const uint64_t fm = __ballot(fresh);
     if (fresh) cand[n_cand + lanes_below(fm)] = nb;
     n_cand += __popcll(fm);
+  }
+
+  // Same for two lists at once (list 0's survivors are appended first).
+  __device__ __forceinline__ void filter_ids2(uint32_t nb0, uint32_t nb1, int &n_cand) {
+    const int f = test_and_set2(nb0 != kEmpty && nb0 < a.n, nb0, nb1 != kEmpty && nb1 < a.n, nb1);
+    const uint64_t fm0 = __ballot(f & 1), fm1 = __ballot(f & 2);
+    const int c0 = __popcll(fm0);
+    if (f & 1) cand[n_cand + lanes_below(fm0)] = nb0;
+    if (f & 2) cand[n_cand + c0 + lanes_below(fm1)] = nb1;
+    n_cand += c0 + __popcll(fm1);
   }
 
   // tau_l for the n_cand nodes in cand[], then merge the ones that can enter
@@ -317,34 +363,57 @@ struct SearchWave {
       n_exp += got;
       if (PMAX > 1 && n_vis + (uint32_t)(got * kWave) > vis_limit) rebuild_table();
 
-      uint32_t rows[PMAX];
-#pragma unroll
-      for (int e = 0; e < PMAX; ++e) {
-        rows[e] = kEmpty;
-        if (e < got) {
-          const uint32_t uid = __builtin_amdgcn_readlane(picked, e);
-          if (PMAX == 1 && uid == pre_id)
-            rows[e] = pre_row;
-          else if (lane < (int)a.degree)
-            rows[e] = a.adjacency[(uint64_t)uid * a.degree + lane];
-        }
-      }
-      if (PMAX == 1) {
-        // fetch ahead the row of the entry that is expanded next unless a
-        // candidate of this step overtakes it
-        pre_id = next_id;
-        pre_row = kEmpty;
-        if (next_id != kEmpty && lane < (int)a.degree) pre_row = a.adjacency[(uint64_t)next_id * a.degree + lane];
-      }
       int n_cand = 0;
+      if (PMAX > 1 && a.degree <= 32) {
+        // two adjacency rows per pass: lanes 0-31 take one, lanes 32-63 the next
+        const int slot = lane & 31;
+        uint32_t rows[PMAX / 2 > 0 ? PMAX / 2 : 1];
 #pragma unroll
-      for (int e = 0; e < PMAX; ++e) {
-        if (e < got) {
-          if (PMAX == 1) {
-            const uint32_t incoming = (uint32_t)__popcll(__ballot(rows[e] != kEmpty));
-            if (n_vis + incoming > vis_limit) rebuild_table();
+        for (int t = 0; t < PMAX / 2; ++t) {
+          rows[t] = kEmpty;
+          if (2 * t < got) {
+            const uint32_t u0 = __builtin_amdgcn_readlane(picked, 2 * t);
+            const uint32_t u1 = __builtin_amdgcn_readlane(picked, 2 * t + 1);
+            const uint32_t uid = lane < 32 ? u0 : u1;
+            if (uid != kEmpty && slot < (int)a.degree) rows[t] = a.adjacency[(uint64_t)uid * a.degree + slot];
           }
-          filter_ids(rows[e], n_cand);
+        }
+#pragma unroll
+        for (int t = 0; t < PMAX / 2; t += 2) {
+          if (t + 1 < PMAX / 2 && 2 * (t + 1) < got)
+            filter_ids2(rows[t], rows[t + 1 < PMAX / 2 ? t + 1 : t], n_cand);
+          else if (2 * t < got)
+            filter_ids(rows[t], n_cand);
+        }
+      } else {
+        uint32_t rows[PMAX];
+#pragma unroll
+        for (int e = 0; e < PMAX; ++e) {
+          rows[e] = kEmpty;
+          if (e < got) {
+            const uint32_t uid = __builtin_amdgcn_readlane(picked, e);
+            if (PMAX == 1 && uid == pre_id)
+              rows[e] = pre_row;
+            else if (lane < (int)a.degree)
+              rows[e] = a.adjacency[(uint64_t)uid * a.degree + lane];
+          }
+        }
+        if (PMAX == 1) {
+          // fetch ahead the row of the entry that is expanded next unless a
+          // candidate of this step overtakes it
+          pre_id = next_id;
+          pre_row = kEmpty;
+          if (next_id != kEmpty && lane < (int)a.degree) pre_row = a.adjacency[(uint64_t)next_id * a.degree + lane];
+        }
+#pragma unroll
+        for (int e = 0; e < PMAX; ++e) {
+          if (e < got) {
+            if (PMAX == 1) {
+              const uint32_t incoming = (uint32_t)__popcll(__ballot(rows[e] != kEmpty));
+              if (n_vis + incoming > vis_limit) rebuild_table();
+            }
+            filter_ids(rows[e], n_cand);
+          }
         }
       }
       evaluate_and_merge(n_cand);
