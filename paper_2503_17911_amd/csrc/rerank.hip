@@ -174,8 +174,9 @@ static void launch_rerank(uint32_t lpr, const float *X, uint32_t d, uint32_t met
 ann_status rerank_device(const float *X, uint64_t n, uint32_t d, uint32_t metric, const float *Q, uint32_t nq,
                          const uint32_t *cand, uint32_t n_cand, uint32_t stride, uint32_t k, uint32_t *out_ids,
                          float *out_dist, hipStream_t st) {
+  // four 16-byte pieces of a row per lane: 128 dimensions -> 8 lanes per row, 8 rows side by side
   uint32_t chunks = (d + 3) / 4, lpr = 8;
-  while (lpr < chunks && lpr < 64) lpr <<= 1;
+  while (lpr * 4 < chunks && lpr < 64) lpr <<= 1;
   const size_t smem = (size_t)n_cand * sizeof(uint64_t) + (size_t)((d + 3) / 4) * 16;
   if (d % 4 == 0)
     launch_rerank<true>(lpr, X, d, metric, Q, nq, n, cand, n_cand, stride, k, out_ids, out_dist, smem, st);

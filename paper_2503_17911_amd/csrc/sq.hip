@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void sq_encode_kernel(const float *__restrict_
 // ------------------------------------------------------------- query folding
 // One wavefront per query.  a_j = delta_j q_j; s = max|a|/127; t_j =
 // rint(a_j * (127/max|a|)) in [-127,127]; qlo = sum_j q_j lo_j in fp64 in
-// dimension order (one lane).  Writes the folded query in the layout the
+// dimension order.  Writes the folded query in the layout the
 // search kernels load (see chunk_dot) and optionally as plain [nq][d] int8.
 template <int BITS>
 __global__ __launch_bounds__(64) void query_prep_kernel(const float *__restrict__ q, uint32_t nq, uint32_t d,
@@ -134,9 +134,14 @@ __global__ __launch_bounds__(64) void query_prep_kernel(const float *__restrict_
     sum += ti;
   }
   sum = group_sum_i32<64>(sum);
+  // every product of two floats is exact in fp64; they are formed by all lanes
+  // and then added by one lane in dimension order, which fixes the rounding
+  extern __shared__ double prod[];
+  for (uint32_t j = lane; j < d; j += kWave) prod[j] = (double)qr[j] * (double)lo[j];
+  __syncthreads();
   if (lane == 0) {
     double acc = 0.0;
-    for (uint32_t j = 0; j < d; ++j) acc += (double)qr[j] * (double)lo[j];
+    for (uint32_t j = 0; j < d; ++j) acc += prod[j];
     float qlo = (float)acc;
     s_ws[qi] = s;
     qlo_ws[qi] = qlo;
@@ -153,10 +158,10 @@ ann_status launch_query_prep(ann_index *ix, uint32_t level, const float *q, uint
   const LevelDev &L = ix->level[level];
   Workspace &w = ix->ws[level];
   if (L.bits == 8)
-    query_prep_kernel<8><<<nq, 64, 0, st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t, t_plain,
+    query_prep_kernel<8><<<nq, 64, (size_t)ix->d * sizeof(double), st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t, t_plain,
                                             s_out, qlo_out);
   else
-    query_prep_kernel<4><<<nq, 64, 0, st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t, t_plain,
+    query_prep_kernel<4><<<nq, 64, (size_t)ix->d * sizeof(double), st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t, t_plain,
                                             s_out, qlo_out);
   ANN_HIP(hipGetLastError());
   return ANN_OK;
