@@ -51,6 +51,20 @@ struct SearchArgs {
 
 __device__ __forceinline__ uint64_t pack64(uint32_t hi, uint32_t lo) { return ((uint64_t)hi << 32) | lo; }
 
+// v with lane `lane` replaced by the wave-uniform `value` (v_writelane_b32; on
+// this ISA the lane select of a write with a scalar value goes through m0).
+__device__ __forceinline__ int write_lane(int v, int value, int lane) {
+  int saved_m0;
+  asm volatile(
+      "s_mov_b32 %1, m0\n\t"
+      "s_mov_b32 m0, %3\n\t"
+      "v_writelane_b32 %0, %2, m0\n\t"
+      "s_mov_b32 m0, %1"
+      : "+v"(v), "=&s"(saved_m0)
+      : "s"(value), "s"(lane));
+  return v;
+}
+
 __device__ __forceinline__ int lanes_below(uint64_t mask) {
   return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
@@ -199,12 +213,13 @@ struct SearchWave {
     const bool mine = have && c64 < worst;
     const uint64_t qm = __ballot(mine);
     if (qm == 0) return;
+    const int n_m = __popcll(qm);
     uint64_t e[M];
-    int shift[M];
+    int above[M];  // candidates greater than this pool entry
 #pragma unroll
     for (int r = 0; r < M; ++r) {
       e[r] = pack64(pk[r], pv[r]);
-      shift[r] = 0;
+      above[r] = 0;
     }
     int below_c = 0, below_p = 0;  // candidates / pool entries smaller than this lane's candidate
     for (uint64_t m = qm; m; m &= m - 1) {
@@ -215,13 +230,15 @@ struct SearchWave {
       for (int r = 0; r < M; ++r) {
         const bool lt = e[r] < s64;
         rank += __popcll(__ballot(lt));
-        shift[r] += lt ? 0 : 1;
+        above[r] += lt ? 1 : 0;
       }
       below_c += s64 < c64 ? 1 : 0;
-      below_p = lane == l ? rank : below_p;
+      below_p = write_lane(below_p, rank, l);
     }
+    // a pool entry moves up by the number of candidates below it (no two
+    // (key, id) pairs are equal)
 #pragma unroll
-    for (int r = 0; r < M; ++r) mbuf[r * kWave + lane + shift[r]] = e[r];
+    for (int r = 0; r < M; ++r) mbuf[r * kWave + lane + (n_m - above[r])] = e[r];
     if (mine) mbuf[below_p + below_c] = c64;
     __syncthreads();
 #pragma unroll
