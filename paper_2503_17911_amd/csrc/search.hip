@@ -71,9 +71,7 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
 
 // The merge scatter buffer doubles as the staging area of a step's qualifying
 // candidates (they are back in registers before the scatter starts).
-__host__ __device__ constexpr int merge_buf_entries(int m, int pmax) {
-  return 64 * m + 64 > 64 * pmax ? 64 * m + 64 : 64 * pmax;
-}
+__host__ __device__ constexpr int merge_buf_entries(int m, int /*pmax*/) { return 64 * m + 64; }
 
 // LDS bytes for one query: merge buffer, visited table, candidate ids.
 __host__ __device__ inline size_t search_smem_bytes(int m, int pmax, uint32_t vis_log2) {
@@ -272,6 +270,22 @@ struct SearchWave {
     n_cand += c0 + __popcll(fm1);
   }
 
+  // Merge the n_q candidates staged in mbuf[0..n_q) into the pool, 64 at a time
+  // (they are copied to registers first: the merge scatters through mbuf).
+  static constexpr int kStage = 64 * M + 64;
+  __device__ __forceinline__ void merge_staged(int &n_q) {
+    if (n_q == 0) return;
+    __syncthreads();
+    uint64_t batch[M + 1];
+#pragma unroll
+    for (int b = 0; b <= M; ++b) batch[b] = b * kWave + lane < n_q ? mbuf[b * kWave + lane] : 0;
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b <= M; ++b)
+      if (b * kWave < n_q) merge(b * kWave + lane < n_q, (uint32_t)(batch[b] >> 32), (uint32_t)batch[b]);
+    n_q = 0;
+  }
+
   // tau_l for the n_cand nodes in cand[], then merge the ones that can enter
   // the pool.
   __device__ __forceinline__ void evaluate_and_merge(int n_cand) {
@@ -308,20 +322,13 @@ struct SearchWave {
           const uint64_t c64 = pack64(order_u32(key), vid[u] << 1);
           const bool q = sub == 0 && base + u * G + grp < n_cand && c64 < worst;
           const uint64_t bm = __ballot(q);
+          if (n_q + G > kStage) merge_staged(n_q);  // rare: make room (the pool's last entry only gets smaller)
           if (q) mbuf[n_q + lanes_below(bm)] = c64;
           n_q += __popcll(bm);
         }
       }
     }
-    if (n_q == 0) return;
-    __syncthreads();
-    uint64_t batch[PMAX];
-#pragma unroll
-    for (int b = 0; b < PMAX; ++b) batch[b] = b * kWave + lane < n_q ? mbuf[b * kWave + lane] : 0;
-    __syncthreads();
-#pragma unroll
-    for (int b = 0; b < PMAX; ++b)
-      if (b * kWave < n_q) merge(b * kWave + lane < n_q, (uint32_t)(batch[b] >> 32), (uint32_t)batch[b]);
+    merge_staged(n_q);
   }
 
   __device__ void run(uint32_t qi) {
