@@ -81,6 +81,11 @@ typedef struct {
  *             holds csr_offsets[n] neighbour ids; rows longer than `degree` are
  *             an error.  degree <= ANN_MAX_DEGREE.
  *   entry_point  default initial node of every search.
+ *   edge_labels  optional [n][degree] (same shape as the fixed-degree adjacency,
+ *             or [csr_offsets[n]] in CSR form): the label L of every edge
+ *             (paper Section 4.3: the smallest pruning rate under which the edge
+ *             exists).  NULL: no labels.
+ *   A row must not name the same neighbour twice (ANN_EINVAL).
  */
 typedef struct {
   uint64_t n;
@@ -94,6 +99,7 @@ typedef struct {
   const uint64_t *csr_offsets;
   uint32_t entry_point;
   uint32_t flags;
+  const float *edge_labels;
 } ann_index_desc;
 
 /*
@@ -110,6 +116,11 @@ typedef struct {
  *                 a power of two, 0 = chosen from ef and degree.  When the
  *                 table fills it is rebuilt from the current pool; this costs
  *                 repeated distance evaluations, never a different result.
+ *   alpha_s, m_s  the search-time edge filter of Algorithm 1 (Section 4.3): an
+ *                 edge is followed only if its label <= alpha_s, and at most
+ *                 m_s unvisited neighbours are taken per expansion, in stored
+ *                 order.  alpha_s = 0 (labels are >= 1): no label test; needs an
+ *                 index uploaded with edge_labels otherwise.  m_s = 0: no cap.
  */
 typedef struct {
   uint32_t k;
@@ -117,7 +128,9 @@ typedef struct {
   uint32_t mode;
   uint32_t expansions_per_step;
   uint32_t visited_slots;
-  uint32_t reserved[3]; /* must be zero */
+  float alpha_s;
+  uint32_t m_s;
+  uint32_t reserved; /* must be zero */
 } ann_search_params;
 
 /*
@@ -140,7 +153,8 @@ ann_status ann_sq_encode(const float *x, uint64_t n, uint32_t d, uint32_t bits, 
  * into 16-byte aligned rows and the adjacency into [n][degree].  Synchronous;
  * the descriptor's arrays may be released afterwards.  *out receives the index.
  * Errors: ANN_EINVAL (NULL arrays, n == 0 or n >= 2^31, degree == 0, bits not
- * 4/8, odd d with 4 bits, entry_point >= n, neighbour id >= n), ANN_ECAPACITY
+ * 4/8, odd d with 4 bits, entry_point >= n, neighbour id >= n, repeated neighbour
+ * in a row), ANN_ECAPACITY
  * (degree > ANN_MAX_DEGREE, d > 2048), ANN_ENOMEM, ANN_EDEVICE.
  */
 ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index **out);

@@ -45,13 +45,13 @@ class IndexDesc(ctypes.Structure):
     _fields_ = [("n", ctypes.c_uint64), ("d", ctypes.c_uint32), ("degree", ctypes.c_uint32),
                 ("metric", ctypes.c_uint32), ("n_levels", ctypes.c_uint32), ("vectors", ctypes.c_void_p),
                 ("level", SQLevelDesc * 2), ("adjacency", ctypes.c_void_p), ("csr_offsets", ctypes.c_void_p),
-                ("entry_point", ctypes.c_uint32), ("flags", ctypes.c_uint32)]
+                ("entry_point", ctypes.c_uint32), ("flags", ctypes.c_uint32), ("edge_labels", ctypes.c_void_p)]
 
 
 class SearchParams(ctypes.Structure):
     _fields_ = [("k", ctypes.c_uint32), ("ef", ctypes.c_uint32), ("mode", ctypes.c_uint32),
                 ("expansions_per_step", ctypes.c_uint32), ("visited_slots", ctypes.c_uint32),
-                ("reserved", ctypes.c_uint32 * 3)]
+                ("alpha_s", ctypes.c_float), ("m_s", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 def _load_library() -> ctypes.CDLL:
@@ -114,7 +114,7 @@ def ann_sq_encode(x, n, d, bits, lo, delta, codes, norm_term, stream=None):
 
 
 def ann_upload_index(*, n, d, degree, metric, vectors, levels, adjacency, entry_point, csr_offsets=None,
-                     host_pointers=False, stream=None) -> int:
+                     edge_labels=None, host_pointers=False, stream=None) -> int:
     """levels: list of (bits, codes, lo, delta, norm_term).  Returns the opaque index handle."""
     desc = IndexDesc()
     desc.n, desc.d, desc.degree, desc.metric = n, d, degree, metric
@@ -128,6 +128,7 @@ def ann_upload_index(*, n, d, degree, metric, vectors, levels, adjacency, entry_
         desc.level[i].norm_term = _ptr(norm)
     desc.adjacency = _ptr(adjacency)
     desc.csr_offsets = _ptr(csr_offsets)
+    desc.edge_labels = _ptr(edge_labels)
     desc.entry_point = entry_point
     desc.flags = DESC_HOST_POINTERS if host_pointers else 0
     handle = ctypes.c_void_p()
@@ -144,8 +145,10 @@ def ann_query_prep(index, level, q, nq, t, s, qlo, stream=None):
 
 
 def ann_search_batch(index, q, nq, *, k, ef, out_ids, out_keys=None, out_idot=None, out_counts=None, mode=0,
-                     expansions_per_step=0, visited_slots=0, entry_ids=None, n_entry=0, stream=None):
-    p = SearchParams(k=k, ef=ef, mode=mode, expansions_per_step=expansions_per_step, visited_slots=visited_slots)
+                     expansions_per_step=0, visited_slots=0, alpha_s=0.0, m_s=0, entry_ids=None, n_entry=0,
+                     stream=None):
+    p = SearchParams(k=k, ef=ef, mode=mode, expansions_per_step=expansions_per_step, visited_slots=visited_slots,
+                     alpha_s=alpha_s, m_s=m_s)
     _check(_lib.ann_search_batch(index, _ptr(q), nq, ctypes.byref(p), _ptr(entry_ids), n_entry, _ptr(out_ids),
                                  _ptr(out_keys), _ptr(out_idot), _ptr(out_counts), stream))
 

@@ -39,6 +39,7 @@ struct ann_index {
   uint32_t d = 0, degree = 0, metric = 0, n_levels = 0, entry_point = 0;
   float *vectors = nullptr;    // [n][d] or nullptr
   uint32_t *adjacency = nullptr;  // [n][degree]
+  float *labels = nullptr;        // [n][degree] edge labels or nullptr
   ann::LevelDev level[ANN_MAX_LEVELS];
   ann::Workspace ws[ANN_MAX_LEVELS];
   int device = 0;

@@ -41,15 +41,30 @@ __global__ void pack_codes_kernel(const uint8_t *__restrict__ in, uint8_t *__res
 }
 
 // CSR -> [n][degree] with padding; sets *bad if a row is too long.
-__global__ void pack_csr_kernel(const uint32_t *__restrict__ cols, const uint64_t *__restrict__ offsets,
-                                uint32_t *__restrict__ out, uint64_t n, uint32_t degree, uint32_t *bad) {
+template <typename T>
+__global__ void pack_csr_kernel(const T *__restrict__ cols, const uint64_t *__restrict__ offsets,
+                                T *__restrict__ out, uint64_t n, uint32_t degree, T pad, uint32_t *bad) {
   uint64_t total = n * degree;
   for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < total; e += (uint64_t)gridDim.x * blockDim.x) {
     uint64_t i = e / degree;
     uint32_t t = (uint32_t)(e - i * degree);
     uint64_t b = offsets[i], len = offsets[i + 1] - b;
     if (t == 0 && len > degree) atomicOr(bad, 1u);
-    out[e] = (t < len) ? cols[b + t] : ANN_PAD_ID;
+    out[e] = (t < len) ? cols[b + t] : pad;
+  }
+}
+
+// A row must not name the same neighbour twice.
+__global__ void check_rows_distinct_kernel(const uint32_t *__restrict__ adj, uint64_t n, uint32_t degree,
+                                           uint32_t *bad) {
+  for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) {
+    const uint32_t *row = adj + i * degree;
+    for (uint32_t t = 1; t < degree; ++t) {
+      const uint32_t v = row[t];
+      if (v == ANN_PAD_ID) continue;
+      for (uint32_t u = 0; u < t; ++u)
+        if (row[u] == v) atomicOr(bad, 4u);
+    }
   }
 }
 
@@ -85,6 +100,7 @@ void destroy(ann_index *ix) {
   if (!ix) return;
   (void)hipFree(ix->vectors);
   (void)hipFree(ix->adjacency);
+  (void)hipFree(ix->labels);
   for (int l = 0; l < ANN_MAX_LEVELS; ++l) {
     (void)hipFree(ix->level[l].codes);
     (void)hipFree(ix->level[l].lo);
@@ -167,11 +183,13 @@ ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index 
   uint8_t *raw_codes = nullptr;
   uint32_t *raw_cols = nullptr;
   uint64_t *raw_offs = nullptr;
+  float *raw_labels = nullptr;
   auto cleanup = [&](ann_status r) {
     (void)hipFree(bad_dev);
     (void)hipFree(raw_codes);
     (void)hipFree(raw_cols);
     (void)hipFree(raw_offs);
+    (void)hipFree(raw_labels);
     if (r != ANN_OK) destroy(ix);
     return r;
   };
@@ -237,11 +255,26 @@ ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index 
       cols = raw_cols;
     }
     ANN_TRY_HIP(hipMalloc((void **)&ix->adjacency, total_adj * sizeof(uint32_t)));
-    pack_csr_kernel<<<grid_for(total_adj, 256), 256, 0, st>>>(cols, offs, ix->adjacency, n, desc->degree, bad_dev);
+    pack_csr_kernel<uint32_t><<<grid_for(total_adj, 256), 256, 0, st>>>(cols, offs, ix->adjacency, n, desc->degree,
+                                                                         ANN_PAD_ID, bad_dev);
     ANN_TRY_HIP(hipGetLastError());
+    if (desc->edge_labels) {
+      const float *lab = desc->edge_labels;
+      if (host) {
+        ANN_TRY(dev_copy(&raw_labels, desc->edge_labels, (size_t)nnz, true, st));
+        lab = raw_labels;
+      }
+      ANN_TRY_HIP(hipMalloc((void **)&ix->labels, total_adj * sizeof(float)));
+      pack_csr_kernel<float><<<grid_for(total_adj, 256), 256, 0, st>>>(lab, offs, ix->labels, n, desc->degree, 0.0f,
+                                                                        bad_dev);
+      ANN_TRY_HIP(hipGetLastError());
+    }
   } else {
     ANN_TRY(dev_copy(&ix->adjacency, desc->adjacency, (size_t)total_adj, host, st));
+    if (desc->edge_labels) ANN_TRY(dev_copy(&ix->labels, desc->edge_labels, (size_t)total_adj, host, st));
   }
+  check_rows_distinct_kernel<<<grid_for(n, 256), 256, 0, st>>>(ix->adjacency, n, desc->degree, bad_dev);
+  ANN_TRY_HIP(hipGetLastError());
   check_adjacency_kernel<<<grid_for(total_adj, 256), 256, 0, st>>>(ix->adjacency, total_adj, n, bad_dev);
   ANN_TRY_HIP(hipGetLastError());
   uint32_t bad = 0;
@@ -249,6 +282,7 @@ ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index 
   ANN_TRY_HIP(hipStreamSynchronize(st));
   if (bad & 1u) return cleanup(fail(ANN_EINVAL, "a CSR row has more than degree = %u neighbours", desc->degree));
   if (bad & 2u) return cleanup(fail(ANN_EINVAL, "adjacency holds a neighbour id >= n"));
+  if (bad & 4u) return cleanup(fail(ANN_EINVAL, "an adjacency row names the same neighbour twice"));
 #undef ANN_TRY
 #undef ANN_TRY_HIP
   cleanup(ANN_OK);

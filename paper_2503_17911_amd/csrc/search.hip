@@ -41,12 +41,16 @@ struct SearchArgs {
   const float *qlo;
   const int32_t *sum_t;
   const uint32_t *entry_ids;
+  const float *labels;  // [n][degree] edge labels or nullptr
   uint32_t *out_ids;
   float *out_keys;
   int32_t *out_idot;
   uint32_t *out_counts;
   uint64_t n;
   uint32_t row_stride, n_chunks, degree, metric, tq_stride, n_entry, entry_point, ef, vis_log2, nq, p;
+  uint32_t filtered;  // the label test and/or the per-expansion cap m_s is active
+  uint32_t m_s;
+  float alpha_s;
 };
 
 __device__ __forceinline__ uint64_t pack64(uint32_t hi, uint32_t lo) { return ((uint64_t)hi << 32) | lo; }
@@ -133,6 +137,19 @@ struct SearchWave {
       uint32_t old = atomicCAS(&vis[slot], kEmpty, id);
       if (old == kEmpty) return true;
       if (old == id) return false;
+      slot = (slot + stride) & vis_mask;
+    }
+  }
+
+  // Membership test without insertion.
+  __device__ __forceinline__ bool lookup(uint32_t id) {
+    const uint32_t h = id * 0x9E3779B1u;
+    uint32_t slot = h >> vis_shift;
+    const uint32_t stride = ((h >> 4) | 1u) & vis_mask;
+    for (;;) {
+      const uint32_t cur = vis[slot];
+      if (cur == id) return true;
+      if (cur == kEmpty) return false;
       slot = (slot + stride) & vis_mask;
     }
   }
@@ -255,6 +272,21 @@ struct SearchWave {
   __device__ __forceinline__ void filter_ids(uint32_t nb, int &n_cand) {
     const bool valid = nb != kEmpty && nb < a.n;
     const bool fresh = valid && test_and_set(nb);
+    const uint64_t fm = __ballot(fresh);
+    if (fresh) cand[n_cand + lanes_below(fm)] = nb;
+    n_cand += __popcll(fm);
+  }
+
+  // The same with the cap of Algorithm 1's inner condition |N| < m_s: only the
+  // first m_s unvisited ids (in lane = stored order) are taken and marked;
+  // the others stay unvisited.
+  __device__ __forceinline__ void filter_ids_capped(uint32_t nb, uint32_t m_s, int &n_cand) {
+    const bool valid = nb != kEmpty && nb < a.n;
+    const bool open = valid && !lookup(nb);
+    const uint64_t om = __ballot(open);
+    const bool take = open && (uint32_t)lanes_below(om) < m_s;
+    __syncthreads();
+    const bool fresh = take && test_and_set(nb);
     const uint64_t fm = __ballot(fresh);
     if (fresh) cand[n_cand + lanes_below(fm)] = nb;
     n_cand += __popcll(fm);
@@ -388,7 +420,24 @@ struct SearchWave {
       if (PMAX > 1 && n_vis + (uint32_t)(got * kWave) > vis_limit) rebuild_table();
 
       int n_cand = 0;
-      if (PMAX > 1 && a.degree <= 32) {
+      if (a.filtered) {
+        // label test and per-expansion cap: rows one after the other, in
+        // the order of the picked entries
+        for (int e = 0; e < got; ++e) {
+          const uint32_t uid = __builtin_amdgcn_readlane(picked, e);
+          uint32_t nb = kEmpty;
+          if (lane < (int)a.degree) {
+            const uint64_t at = (uint64_t)uid * a.degree + lane;
+            nb = a.adjacency[at];
+            if (a.labels && !(a.labels[at] <= a.alpha_s)) nb = kEmpty;
+          }
+          if (PMAX == 1) {
+            const uint32_t incoming = (uint32_t)__popcll(__ballot(nb != kEmpty));
+            if (n_vis + incoming > vis_limit) rebuild_table();
+          }
+          filter_ids_capped(nb, a.m_s, n_cand);
+        }
+      } else if (PMAX > 1 && a.degree <= 32) {
         // two adjacency rows per pass: lanes 0-31 take one, lanes 32-63 the next
         const int slot = lane & 31;
         uint32_t rows[PMAX / 2 > 0 ? PMAX / 2 : 1];
@@ -535,7 +584,9 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   if (params->k == 0) return fail(ANN_EINVAL, "ann_search_batch: k == 0");
   if (params->ef < params->k) return fail(ANN_EINVAL, "ann_search_batch: ef = %u < k = %u", params->ef, params->k);
   if (params->ef > ANN_MAX_EF) return fail(ANN_ECAPACITY, "ann_search_batch: ef = %u exceeds ANN_MAX_EF = %u", params->ef, ANN_MAX_EF);
-  if (params->reserved[0] || params->reserved[1] || params->reserved[2]) return fail(ANN_EINVAL, "ann_search_batch: reserved fields must be zero");
+  if (params->reserved) return fail(ANN_EINVAL, "ann_search_batch: reserved field must be zero");
+  if (!(params->alpha_s >= 0.0f)) return fail(ANN_EINVAL, "ann_search_batch: alpha_s must be >= 0");
+  if (params->alpha_s > 0.0f && !index->labels) return fail(ANN_EINVAL, "ann_search_batch: alpha_s given but the index was uploaded without edge labels");
   if (params->mode > 1) return fail(ANN_EINVAL, "ann_search_batch: unknown mode %u", params->mode);
   if (params->mode == 0 && params->expansions_per_step > 1) return fail(ANN_EINVAL, "ann_search_batch: expansions_per_step needs mode 1");
   if (params->expansions_per_step > (uint32_t)kMaxExpansionsPerStep) return fail(ANN_ECAPACITY, "ann_search_batch: expansions_per_step = %u exceeds %d", params->expansions_per_step, kMaxExpansionsPerStep);
@@ -578,6 +629,10 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   a.qlo = w.qlo;
   a.sum_t = w.sum_t;
   a.entry_ids = entry_ids;
+  a.labels = params->alpha_s > 0.0f ? index->labels : nullptr;
+  a.alpha_s = params->alpha_s;
+  a.m_s = params->m_s == 0 || params->m_s > index->degree ? index->degree : params->m_s;
+  a.filtered = (a.labels != nullptr || a.m_s < index->degree) ? 1u : 0u;
   a.out_ids = out_ids;
   a.out_keys = out_keys;
   a.out_idot = out_idot;

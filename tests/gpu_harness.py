@@ -48,7 +48,7 @@ def gpu_sq_fit(X, bits):
 class GpuIndex:
     """Device index built from numpy arrays (oracle-encoded or GPU-encoded levels)."""
 
-    def __init__(self, X, adj, entry, levels, metric, csr=None, host_pointers=False):
+    def __init__(self, X, adj, entry, levels, metric, csr=None, host_pointers=False, labels=None):
         self.n, self.d = X.shape
         self.metric = metric
         keep = []
@@ -66,6 +66,7 @@ class GpuIndex:
             item = (L.bits, conv_u8(L.codes), conv_f(L.lo), conv_f(L.delta), conv_f(L.norm_term))
             keep.append(item)
             lv.append(item)
+        lab = None if labels is None else conv_f(labels)
         if csr is not None:
             offsets, cols, degree = csr
             offs = np.ascontiguousarray(offsets, np.uint64)
@@ -74,12 +75,12 @@ class GpuIndex:
             self.degree = degree
             self.handle = ann.ann_upload_index(n=self.n, d=self.d, degree=degree, metric=metric, vectors=xv,
                                                levels=lv, adjacency=cols_d, csr_offsets=offs_d, entry_point=entry,
-                                               host_pointers=host_pointers, stream=stream_ptr())
+                                               edge_labels=lab, host_pointers=host_pointers, stream=stream_ptr())
         else:
             self.degree = adj.shape[1]
             adj_d = conv_u32(adj)
             self.handle = ann.ann_upload_index(n=self.n, d=self.d, degree=self.degree, metric=metric, vectors=xv,
-                                               levels=lv, adjacency=adj_d, entry_point=entry,
+                                               levels=lv, adjacency=adj_d, entry_point=entry, edge_labels=lab,
                                                host_pointers=host_pointers, stream=stream_ptr())
         torch.cuda.synchronize()
 

@@ -61,6 +61,9 @@ def test_host_side_argument_checks():
         ann.ann_search_batch(1, 1, 1, k=10, ef=64, out_ids=1, visited_slots=128)
     assert "minimum" in str(e.value)
     with pytest.raises(ann.AnnError) as e:
+        ann.ann_search_batch(1, 1, 1, k=10, ef=64, out_ids=1, alpha_s=-1.0)
+    assert "alpha_s" in str(e.value)
+    with pytest.raises(ann.AnnError) as e:
         ann.ann_bruteforce_topk(1, 100, 8, 1, 1, 300, 0, 1, 1)
     assert e.value.status == ann.ECAPACITY
     with pytest.raises(ann.AnnError) as e:

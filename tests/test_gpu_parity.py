@@ -145,6 +145,79 @@ def test_multi_expansion_matches_the_batched_oracle(H, n, d, R, nq, metric, bits
     ix.close()
 
 
+def test_upload_rejects_bad_graphs(H):
+    import paper_2503_17911_amd as ann
+    w, X, Q, adj = small_case(200, 16, 6, 2, seed=4)
+    lv = oracle.sq_fit(X, 8)
+    bad = adj.copy()
+    bad[7, :] = PAD
+    bad[7, 0] = bad[7, 1] = 3                    # the same neighbour twice
+    with pytest.raises(ann.AnnError) as e:
+        H.GpuIndex(X, bad, 0, [lv], oracle.L2)
+    assert e.value.status == ann.EINVAL and "twice" in str(e.value)
+    bad = adj.copy()
+    bad[9, 0] = 200                              # not a node
+    with pytest.raises(ann.AnnError) as e:
+        H.GpuIndex(X, bad, 0, [lv], oracle.L2)
+    assert e.value.status == ann.EINVAL
+
+
+def test_label_filter_paper_example_on_gpu(H):
+    """Section 4.3 worked example (5 neighbours, m_s = 3, alpha_s = 1.2, second
+    label 1.4 -> x1, x3, x4 are visited), through the C ABI."""
+    from conftest import read_golden
+    g = read_golden("label_filter_example.txt")
+    n = 6
+    X = np.zeros((n, 2), np.float32)
+    X[:, 0] = np.arange(n)
+    adj = np.full((n, 5), PAD, np.uint32)
+    adj[0] = [1, 2, 3, 4, 5]
+    labels = np.ones((n, 5), np.float32)
+    labels[0] = [float(v) for v in g["labels"]]
+    lv = oracle.sq_fit(X, 8)
+    q = np.array([[0.0, 0.0]], np.float32)
+    ix = H.GpuIndex(X, adj, 0, [lv], oracle.L2, labels=labels)
+    ids, _, _, cnt = ix.search(q, 8, alpha_s=float(g["alpha_s"][0]), m_s=int(g["m_s"][0]))
+    assert sorted(int(v) for v in ids[0] if v != PAD and v != 0) == [int(v) for v in g["visited"]]
+    assert cnt[0, 1] == 1 + len(g["visited"])
+    ix.close()
+
+
+@pytest.mark.parametrize("mode,P", [(0, 1), (1, 2), (1, 4)])
+def test_label_filter_and_degree_cap_match_the_oracle(H, mode, P):
+    n, d, R, nq = 3000, 64, 24, 30
+    w, X, Q, adj = small_case(n, d, R, nq, seed=123)
+    rng = np.random.default_rng(9)
+    labels = rng.choice([1.0, 1.1, 1.2, 1.4, 2.0], size=adj.shape).astype(np.float32)
+    lv = oracle.sq_fit(X, 8)
+    offsets = np.zeros(n + 1, np.uint64)
+    cols, labs = [], []
+    for i in range(n):
+        keep = adj[i] != PAD
+        cols.extend(adj[i][keep].tolist())
+        labs.extend(labels[i][keep].tolist())
+        offsets[i + 1] = len(cols)
+    for csr in (None, (offsets, np.array(cols, np.uint32), R)):
+        lab = labels if csr is None else np.array(labs, np.float32)
+        ix = H.GpuIndex(X, adj, 0, [lv], oracle.L2, labels=lab, csr=csr)
+        lab_full = labels.copy()
+        if csr is not None:                      # CSR rows are compacted to the front
+            lab_full = np.zeros_like(labels)
+            adj_c = np.full_like(adj, PAD)
+            for i in range(n):
+                keep = adj[i] != PAD
+                adj_c[i, :keep.sum()] = adj[i][keep]
+                lab_full[i, :keep.sum()] = labels[i][keep]
+        else:
+            adj_c = adj
+        for alpha_s, m_s in ((1.2, 0), (0.0, 5), (1.4, 7), (2.0, 1)):
+            kw = dict(labels=lab_full, alpha_s=alpha_s) if alpha_s > 0 else {}
+            orc = oracle.search_batch(lv, d, adj_c, 0, Q, 48, m_s=m_s, expansions_per_step=P, **kw)
+            gpu = ix.search(Q, 48, mode=mode, expansions_per_step=P if mode else 0, alpha_s=alpha_s, m_s=m_s)
+            assert_search_equal(gpu, orc)
+        ix.close()
+
+
 def test_search_with_per_query_entries_and_csr_upload(H):
     n, d, R, nq = 2000, 64, 16, 25
     w, X, Q, adj = small_case(n, d, R, nq, seed=77)
