@@ -172,6 +172,22 @@ ann_status ann_query_prep(ann_index *index, uint32_t level, const float *q, uint
                           float *qlo, void *stream);
 
 /*
+ * Entry-point stage: per-query initial nodes I for Algorithm 1 (which takes
+ * "initial nodes I" as an input).  ann_build_entry_table samples n_pivots base
+ * vectors, node floor(i * n / n_pivots) for i = 0..n_pivots-1, and keeps a
+ * compact copy of their level-0 codes in the index (synchronous; replaces an
+ * earlier table).  ann_entry_scan evaluates the traversal distance tau_l of
+ * every pivot for every query and writes the n_entry (<= 4) closest pivots'
+ * node ids, in ascending (key, id) order, to out_entry_ids [nq][n_entry]
+ * (padded with ANN_PAD_ID if n_pivots < n_entry) - ready to be passed to
+ * ann_search_batch as entry_ids.  Errors: ANN_EINVAL (NULL arguments, n_pivots
+ * outside [1, n], no table built), ANN_ECAPACITY (n_entry > 4), ANN_ENOMEM.
+ */
+ann_status ann_build_entry_table(ann_index *index, uint32_t n_pivots, void *stream);
+ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_t n_entry,
+                          uint32_t *out_entry_ids, void *stream);
+
+/*
  * Algorithm 1 ("Deterministic Access Greedy Search") for a batch of queries,
  * up to but excluding the final rerank: returns the whole final pool.
  *   q          [nq][d] fp32.

@@ -51,10 +51,11 @@ def _load():
                                          _f32p, _i32, _u32p, _i32, _i32, _f32p, _f32, _i32, _i32, _u32p, _f32p, _i32p, _u32p]
         lib.orc_rescore_batch.argtypes = [_i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _f32p, _i32, _u32p, _i32,
                                           _u32p, _f32p, _i32p]
+        lib.orc_entry_scan.argtypes = [_i64, _i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _f32p, _i32, _i32, _i32, _u32p]
         lib.orc_rerank_batch.argtypes = [_f32p, _i32, _i32, _f32p, _i32, _u32p, _i32, _i32, _u32p, _f32p]
         lib.orc_bruteforce_topk.argtypes = [_f32p, _i64, _i32, _i32, _f32p, _i32, _i32, _u32p, _f64p]
         for name in ("orc_sq_train", "orc_sq_encode", "orc_sq_decode", "orc_query_prep", "orc_search_batch",
-                     "orc_rescore_batch", "orc_rerank_batch", "orc_bruteforce_topk"):
+                     "orc_rescore_batch", "orc_rerank_batch", "orc_bruteforce_topk", "orc_entry_scan"):
             getattr(lib, name).restype = None
         _lib = lib
     return _lib
@@ -153,6 +154,17 @@ def search_batch(level: SQLevel, d, adjacency, entry_point, Q, ef, metric=L2, en
                              float(alpha_s), int(m_s), int(expansions_per_step), _p(ids, _u32p),
                              _p(keys, _f32p), _p(dots, _i32p), _p(counts, _u32p))
     return ids, keys, dots, counts
+
+
+def entry_scan(level: SQLevel, d, Q, n_pivots, n_entry, metric=L2):
+    """Per-query initial nodes: the n_entry closest (tau_l) of n_pivots evenly spaced base nodes."""
+    Q = _c(Q, np.float32)
+    nq = Q.shape[0]
+    out = np.empty((nq, n_entry), np.uint32)
+    _load().orc_entry_scan(level.codes.shape[0], d, metric, level.bits, _p(level.codes, _u8p), _p(level.lo, _f32p),
+                           _p(level.delta, _f32p), _p(level.norm_term, _f32p), _p(Q, _f32p), nq, n_pivots, n_entry,
+                           _p(out, _u32p))
+    return out
 
 
 def rescore_batch(level: SQLevel, d, Q, cand_ids, metric=L2):

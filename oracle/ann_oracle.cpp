@@ -298,6 +298,29 @@ void orc_rescore_batch(int32_t d, int32_t metric, int32_t bits, const uint8_t *c
   }
 }
 
+// ---------------------------------------------------------------- entry points
+// Initial nodes I of Algorithm 1 chosen per query: among the n_pivots sampled
+// nodes floor(i * n / n_pivots), the n_entry with the smallest (tau_l key, id).
+void orc_entry_scan(int64_t n, int32_t d, int32_t metric, int32_t bits, const uint8_t *codes, const float *lo,
+                    const float *delta, const float *norm_term, const float *Q, int32_t nq, int32_t n_pivots,
+                    int32_t n_entry, uint32_t *out_ids) {
+  const int rb = row_bytes(d, bits);
+  std::vector<int8_t> t(d);
+  std::vector<Entry> all;
+  for (int32_t qi = 0; qi < nq; ++qi) {
+    float s, qlo;
+    orc_query_prep(Q + (int64_t)qi * d, d, lo, delta, t.data(), &s, &qlo);
+    all.clear();
+    for (int64_t i = 0; i < n_pivots; ++i) {
+      const int64_t v = i * n / n_pivots;
+      const int32_t idot = orc_idot(t.data(), codes + v * rb, d, bits);
+      all.push_back({key_from_idot(metric, s, qlo, idot, norm_term ? norm_term[v] : 0.0f), (uint32_t)v, idot, false});
+    }
+    std::sort(all.begin(), all.end(), entry_less);
+    for (int e = 0; e < n_entry; ++e) out_ids[(int64_t)qi * n_entry + e] = e < (int)all.size() ? all[e].id : kPad;
+  }
+}
+
 // ---------------------------------------------------------------- rerank
 // High-precision distance tau_h on the original vectors (fp64 accumulation,
 // rounded once to fp32) for the given candidates; sort by (distance, id);

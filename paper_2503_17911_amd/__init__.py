@@ -26,8 +26,8 @@ OK, EINVAL, ENOMEM, EDEVICE, EUNSUPPORTED, ECAPACITY = range(6)
 _STATUS_NAMES = ["ANN_OK", "ANN_EINVAL", "ANN_ENOMEM", "ANN_EDEVICE", "ANN_EUNSUPPORTED", "ANN_ECAPACITY"]
 
 EXPORTED_SYMBOLS = ["ann_sq_train", "ann_sq_encode", "ann_upload_index", "ann_free_index", "ann_query_prep",
-                    "ann_search_batch", "ann_rescore", "ann_rerank", "ann_bruteforce_topk", "ann_last_error",
-                    "ann_version"]
+                    "ann_search_batch", "ann_rescore", "ann_rerank", "ann_bruteforce_topk", "ann_build_entry_table",
+                    "ann_entry_scan", "ann_last_error", "ann_version"]
 
 
 class AnnError(RuntimeError):
@@ -69,6 +69,8 @@ def _load_library() -> ctypes.CDLL:
     lib.ann_rescore.argtypes = [vp, u32, vp, u32, vp, u32, u32, vp, vp, vp, vp]
     lib.ann_rerank.argtypes = [vp, vp, u32, vp, u32, u32, u32, vp, vp, vp]
     lib.ann_bruteforce_topk.argtypes = [vp, u64, u32, vp, u32, u32, u32, vp, vp, vp]
+    lib.ann_build_entry_table.argtypes = [vp, u32, vp]
+    lib.ann_entry_scan.argtypes = [vp, vp, u32, u32, vp, vp]
     for name in EXPORTED_SYMBOLS[:-2]:
         getattr(lib, name).restype = i32
     lib.ann_last_error.restype = ctypes.c_char_p
@@ -162,6 +164,14 @@ def ann_rescore(index, level, q, nq, cand_ids, n_cand, cand_stride, out_ids, out
 def ann_rerank(index, q, nq, cand_ids, n_cand, cand_stride, k, out_ids, out_dist, stream=None):
     _check(_lib.ann_rerank(index, _ptr(q), nq, _ptr(cand_ids), n_cand, cand_stride, k, _ptr(out_ids),
                            _ptr(out_dist), stream))
+
+
+def ann_build_entry_table(index, n_pivots, stream=None):
+    _check(_lib.ann_build_entry_table(index, n_pivots, stream))
+
+
+def ann_entry_scan(index, q, nq, n_entry, out_entry_ids, stream=None):
+    _check(_lib.ann_entry_scan(index, _ptr(q), nq, n_entry, _ptr(out_entry_ids), stream))
 
 
 def ann_bruteforce_topk(x, n, d, q, nq, k, metric, out_ids, out_dist, stream=None):

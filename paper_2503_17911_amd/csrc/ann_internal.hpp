@@ -40,6 +40,10 @@ struct ann_index {
   float *vectors = nullptr;    // [n][d] or nullptr
   uint32_t *adjacency = nullptr;  // [n][degree]
   float *labels = nullptr;        // [n][degree] edge labels or nullptr
+  uint8_t *pivot_codes = nullptr;  // entry-point stage: [n_pivots][row_stride] level-0 codes of the sampled nodes
+  float *pivot_norm = nullptr;     // [n_pivots] their norm terms (L2)
+  uint32_t *pivot_ids = nullptr;   // [n_pivots] their node ids
+  uint32_t n_pivots = 0;
   ann::LevelDev level[ANN_MAX_LEVELS];
   ann::Workspace ws[ANN_MAX_LEVELS];
   int device = 0;

@@ -1,0 +1,164 @@
+// Entry-point stage: choose the initial nodes I of Algorithm 1 per query.
+// The paper takes I as an input of the search ("initial nodes I"); a fixed
+// sample of base vectors (pivots) is scanned with the same low-precision
+// distance tau_l as the traversal, and the closest few become the query's
+// initial nodes.  One query per wavefront; the pivot codes are a compact copy,
+// read sequentially.
+#include "ann_internal.hpp"
+#include "device_utils.hpp"
+
+namespace ann {
+
+constexpr int kScanKeep = 4;  // best pivots kept per lane and returned at most
+
+__device__ __forceinline__ uint64_t pack_ki(uint32_t hi, uint32_t lo) { return ((uint64_t)hi << 32) | lo; }
+
+template <int BITS, int LPR>
+__global__ __launch_bounds__(64) void entry_scan_kernel(const uint8_t *__restrict__ pcodes,
+                                                        const float *__restrict__ pnorm,
+                                                        const uint32_t *__restrict__ pids, uint32_t n_pivots,
+                                                        uint32_t row_stride, uint32_t n_chunks, uint32_t metric,
+                                                        const uint8_t *__restrict__ tq, uint32_t tq_stride,
+                                                        const float *__restrict__ s_arr,
+                                                        const float *__restrict__ qlo_arr,
+                                                        const int32_t *__restrict__ sum_t, uint32_t nq,
+                                                        uint32_t n_entry, uint32_t *__restrict__ out) {
+  constexpr int G = kWave / LPR, CPL = 4, TQW = TqRegs<BITS>::kWords;
+  __shared__ uint64_t list[kWave * kScanKeep];
+  const uint32_t qi = blockIdx.x;
+  if (qi >= nq) return;
+  const int lane = threadIdx.x, sub = lane % LPR, grp = lane / LPR;
+  int tqr[CPL][TQW];
+  uint32_t coff[CPL];
+#pragma unroll
+  for (int j = 0; j < CPL; ++j) {
+    const uint32_t c = (uint32_t)(sub + j * LPR);
+    coff[j] = (c < n_chunks ? c : n_chunks - 1) * 16u;
+    const int *tqp = reinterpret_cast<const int *>(tq + (uint64_t)qi * tq_stride + c * (TQW * 4u));
+#pragma unroll
+    for (int w = 0; w < TQW; ++w) tqr[j][w] = tqp[w];
+  }
+  const float s = s_arr[qi], qlo = qlo_arr[qi];
+  const int bias = BITS == 8 ? 128 * sum_t[qi] : 0;
+  uint64_t best[kScanKeep];
+#pragma unroll
+  for (int t = 0; t < kScanKeep; ++t) best[t] = ~0ull;
+  for (uint32_t base = 0; base < n_pivots; base += G) {
+    const uint32_t pi = base + grp;
+    const uint32_t pc = pi < n_pivots ? pi : n_pivots - 1;
+    const uint8_t *rp = pcodes + (uint64_t)pc * row_stride;
+    int dot = 0;
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) dot += chunk_dot<BITS>(*reinterpret_cast<const uint4 *>(rp + coff[j]), tqr[j]);
+    dot = group_sum_i32<LPR>(dot) + bias;
+    const float key = key_from_idot(metric, s, qlo, dot, pnorm ? pnorm[pc] : 0.0f);
+    uint64_t c = (sub == 0 && pi < n_pivots) ? pack_ki(order_u32(key), pids[pc]) : ~0ull;
+    // sorted insertion into this lane's short list
+#pragma unroll
+    for (int t = 0; t < kScanKeep; ++t) {
+      const uint64_t lo = c < best[t] ? c : best[t];
+      c = c < best[t] ? best[t] : c;
+      best[t] = lo;
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < kScanKeep; ++t) list[lane * kScanKeep + t] = best[t];
+  __syncthreads();
+  // rank the 256 survivors; (key, id) pairs are distinct except for the all-ones filler
+  for (int i = lane; i < kWave * kScanKeep; i += kWave) {
+    const uint64_t e = list[i];
+    uint32_t rank = 0;
+    for (int j = 0; j < kWave * kScanKeep; ++j) {
+      const uint64_t o = list[j];
+      rank += (o < e || (o == e && j < i)) ? 1u : 0u;
+    }
+    if (rank < n_entry) out[(uint64_t)qi * n_entry + rank] = e == ~0ull ? ANN_PAD_ID : (uint32_t)e;
+  }
+}
+
+__global__ void gather_pivots_kernel(const uint8_t *__restrict__ codes, const float *__restrict__ norm,
+                                     uint64_t n, uint32_t n_pivots, uint32_t row_stride,
+                                     uint8_t *__restrict__ pcodes, float *__restrict__ pnorm,
+                                     uint32_t *__restrict__ pids) {
+  const uint64_t total = (uint64_t)n_pivots * (row_stride / 16);
+  for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < total; e += (uint64_t)gridDim.x * blockDim.x) {
+    const uint32_t p = (uint32_t)(e / (row_stride / 16)), c = (uint32_t)(e % (row_stride / 16));
+    const uint64_t id = (uint64_t)p * n / n_pivots;  // evenly spaced sample of the base set
+    reinterpret_cast<uint4 *>(pcodes)[e] = reinterpret_cast<const uint4 *>(codes + id * row_stride)[c];
+    if (c == 0) {
+      pids[p] = (uint32_t)id;
+      if (pnorm) pnorm[p] = norm[id];
+    }
+  }
+}
+
+}  // namespace ann
+
+using namespace ann;
+
+extern "C" {
+
+ann_status ann_build_entry_table(ann_index *index, uint32_t n_pivots, void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  if (!index) return fail(ANN_EINVAL, "ann_build_entry_table: index is NULL");
+  if (n_pivots == 0 || n_pivots > index->n) return fail(ANN_EINVAL, "ann_build_entry_table: n_pivots must be in [1, n]");
+  ANN_HIP(hipDeviceSynchronize());
+  (void)hipFree(index->pivot_codes);
+  (void)hipFree(index->pivot_norm);
+  (void)hipFree(index->pivot_ids);
+  index->pivot_codes = nullptr;
+  index->pivot_norm = nullptr;
+  index->pivot_ids = nullptr;
+  index->n_pivots = 0;
+  const LevelDev &L = index->level[0];
+  ANN_HIP(hipMalloc((void **)&index->pivot_codes, (size_t)n_pivots * L.row_stride));
+  ANN_HIP(hipMalloc((void **)&index->pivot_ids, (size_t)n_pivots * sizeof(uint32_t)));
+  if (index->metric == ANN_L2) ANN_HIP(hipMalloc((void **)&index->pivot_norm, (size_t)n_pivots * sizeof(float)));
+  const uint64_t total = (uint64_t)n_pivots * (L.row_stride / 16);
+  const int grid = (int)((total + 255) / 256 > 65535 ? 65535 : (total + 255) / 256);
+  gather_pivots_kernel<<<grid, 256, 0, st>>>(L.codes, index->metric == ANN_L2 ? L.norm_term : nullptr, index->n, n_pivots,
+                                             L.row_stride, index->pivot_codes, index->pivot_norm, index->pivot_ids);
+  ANN_HIP(hipGetLastError());
+  ANN_HIP(hipStreamSynchronize(st));
+  index->n_pivots = n_pivots;
+  return ANN_OK;
+}
+
+ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_t n_entry, uint32_t *out_entry_ids,
+                          void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  if (!index || !q || !out_entry_ids) return fail(ANN_EINVAL, "ann_entry_scan: NULL argument");
+  if (index->n_pivots == 0) return fail(ANN_EINVAL, "ann_entry_scan: call ann_build_entry_table first");
+  if (nq == 0 || n_entry == 0) return fail(ANN_EINVAL, "ann_entry_scan: nq and n_entry must be positive");
+  if (n_entry > (uint32_t)kScanKeep) return fail(ANN_ECAPACITY, "ann_entry_scan: n_entry = %u exceeds %d", n_entry, kScanKeep);
+  ann_status rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st);
+  if (rc != ANN_OK) return rc;
+  const LevelDev &L = index->level[0];
+  const Workspace &w = index->ws[0];
+#define ANN_ES(B, P)                                                                                                   \
+  entry_scan_kernel<B, P><<<nq, 64, 0, st>>>(index->pivot_codes, index->pivot_norm, index->pivot_ids, index->n_pivots,   \
+                                             L.row_stride, L.row_stride / 16, index->metric, w.tq, w.tq_stride, w.s,    \
+                                             w.qlo, w.sum_t, nq, n_entry, out_entry_ids)
+  if (L.bits == 8) {
+    switch (L.search_lanes) {
+      case 1: ANN_ES(8, 1); break;
+      case 2: ANN_ES(8, 2); break;
+      case 4: ANN_ES(8, 4); break;
+      case 8: ANN_ES(8, 8); break;
+      default: ANN_ES(8, 16); break;
+    }
+  } else {
+    switch (L.search_lanes) {
+      case 1: ANN_ES(4, 1); break;
+      case 2: ANN_ES(4, 2); break;
+      case 4: ANN_ES(4, 4); break;
+      case 8: ANN_ES(4, 8); break;
+      default: ANN_ES(4, 16); break;
+    }
+  }
+#undef ANN_ES
+  ANN_HIP(hipGetLastError());
+  return ANN_OK;
+}
+
+}  // extern "C"

@@ -101,6 +101,9 @@ void destroy(ann_index *ix) {
   (void)hipFree(ix->vectors);
   (void)hipFree(ix->adjacency);
   (void)hipFree(ix->labels);
+  (void)hipFree(ix->pivot_codes);
+  (void)hipFree(ix->pivot_norm);
+  (void)hipFree(ix->pivot_ids);
   for (int l = 0; l < ANN_MAX_LEVELS; ++l) {
     (void)hipFree(ix->level[l].codes);
     (void)hipFree(ix->level[l].lo);

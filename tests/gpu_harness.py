@@ -122,6 +122,15 @@ class GpuIndex:
         torch.cuda.synchronize()
         return (as_u32(ids), keys.cpu().numpy(), dots.cpu().numpy() if want_idot else None, as_u32(counts))
 
+    def entry_scan(self, Q, n_pivots, n_entry):
+        nq = Q.shape[0]
+        ann.ann_build_entry_table(self.handle, n_pivots, stream_ptr())
+        qd = dev(Q)
+        out = torch.empty((nq, n_entry), dtype=torch.int32, device=DEV)
+        ann.ann_entry_scan(self.handle, qd, nq, n_entry, out, stream_ptr())
+        torch.cuda.synchronize()
+        return as_u32(out)
+
     def rescore(self, Q, cand, level=1):
         nq, n_cand = cand.shape
         qd, cd = dev(Q), u32(cand)

@@ -145,6 +145,23 @@ def test_multi_expansion_matches_the_batched_oracle(H, n, d, R, nq, metric, bits
     ix.close()
 
 
+@pytest.mark.parametrize("n,d,R,metric,bits", [(5000, 128, 32, "l2", 8), (2000, 960, 16, "l2", 4), (3000, 96, 32, "ip", 8),
+                                                 (300, 16, 4, "ip", 8)])
+def test_entry_scan_and_search_from_scanned_entries(H, n, d, R, metric, bits):
+    w, X, Q, adj = small_case(n, d, R, 20, seed=n + 7, metric=metric, bits=bits, normalize=(metric == "ip"))
+    m = metric_id(metric)
+    lv = oracle.sq_fit(X, bits)
+    ix = H.GpuIndex(X, adj, 0, [lv], m)
+    for P, E in ((257, 4), (n, 1), (3, 4)):
+        want = oracle.entry_scan(lv, d, Q, P, E, metric=m)
+        got = ix.entry_scan(Q, P, E)
+        assert (got == want).all()
+        orc = oracle.search_batch(lv, d, adj, 0, Q, 40, metric=m, entries=want)
+        gpu = ix.search(Q, 40, entries=got)
+        assert_search_equal(gpu, orc)
+    ix.close()
+
+
 def test_upload_rejects_bad_graphs(H):
     import paper_2503_17911_amd as ann
     w, X, Q, adj = small_case(200, 16, 6, 2, seed=4)

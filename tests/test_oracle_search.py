@@ -190,3 +190,18 @@ def test_rescore_resorts_with_finer_codes():
 def test_recall_definition():
     assert oracle.recall(np.array([[1, 2, 3, 4]]), np.array([[4, 3, 9, 8]])) == 0.5
     assert oracle.recall(np.array([[1, 2, PAD, PAD]]), np.array([[1, 2, 3, 4]])) == 0.5
+
+
+def test_entry_scan_is_bruteforce_over_the_pivot_sample():
+    w, X, Q, adj = small_case(500, 32, 6, 7, seed=41)
+    for metric, bits in ((oracle.L2, 8), (oracle.IP, 4)):
+        lv = oracle.sq_fit(X, bits)
+        for P, E in ((64, 3), (500, 4), (2, 4)):
+            got = oracle.entry_scan(lv, w.d, Q, P, E, metric=metric)
+            piv = [i * 500 // P for i in range(P)]
+            assert len(set(piv)) == P
+            for qi in range(len(Q)):
+                k = all_keys(lv, w.d, Q[qi], metric)
+                order = sorted((float(k[v]), v) for v in piv)[:E]
+                want = [v for _, v in order] + [PAD] * (E - len(order))
+                assert got[qi].tolist() == want
