@@ -145,6 +145,16 @@ typedef struct {
  */
 ann_status ann_sq_train(const float *x, uint64_t n, uint32_t d, uint32_t bits, float *lo, float *delta,
                         void *stream);
+/*
+ * Truncated scalar quantization (paper Appendix G: the range comes from
+ * percentile statistics rather than the extremes).  With a column sorted
+ * ascending, lo[j] is its element of rank k = floor((1 - coverage) * (n - 1))
+ * and the upper end its element of rank n - 1 - k (exact order statistics);
+ * coverage in (0.5, 1], 0.99 being the paper's choice, 1 the same as
+ * ann_sq_train.  ann_sq_encode clamps values outside the range.
+ */
+ann_status ann_sq_train_truncated(const float *x, uint64_t n, uint32_t d, uint32_t bits, double coverage,
+                                  float *lo, float *delta, void *stream);
 ann_status ann_sq_encode(const float *x, uint64_t n, uint32_t d, uint32_t bits, const float *lo,
                          const float *delta, uint8_t *codes, float *norm_term, void *stream);
 

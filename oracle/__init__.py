@@ -40,6 +40,7 @@ def _load():
         build()
         lib = ctypes.CDLL(str(_SO))
         lib.orc_sq_train.argtypes = [_f32p, _i64, _i32, _i32, _f32p, _f32p]
+        lib.orc_sq_train_truncated.argtypes = [_f32p, _i64, _i32, _i32, ctypes.c_double, _f32p, _f32p]
         lib.orc_sq_encode.argtypes = [_f32p, _i64, _i32, _i32, _f32p, _f32p, _u8p, _f32p]
         lib.orc_sq_decode.argtypes = [_u8p, _i64, _i32, _i32, _f32p, _f32p, _f32p]
         lib.orc_query_prep.argtypes = [_f32p, _i32, _f32p, _f32p, _i8p, _f32p, _f32p]
@@ -54,7 +55,7 @@ def _load():
         lib.orc_entry_scan.argtypes = [_i64, _i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _f32p, _i32, _i32, _i32, _u32p]
         lib.orc_rerank_batch.argtypes = [_f32p, _i32, _i32, _f32p, _i32, _u32p, _i32, _i32, _u32p, _f32p]
         lib.orc_bruteforce_topk.argtypes = [_f32p, _i64, _i32, _i32, _f32p, _i32, _i32, _u32p, _f64p]
-        for name in ("orc_sq_train", "orc_sq_encode", "orc_sq_decode", "orc_query_prep", "orc_search_batch",
+        for name in ("orc_sq_train", "orc_sq_train_truncated", "orc_sq_encode", "orc_sq_decode", "orc_query_prep", "orc_search_batch",
                      "orc_rescore_batch", "orc_rerank_batch", "orc_bruteforce_topk", "orc_entry_scan"):
             getattr(lib, name).restype = None
         _lib = lib
@@ -91,6 +92,14 @@ def sq_train(X, bits):
     return lo, delta
 
 
+def sq_train_truncated(X, bits, coverage):
+    X = _c(X, np.float32)
+    n, d = X.shape
+    lo, delta = np.empty(d, np.float32), np.empty(d, np.float32)
+    _load().orc_sq_train_truncated(_p(X, _f32p), n, d, bits, float(coverage), _p(lo, _f32p), _p(delta, _f32p))
+    return lo, delta
+
+
 def sq_encode(X, bits, lo, delta) -> SQLevel:
     X, lo, delta = _c(X, np.float32), _c(lo, np.float32), _c(delta, np.float32)
     n, d = X.shape
@@ -101,8 +110,8 @@ def sq_encode(X, bits, lo, delta) -> SQLevel:
     return SQLevel(bits, lo, delta, codes, norm)
 
 
-def sq_fit(X, bits) -> SQLevel:
-    lo, delta = sq_train(X, bits)
+def sq_fit(X, bits, coverage=1.0) -> SQLevel:
+    lo, delta = sq_train(X, bits) if coverage >= 1.0 else sq_train_truncated(X, bits, coverage)
     return sq_encode(X, bits, lo, delta)
 
 

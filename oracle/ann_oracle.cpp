@@ -89,6 +89,26 @@ void orc_sq_train(const float *X, int64_t n, int32_t d, int32_t bits, float *lo,
   }
 }
 
+// Truncated scalar quantization (App. G): the range of a dimension is taken
+// between two order statistics instead of the extremes, so that outliers do
+// not stretch the step.  With the column sorted ascending, lo_j is the element
+// of rank k = floor((1 - coverage) * (n - 1)) and the upper end the element of
+// rank n - 1 - k; coverage = 0.99 is the paper's "99th percentile", coverage =
+// 1 is orc_sq_train.  Values outside the range are clamped by the encoder.
+void orc_sq_train_truncated(const float *X, int64_t n, int32_t d, int32_t bits, double coverage, float *lo,
+                            float *delta) {
+  const float levels = (float)((1 << bits) - 1);
+  const int64_t k = (int64_t)std::floor((1.0 - coverage) * (double)(n - 1));
+  std::vector<float> col(n);
+  for (int j = 0; j < d; ++j) {
+    for (int64_t i = 0; i < n; ++i) col[i] = X[i * (int64_t)d + j];
+    std::sort(col.begin(), col.end());
+    const float mn = col[k], mx = col[n - 1 - k];
+    lo[j] = mn;
+    delta[j] = (mx > mn) ? (mx - mn) / levels : 1.0f;
+  }
+}
+
 // c_ij = clamp(floor((x - lo_j) / delta_j + 0.5), 0, 2^b - 1).  Also emits the
 // norm term B_i = sum_j decode(c_ij)^2 (fp64 accumulation in index order,
 // rounded once), the "one additional FLOAT32 per database vector" of Sec. 5.2.

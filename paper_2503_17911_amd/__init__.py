@@ -25,7 +25,7 @@ DESC_HOST_POINTERS = 1
 OK, EINVAL, ENOMEM, EDEVICE, EUNSUPPORTED, ECAPACITY = range(6)
 _STATUS_NAMES = ["ANN_OK", "ANN_EINVAL", "ANN_ENOMEM", "ANN_EDEVICE", "ANN_EUNSUPPORTED", "ANN_ECAPACITY"]
 
-EXPORTED_SYMBOLS = ["ann_sq_train", "ann_sq_encode", "ann_upload_index", "ann_free_index", "ann_query_prep",
+EXPORTED_SYMBOLS = ["ann_sq_train", "ann_sq_train_truncated", "ann_sq_encode", "ann_upload_index", "ann_free_index", "ann_query_prep",
                     "ann_search_batch", "ann_rescore", "ann_rerank", "ann_bruteforce_topk", "ann_build_entry_table",
                     "ann_entry_scan", "ann_last_error", "ann_version"]
 
@@ -61,6 +61,7 @@ def _load_library() -> ctypes.CDLL:
     lib = ctypes.CDLL(str(LIB_PATH))
     vp, u32, u64, i32 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int
     lib.ann_sq_train.argtypes = [vp, u64, u32, u32, vp, vp, vp]
+    lib.ann_sq_train_truncated.argtypes = [vp, u64, u32, u32, ctypes.c_double, vp, vp, vp]
     lib.ann_sq_encode.argtypes = [vp, u64, u32, u32, vp, vp, vp, vp, vp]
     lib.ann_upload_index.argtypes = [ctypes.POINTER(IndexDesc), vp, ctypes.POINTER(vp)]
     lib.ann_free_index.argtypes = [vp]
@@ -109,6 +110,10 @@ def ann_version() -> str:
 
 def ann_sq_train(x, n, d, bits, lo, delta, stream=None):
     _check(_lib.ann_sq_train(_ptr(x), n, d, bits, _ptr(lo), _ptr(delta), stream))
+
+
+def ann_sq_train_truncated(x, n, d, bits, coverage, lo, delta, stream=None):
+    _check(_lib.ann_sq_train_truncated(_ptr(x), n, d, bits, coverage, _ptr(lo), _ptr(delta), stream))
 
 
 def ann_sq_encode(x, n, d, bits, lo, delta, codes, norm_term, stream=None):

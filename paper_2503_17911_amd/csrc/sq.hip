@@ -1,6 +1,10 @@
 // Scalar quantization: codebook training, encoding, and query folding.
 // Paper Appendix G (SQ-b: uniform levels over the value range of a dimension)
 // and Section 5.2 (stored squared norm; query terms precomputed before search).
+#include <math.h>
+
+#include <vector>
+
 #include "ann_internal.hpp"
 #include "device_utils.hpp"
 
@@ -34,6 +38,65 @@ __global__ void sq_minmax_final_kernel(const float *__restrict__ pmin, const flo
     mn = fminf(mn, pmin[(uint64_t)b * d + j]);
     mx = fmaxf(mx, pmax[(uint64_t)b * d + j]);
   }
+  lo[j] = mn;
+  delta[j] = (mx > mn) ? __fdiv_rn(__fsub_rn(mx, mn), levels) : 1.0f;
+}
+
+// ------------------------------------------------------------- truncated range
+// Exact order statistics of every column by radix selection on the ordered
+// bit pattern of the floats: four passes of 8 bits; each pass histograms the
+// next digit of the elements that still match the prefix found so far.  Two
+// selections per column run side by side (lower and upper end of the range).
+constexpr int kSelCols = 32;  // columns per workgroup
+
+__global__ __launch_bounds__(256) void radix_hist_kernel(const float *__restrict__ x, uint64_t n, uint32_t d,
+                                                         uint32_t rows_per_block, int shift,
+                                                         const uint32_t *__restrict__ prefix /*[2][d]*/,
+                                                         uint32_t *__restrict__ hist /*[2][d][256]*/) {
+  __shared__ uint32_t lh[2][kSelCols][256];
+  for (int e = threadIdx.x; e < 2 * kSelCols * 256; e += 256) (&lh[0][0][0])[e] = 0;
+  __syncthreads();
+  const uint32_t c = threadIdx.x % kSelCols, col = blockIdx.y * kSelCols + c;
+  const uint64_t r0 = (uint64_t)blockIdx.x * rows_per_block;
+  const uint64_t r1 = r0 + rows_per_block < n ? r0 + rows_per_block : n;
+  if (col < d) {
+    const uint32_t p0 = prefix[col], p1 = prefix[d + col];
+    for (uint64_t i = r0 + threadIdx.x / kSelCols; i < r1; i += 256 / kSelCols) {
+      const uint32_t key = order_u32(x[i * d + col]);
+      const uint32_t digit = (key >> shift) & 255u;
+      const uint32_t high = shift == 24 ? 0u : key >> (shift + 8);
+      if (high == p0) atomicAdd(&lh[0][c][digit], 1u);
+      if (high == p1) atomicAdd(&lh[1][c][digit], 1u);
+    }
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < 2 * kSelCols * 256; e += 256) {
+    const int sel = e / (kSelCols * 256), cc = (e / 256) % kSelCols, b = e % 256;
+    const uint32_t v = lh[sel][cc][b], gc = blockIdx.y * kSelCols + cc;
+    if (v != 0 && gc < d) atomicAdd(&hist[((size_t)sel * d + gc) * 256 + b], v);
+  }
+}
+
+// One thread per (selection, column): the digit whose bucket holds the wanted rank.
+__global__ void radix_pick_kernel(const uint32_t *__restrict__ hist, uint32_t d, uint32_t *__restrict__ prefix,
+                                  uint32_t *__restrict__ rank) {
+  const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= 2 * d) return;
+  const uint32_t *h = hist + (size_t)t * 256;
+  uint32_t want = rank[t], cum = 0, b = 0;
+  for (; b < 255; ++b) {
+    if (want < cum + h[b]) break;
+    cum += h[b];
+  }
+  rank[t] = want - cum;
+  prefix[t] = (prefix[t] << 8) | b;
+}
+
+__global__ void truncated_range_kernel(const uint32_t *__restrict__ prefix, uint32_t d, float levels,
+                                       float *__restrict__ lo, float *__restrict__ delta) {
+  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= d) return;
+  const float mn = unorder_f32(prefix[j]), mx = unorder_f32(prefix[d + j]);
   lo[j] = mn;
   delta[j] = (mx > mn) ? __fdiv_rn(__fsub_rn(mx, mn), levels) : 1.0f;
 }
@@ -194,6 +257,48 @@ ann_status ann_sq_train(const float *x, uint64_t n, uint32_t d, uint32_t bits, f
   (void)hipFree(pmin);
   (void)hipFree(pmax);
   if (e != hipSuccess) return hip_fail(e, "sq_minmax launch");
+  if (e2 != hipSuccess) return hip_fail(e2, "hipStreamSynchronize");
+  return ANN_OK;
+}
+
+ann_status ann_sq_train_truncated(const float *x, uint64_t n, uint32_t d, uint32_t bits, double coverage, float *lo,
+                                  float *delta, void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  if (!x || !lo || !delta) return fail(ANN_EINVAL, "ann_sq_train_truncated: NULL argument");
+  if (n == 0 || n >= (1ull << 31) || d == 0) return fail(ANN_EINVAL, "ann_sq_train_truncated: empty input or n >= 2^31");
+  if (bits != 8 && bits != 4) return fail(ANN_EINVAL, "ann_sq_train_truncated: bits must be 4 or 8");
+  if (!(coverage > 0.5 && coverage <= 1.0)) return fail(ANN_EINVAL, "ann_sq_train_truncated: coverage must be in (0.5, 1]");
+  const uint64_t k = (uint64_t)floor((1.0 - coverage) * (double)(n - 1));
+  uint32_t *hist = nullptr, *state = nullptr;  // state: prefix[2][d], rank[2][d]
+  ANN_HIP(hipMalloc((void **)&hist, (size_t)2 * d * 256 * sizeof(uint32_t)));
+  hipError_t e = hipMalloc((void **)&state, (size_t)4 * d * sizeof(uint32_t));
+  if (e != hipSuccess) {
+    (void)hipFree(hist);
+    return hip_fail(e, "hipMalloc");
+  }
+  std::vector<uint32_t> init((size_t)4 * d, 0u);
+  for (uint32_t j = 0; j < d; ++j) {
+    init[(size_t)2 * d + j] = (uint32_t)k;
+    init[(size_t)3 * d + j] = (uint32_t)(n - 1 - k);
+  }
+  e = hipMemcpyAsync(state, init.data(), init.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st);
+  const uint32_t rows_per_block = 4096;
+  const dim3 grid((uint32_t)((n + rows_per_block - 1) / rows_per_block), (d + kSelCols - 1) / kSelCols);
+  for (int shift = 24; shift >= 0 && e == hipSuccess; shift -= 8) {
+    e = hipMemsetAsync(hist, 0, (size_t)2 * d * 256 * sizeof(uint32_t), st);
+    if (e != hipSuccess) break;
+    radix_hist_kernel<<<grid, 256, 0, st>>>(x, n, d, rows_per_block, shift, state, hist);
+    radix_pick_kernel<<<(2 * d + 255) / 256, 256, 0, st>>>(hist, d, state, state + (size_t)2 * d);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) {
+    truncated_range_kernel<<<(d + 255) / 256, 256, 0, st>>>(state, d, (float)((1u << bits) - 1u), lo, delta);
+    e = hipGetLastError();
+  }
+  hipError_t e2 = hipStreamSynchronize(st);  // also keeps `init` alive until the copy is done
+  (void)hipFree(hist);
+  (void)hipFree(state);
+  if (e != hipSuccess) return hip_fail(e, "ann_sq_train_truncated");
   if (e2 != hipSuccess) return hip_fail(e2, "hipStreamSynchronize");
   return ANN_OK;
 }

@@ -30,8 +30,8 @@ def stream_ptr():
     return torch.cuda.current_stream().cuda_stream
 
 
-def gpu_sq_fit(X, bits):
-    """ann_sq_train + ann_sq_encode; returns numpy (lo, delta, codes, norm_term)."""
+def gpu_sq_fit(X, bits, coverage=1.0):
+    """ann_sq_train(_truncated) + ann_sq_encode; returns numpy (lo, delta, codes, norm_term)."""
     n, d = X.shape
     xd = dev(X)
     lo = torch.empty(d, dtype=torch.float32, device=DEV)
@@ -39,7 +39,10 @@ def gpu_sq_fit(X, bits):
     rb = d if bits == 8 else d // 2
     codes = torch.empty((n, rb), dtype=torch.uint8, device=DEV)
     norm = torch.empty(n, dtype=torch.float32, device=DEV)
-    ann.ann_sq_train(xd, n, d, bits, lo, delta, stream_ptr())
+    if coverage >= 1.0:
+        ann.ann_sq_train(xd, n, d, bits, lo, delta, stream_ptr())
+    else:
+        ann.ann_sq_train_truncated(xd, n, d, bits, coverage, lo, delta, stream_ptr())
     ann.ann_sq_encode(xd, n, d, bits, lo, delta, codes, norm, stream_ptr())
     torch.cuda.synchronize()
     return lo.cpu().numpy(), delta.cpu().numpy(), codes.cpu().numpy(), norm.cpu().numpy()

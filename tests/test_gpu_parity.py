@@ -49,6 +49,26 @@ def test_sq_train_encode_bitwise(H, n, d, bits):
     assert (norm.view(np.uint32) == lv.norm_term.view(np.uint32)).all()
 
 
+@pytest.mark.parametrize("n,d,bits,coverage", [(20000, 128, 8, 0.99), (5000, 960, 4, 0.99), (3333, 50, 4, 0.9),
+                                                 (101, 8, 8, 0.99), (7, 4, 8, 0.75), (4000, 33, 8, 1.0)])
+def test_truncated_sq_bitwise(H, n, d, bits, coverage):
+    """Appendix G's truncated range: exact order statistics, then the same encoder."""
+    if bits == 4 and d % 2:
+        d += 1
+    w = inputs.Workload("tsq", n, d, 5, 0.3, 1, seed=n + d, aniso_sigma=0.5)
+    X = inputs.base_vectors(w)
+    X[::97] *= 20.0                              # outliers
+    X[:, 0] = np.round(X[:, 0])                  # many equal values
+    if n > 50:
+        X[:, 1] = -0.0
+    lo_o, delta_o = oracle.sq_train_truncated(X, bits, coverage)
+    lv = oracle.sq_encode(X, bits, lo_o, delta_o)
+    lo, delta, codes, norm = H.gpu_sq_fit(X, bits, coverage=coverage)
+    assert (lo == lo_o).all() and (delta.view(np.uint32) == delta_o.view(np.uint32)).all()
+    assert (codes == lv.codes).all()
+    assert (norm.view(np.uint32) == lv.norm_term.view(np.uint32)).all()
+
+
 @pytest.mark.parametrize("d,bits", [(128, 8), (960, 4), (96, 8), (100, 8), (30, 4), (768, 8)])
 def test_query_prep_bitwise(H, d, bits):
     w, X, Q, adj = small_case(400, d, 8, 33, seed=d + bits, bits=bits)

@@ -154,3 +154,32 @@ def test_key_closed_forms():
     assert oracle.key(oracle.IP, 0.5, 3.0, 8, 0.0) == np.float32(-7.0)
     z = oracle.key(oracle.IP, 1.0, 0.0, 0, 0.0)
     assert z == 0.0 and not np.signbit(z)
+
+
+def test_truncated_sq_hand_case_and_invariants():
+    """Appendix G: the range comes from percentile statistics, not the extremes."""
+    # column 0: 0, 1, ..., 100 (n = 101): coverage 0.99 -> k = floor(0.01 * 100) = 1 -> range [1, 99]
+    X = np.zeros((101, 2), np.float32)
+    X[:, 0] = np.random.default_rng(0).permutation(101)
+    X[:, 1] = 5.0
+    lo, delta = oracle.sq_train_truncated(X, 8, 0.99)
+    assert lo[0] == 1.0 and delta[0] == np.float32(np.float32(98.0) / np.float32(255.0))
+    assert lo[1] == 5.0 and delta[1] == 1.0
+    lo1, d1 = oracle.sq_train_truncated(X, 8, 1.0)
+    lo2, d2 = oracle.sq_train(X, 8)
+    assert (lo1 == lo2).all() and (d1 == d2).all()
+    # outliers are clamped, inliers keep the half-step bound, and the step is finer than min/max
+    rng = np.random.default_rng(1)
+    Y = rng.normal(size=(20000, 4)).astype(np.float32)
+    Y[::500] *= 50.0
+    lv_t, lv_m = oracle.sq_fit(Y, 4, coverage=0.99), oracle.sq_fit(Y, 4)
+    assert (lv_t.delta < 0.2 * lv_m.delta).all()
+    dec = oracle.sq_decode(lv_t, 4).astype(np.float64)
+    hi = lv_t.lo.astype(np.float64) + 15 * lv_t.delta.astype(np.float64)
+    inl = (Y >= lv_t.lo) & (Y <= hi)
+    assert 0.975 <= inl.mean() <= 0.985           # 1 % cut at each end of every column
+    assert (np.abs(dec - Y)[inl] <= 0.5 * np.broadcast_to(lv_t.delta, Y.shape)[inl] * (1 + 1e-5) + 1e-6).all()
+    c = np.empty((20000, 4), np.int64)
+    c[:, 0::2] = lv_t.codes & 0x0F
+    c[:, 1::2] = lv_t.codes >> 4
+    assert (c[Y < lv_t.lo] == 0).all() and (c[Y > hi] == 15).all()
