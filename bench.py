@@ -54,6 +54,7 @@ def main():
     ap.add_argument("--pivots", type=int, default=0,
                     help="entry-point stage: scan this many sampled base vectors per query (0 = start at the medoid)")
     ap.add_argument("--n-entry", type=int, default=1, help="initial nodes per query taken from the pivot scan")
+    ap.add_argument("--layout", type=int, default=0, help="1: redundant neighbour-code layout (PRS)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -115,6 +116,8 @@ def main():
     out_ids = torch.empty((nq, k), dtype=torch.int32, device=dev)
     out_dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
 
+    if args.layout == 1:
+        ann.ann_build_prs(index, st)
     entries = None
     if args.pivots:
         ann.ann_build_entry_table(index, args.pivots, st)
@@ -124,7 +127,7 @@ def main():
         if entries is not None:
             ann.ann_entry_scan(index, qd, nq, args.n_entry, entries, st)
         ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=mode, out_ids=pool, out_counts=counts,
-                             entry_ids=entries, n_entry=args.n_entry if entries is not None else 0,
+                             entry_ids=entries, n_entry=args.n_entry if entries is not None else 0, layout=args.layout,
                              expansions_per_step=args.expansions if mode == 1 else 0,
                              visited_slots=args.visited_slots if visited_slots is None else visited_slots, stream=st)
         ann.ann_rerank(index, qd, nq, pool, min(n_rerank, ef), ef, k, out_ids, out_dist, st)
@@ -199,7 +202,7 @@ def main():
             ann.ann_entry_scan(index, qd, nq, args.n_entry, entries, st)
         e_begin[i].record()
         ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=mode, out_ids=pool,
-                             entry_ids=entries, n_entry=args.n_entry if entries is not None else 0,
+                             entry_ids=entries, n_entry=args.n_entry if entries is not None else 0, layout=args.layout,
                              expansions_per_step=args.expansions if mode == 1 else 0,
                              visited_slots=args.visited_slots, stream=st)
         e_mid[i].record()
@@ -244,7 +247,7 @@ def main():
         if entries_big is not None:
             ann.ann_entry_scan(index, q_big, nq * rep, args.n_entry, entries_big, st)
         ann.ann_search_batch(index, q_big, nq * rep, k=k, ef=ef, mode=mode, out_ids=pool_big,
-                             entry_ids=entries_big, n_entry=args.n_entry if entries_big is not None else 0,
+                             entry_ids=entries_big, n_entry=args.n_entry if entries_big is not None else 0, layout=args.layout,
                              expansions_per_step=args.expansions if mode == 1 else 0,
                              visited_slots=args.visited_slots, stream=st)
         ann.ann_rerank(index, q_big, nq * rep, pool_big, min(n_rerank, ef), ef, k, ids_big, dist_big, st)

@@ -121,6 +121,9 @@ typedef struct {
  *                 m_s unvisited neighbours are taken per expansion, in stored
  *                 order.  alpha_s = 0 (labels are >= 1): no label test; needs an
  *                 index uploaded with edge_labels otherwise.  m_s = 0: no cap.
+ *   layout        0: neighbour code rows are gathered from the code table;
+ *                 1: they are read from the redundant copy made by
+ *                    ann_build_prs (same results; not with alpha_s / m_s).
  */
 typedef struct {
   uint32_t k;
@@ -130,7 +133,8 @@ typedef struct {
   uint32_t visited_slots;
   float alpha_s;
   uint32_t m_s;
-  uint32_t reserved; /* must be zero */
+  uint32_t layout;
+
 } ann_search_params;
 
 /*
@@ -182,6 +186,16 @@ ann_status ann_query_prep(ann_index *index, uint32_t level, const float *q, uint
                           float *qlo, void *stream);
 
 /*
+ * Redundant vector storage (the paper's PRS layout, Section 3.3, redundancy
+ * ratio 1): stores, for every node, the level-0 code rows and norm terms of its
+ * neighbours next to each other in slot order, so that an expansion reads them
+ * in one sequential sweep together with the id row.  Costs n * degree *
+ * row_stride bytes of device memory.  Synchronous; a second call is a no-op.
+ * Errors: ANN_EINVAL, ANN_ENOMEM.
+ */
+ann_status ann_build_prs(ann_index *index, void *stream);
+
+/*
  * Entry-point stage: per-query initial nodes I for Algorithm 1 (which takes
  * "initial nodes I" as an input).  ann_build_entry_table samples n_pivots base
  * vectors, node floor(i * n / n_pivots) for i = 0..n_pivots-1, and keeps a
@@ -212,8 +226,8 @@ ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_
  *              for them costs one more pass over the pool's code rows).
  *   out_counts [nq][4] (NULL allowed): expansions, distance evaluations,
  *              pool size, visited-table rebuilds.
- * Errors: ANN_EINVAL (NULL q/out_ids/params, nq == 0, k == 0, ef < k, reserved
- * fields non-zero, visited_slots not a power of two or too small for ef),
+ * Errors: ANN_EINVAL (NULL q/out_ids/params, nq == 0, k == 0, ef < k, unknown
+ * mode or layout, visited_slots not a power of two or too small for ef),
  * ANN_ECAPACITY (ef > ANN_MAX_EF, n_entry > ANN_MAX_ENTRIES), ANN_ENOMEM when
  * the per-index workspace has to grow for a larger nq (the only allocation on
  * this path), ANN_EDEVICE.

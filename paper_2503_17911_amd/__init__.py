@@ -27,7 +27,7 @@ _STATUS_NAMES = ["ANN_OK", "ANN_EINVAL", "ANN_ENOMEM", "ANN_EDEVICE", "ANN_EUNSU
 
 EXPORTED_SYMBOLS = ["ann_sq_train", "ann_sq_train_truncated", "ann_sq_encode", "ann_upload_index", "ann_free_index", "ann_query_prep",
                     "ann_search_batch", "ann_rescore", "ann_rerank", "ann_bruteforce_topk", "ann_build_entry_table",
-                    "ann_entry_scan", "ann_last_error", "ann_version"]
+                    "ann_entry_scan", "ann_build_prs", "ann_last_error", "ann_version"]
 
 
 class AnnError(RuntimeError):
@@ -51,7 +51,7 @@ class IndexDesc(ctypes.Structure):
 class SearchParams(ctypes.Structure):
     _fields_ = [("k", ctypes.c_uint32), ("ef", ctypes.c_uint32), ("mode", ctypes.c_uint32),
                 ("expansions_per_step", ctypes.c_uint32), ("visited_slots", ctypes.c_uint32),
-                ("alpha_s", ctypes.c_float), ("m_s", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("alpha_s", ctypes.c_float), ("m_s", ctypes.c_uint32), ("layout", ctypes.c_uint32)]
 
 
 def _load_library() -> ctypes.CDLL:
@@ -70,6 +70,7 @@ def _load_library() -> ctypes.CDLL:
     lib.ann_rescore.argtypes = [vp, u32, vp, u32, vp, u32, u32, vp, vp, vp, vp]
     lib.ann_rerank.argtypes = [vp, vp, u32, vp, u32, u32, u32, vp, vp, vp]
     lib.ann_bruteforce_topk.argtypes = [vp, u64, u32, vp, u32, u32, u32, vp, vp, vp]
+    lib.ann_build_prs.argtypes = [vp, vp]
     lib.ann_build_entry_table.argtypes = [vp, u32, vp]
     lib.ann_entry_scan.argtypes = [vp, vp, u32, u32, vp, vp]
     for name in EXPORTED_SYMBOLS[:-2]:
@@ -152,10 +153,10 @@ def ann_query_prep(index, level, q, nq, t, s, qlo, stream=None):
 
 
 def ann_search_batch(index, q, nq, *, k, ef, out_ids, out_keys=None, out_idot=None, out_counts=None, mode=0,
-                     expansions_per_step=0, visited_slots=0, alpha_s=0.0, m_s=0, entry_ids=None, n_entry=0,
-                     stream=None):
+                     expansions_per_step=0, visited_slots=0, alpha_s=0.0, m_s=0, layout=0, entry_ids=None,
+                     n_entry=0, stream=None):
     p = SearchParams(k=k, ef=ef, mode=mode, expansions_per_step=expansions_per_step, visited_slots=visited_slots,
-                     alpha_s=alpha_s, m_s=m_s)
+                     alpha_s=alpha_s, m_s=m_s, layout=layout)
     _check(_lib.ann_search_batch(index, _ptr(q), nq, ctypes.byref(p), _ptr(entry_ids), n_entry, _ptr(out_ids),
                                  _ptr(out_keys), _ptr(out_idot), _ptr(out_counts), stream))
 
@@ -169,6 +170,10 @@ def ann_rescore(index, level, q, nq, cand_ids, n_cand, cand_stride, out_ids, out
 def ann_rerank(index, q, nq, cand_ids, n_cand, cand_stride, k, out_ids, out_dist, stream=None):
     _check(_lib.ann_rerank(index, _ptr(q), nq, _ptr(cand_ids), n_cand, cand_stride, k, _ptr(out_ids),
                            _ptr(out_dist), stream))
+
+
+def ann_build_prs(index, stream=None):
+    _check(_lib.ann_build_prs(index, stream))
 
 
 def ann_build_entry_table(index, n_pivots, stream=None):

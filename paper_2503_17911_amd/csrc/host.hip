@@ -68,6 +68,24 @@ __global__ void check_rows_distinct_kernel(const uint32_t *__restrict__ adj, uin
   }
 }
 
+// Redundant layout: slot (i, t) receives a copy of the code row (and norm term)
+// of neighbour adjacency[i][t]; padding slots are zero.
+__global__ void build_prs_kernel(const uint32_t *__restrict__ adj, const uint8_t *__restrict__ codes,
+                                 const float *__restrict__ norm, uint64_t slots, uint64_t n, uint32_t row_stride,
+                                 uint8_t *__restrict__ out_codes, float *__restrict__ out_norm) {
+  const uint32_t cpr = row_stride / 16;
+  const uint64_t total = slots * cpr;
+  for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < total; e += (uint64_t)gridDim.x * blockDim.x) {
+    const uint64_t slot = e / cpr;
+    const uint32_t c = (uint32_t)(e - slot * cpr);
+    const uint32_t v = adj[slot];
+    const bool real = v != ANN_PAD_ID && v < n;
+    reinterpret_cast<uint4 *>(out_codes)[e] =
+        real ? reinterpret_cast<const uint4 *>(codes + (uint64_t)v * row_stride)[c] : make_uint4(0, 0, 0, 0);
+    if (c == 0 && out_norm) out_norm[slot] = real ? norm[v] : 0.0f;
+  }
+}
+
 __global__ void check_adjacency_kernel(const uint32_t *__restrict__ adj, uint64_t total, uint64_t n, uint32_t *bad) {
   for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < total; e += (uint64_t)gridDim.x * blockDim.x) {
     uint32_t v = adj[e];
@@ -102,6 +120,8 @@ void destroy(ann_index *ix) {
   (void)hipFree(ix->adjacency);
   (void)hipFree(ix->labels);
   (void)hipFree(ix->pivot_codes);
+  (void)hipFree(ix->prs_codes);
+  (void)hipFree(ix->prs_norm);
   (void)hipFree(ix->pivot_norm);
   (void)hipFree(ix->pivot_ids);
   for (int l = 0; l < ANN_MAX_LEVELS; ++l) {
@@ -290,6 +310,29 @@ ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index 
 #undef ANN_TRY_HIP
   cleanup(ANN_OK);
   *out = ix;
+  return ANN_OK;
+}
+
+ann_status ann_build_prs(ann_index *index, void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  if (!index) return fail(ANN_EINVAL, "ann_build_prs: index is NULL");
+  if (index->prs_codes) return ANN_OK;
+  const LevelDev &L = index->level[0];
+  const uint64_t slots = index->n * index->degree;
+  ANN_HIP(hipMalloc((void **)&index->prs_codes, (size_t)slots * L.row_stride));
+  if (index->metric == ANN_L2) {
+    hipError_t e = hipMalloc((void **)&index->prs_norm, (size_t)slots * sizeof(float));
+    if (e != hipSuccess) {
+      (void)hipFree(index->prs_codes);
+      index->prs_codes = nullptr;
+      return hip_fail(e, "hipMalloc");
+    }
+  }
+  const uint64_t total = slots * (L.row_stride / 16);
+  build_prs_kernel<<<grid_for(total, 256), 256, 0, st>>>(index->adjacency, L.codes, index->prs_norm ? L.norm_term : nullptr,
+                                                         slots, index->n, L.row_stride, index->prs_codes, index->prs_norm);
+  ANN_HIP(hipGetLastError());
+  ANN_HIP(hipStreamSynchronize(st));
   return ANN_OK;
 }
 

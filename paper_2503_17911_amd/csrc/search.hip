@@ -42,6 +42,8 @@ struct SearchArgs {
   const int32_t *sum_t;
   const uint32_t *entry_ids;
   const float *labels;  // [n][degree] edge labels or nullptr
+  const uint8_t *prs_codes;  // [n][degree][row_stride] code rows of every node's neighbours, or nullptr
+  const float *prs_norm;     // [n][degree] their norm terms (L2), or nullptr
   uint32_t *out_ids;
   float *out_keys;
   int32_t *out_idot;
@@ -363,6 +365,52 @@ struct SearchWave {
     merge_staged(n_q);
   }
 
+  // Expansion with redundantly stored neighbour vectors (the paper's PRS
+  // layout, Section 3.3, with ratio 1): the code rows and norm terms of u's
+  // neighbours lie next to each other in slot order, so they are requested
+  // together with the id row - one memory round trip per expansion instead of
+  // two, sequential instead of scattered reads, and no compaction.  Rows of
+  // visited neighbours are fetched as well; only unvisited ones are counted and
+  // can enter the pool.
+  __device__ __forceinline__ void expand_prs(uint32_t uid, int &n_q) {
+    const uint64_t rowbase = (uint64_t)uid * a.degree;
+    const uint32_t nb = lane < (int)a.degree ? a.adjacency[rowbase + lane] : kEmpty;
+    uint64_t fm = 0;
+    for (int sg = 0; sg < (int)a.degree; sg += G) {
+      const int slot = sg + grp;
+      const uint64_t at = rowbase + (uint32_t)(slot < (int)a.degree ? slot : (int)a.degree - 1);
+      const uint8_t *rp = a.prs_codes + at * a.row_stride;
+      uint4 rows[CPL];
+#pragma unroll
+      for (int j = 0; j < CPL; ++j) rows[j] = *reinterpret_cast<const uint4 *>(rp + coff[j]);
+      const float nrm = a.prs_norm ? a.prs_norm[at] : 0.0f;
+      if (sg == 0) {
+        // all ids of the row against the visited set, while the rows are on their way
+        if (PMAX == 1) {
+          const uint32_t incoming = (uint32_t)__popcll(__ballot(nb != kEmpty));
+          if (n_vis + incoming > vis_limit) rebuild_table();
+        }
+        const bool fresh = nb != kEmpty && nb < a.n && test_and_set(nb);
+        fm = __ballot(fresh);
+        const int n_new = __popcll(fm);
+        n_vis += n_new;
+        n_dist += n_new;
+      }
+      int dot = 0;
+#pragma unroll
+      for (int j = 0; j < CPL; ++j) dot += chunk_dot<BITS>(rows[j], tq[j]);
+      dot = group_sum_i32<LPR>(dot) + bias;
+      const uint32_t vid = (uint32_t)__shfl((int)nb, slot & 63);
+      const float key = key_from_idot(a.metric, s, qlo, dot, nrm);
+      const uint64_t c64 = pack64(order_u32(key), vid << 1);
+      const bool q = sub == 0 && slot < (int)a.degree && ((fm >> (slot & 63)) & 1ull) && c64 < worst;
+      const uint64_t bm = __ballot(q);
+      if (n_q + G > kStage) merge_staged(n_q);
+      if (q) mbuf[n_q + lanes_below(bm)] = c64;
+      n_q += __popcll(bm);
+    }
+  }
+
   __device__ void run(uint32_t qi) {
     // this lane's share of the folded query
 #pragma unroll
@@ -419,6 +467,12 @@ struct SearchWave {
       n_exp += got;
       if (PMAX > 1 && n_vis + (uint32_t)(got * kWave) > vis_limit) rebuild_table();
 
+      if (a.prs_codes) {
+        int n_q = 0;
+        for (int e = 0; e < got; ++e) expand_prs(__builtin_amdgcn_readlane(picked, e), n_q);
+        merge_staged(n_q);
+        continue;
+      }
       int n_cand = 0;
       if (a.filtered) {
         // label test and per-expansion cap: rows one after the other, in
@@ -584,7 +638,10 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   if (params->k == 0) return fail(ANN_EINVAL, "ann_search_batch: k == 0");
   if (params->ef < params->k) return fail(ANN_EINVAL, "ann_search_batch: ef = %u < k = %u", params->ef, params->k);
   if (params->ef > ANN_MAX_EF) return fail(ANN_ECAPACITY, "ann_search_batch: ef = %u exceeds ANN_MAX_EF = %u", params->ef, ANN_MAX_EF);
-  if (params->reserved) return fail(ANN_EINVAL, "ann_search_batch: reserved field must be zero");
+  if (params->layout > 1) return fail(ANN_EINVAL, "ann_search_batch: unknown layout %u", params->layout);
+  if (params->layout == 1 && !index->prs_codes) return fail(ANN_EINVAL, "ann_search_batch: layout 1 needs ann_build_prs first");
+  if (params->layout == 1 && (params->alpha_s > 0.0f || (params->m_s != 0 && params->m_s < index->degree)))
+    return fail(ANN_EUNSUPPORTED, "ann_search_batch: the edge filter is not available with the redundant layout");
   if (!(params->alpha_s >= 0.0f)) return fail(ANN_EINVAL, "ann_search_batch: alpha_s must be >= 0");
   if (params->alpha_s > 0.0f && !index->labels) return fail(ANN_EINVAL, "ann_search_batch: alpha_s given but the index was uploaded without edge labels");
   if (params->mode > 1) return fail(ANN_EINVAL, "ann_search_batch: unknown mode %u", params->mode);
@@ -629,6 +686,8 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   a.qlo = w.qlo;
   a.sum_t = w.sum_t;
   a.entry_ids = entry_ids;
+  a.prs_codes = params->layout == 1 ? index->prs_codes : nullptr;
+  a.prs_norm = params->layout == 1 && index->metric == ANN_L2 ? index->prs_norm : nullptr;
   a.labels = params->alpha_s > 0.0f ? index->labels : nullptr;
   a.alpha_s = params->alpha_s;
   a.m_s = params->m_s == 0 || params->m_s > index->degree ? index->degree : params->m_s;

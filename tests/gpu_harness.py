@@ -125,6 +125,10 @@ class GpuIndex:
         torch.cuda.synchronize()
         return (as_u32(ids), keys.cpu().numpy(), dots.cpu().numpy() if want_idot else None, as_u32(counts))
 
+    def build_prs(self):
+        ann.ann_build_prs(self.handle, stream_ptr())
+        torch.cuda.synchronize()
+
     def entry_scan(self, Q, n_pivots, n_entry):
         nq = Q.shape[0]
         ann.ann_build_entry_table(self.handle, n_pivots, stream_ptr())

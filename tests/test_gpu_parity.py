@@ -165,6 +165,24 @@ def test_multi_expansion_matches_the_batched_oracle(H, n, d, R, nq, metric, bits
     ix.close()
 
 
+@pytest.mark.parametrize("n,d,R,nq,metric,bits,efs", CASES)
+def test_redundant_layout_gives_identical_results(H, n, d, R, nq, metric, bits, efs):
+    """The PRS layout (neighbour codes stored with the node, Section 3.3) is a
+    storage choice: pools, keys, dots and counts equal the oracle's, in both modes."""
+    w, X, Q, adj = small_case(n, d, R, nq, seed=n + d + R, metric=metric, bits=bits, normalize=(metric == "ip"))
+    m = metric_id(metric)
+    lv = oracle.sq_fit(X, bits)
+    ix = H.GpuIndex(X, adj, 0, [lv], m)
+    ix.build_prs()
+    for ef in efs:
+        orc = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m)
+        assert_search_equal(ix.search(Q, ef, layout=1), orc)
+        assert_search_equal(ix.search(Q, ef, layout=1, visited_slots=0), orc, check_counts=False)
+        orc4 = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=3)
+        assert_search_equal(ix.search(Q, ef, layout=1, mode=1, expansions_per_step=3), orc4)
+    ix.close()
+
+
 @pytest.mark.parametrize("n,d,R,metric,bits", [(5000, 128, 32, "l2", 8), (2000, 960, 16, "l2", 4), (3000, 96, 32, "ip", 8),
                                                  (300, 16, 4, "ip", 8)])
 def test_entry_scan_and_search_from_scanned_entries(H, n, d, R, metric, bits):
