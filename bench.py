@@ -50,7 +50,8 @@ def main():
     ap.add_argument("--ef", type=int, default=0, help="skip the sweep and use this ef")
     ap.add_argument("--mode", type=int, default=-1, help="0 exact, 1 multi-expansion; -1: fastest that meets recall")
     ap.add_argument("--expansions", type=int, default=0, help="expansions per step in mode 1 (0 = library default)")
-    ap.add_argument("--visited-slots", type=int, default=0, help="LDS visited-table slots (0 = library default)")
+    ap.add_argument("--visited-slots", type=int, default=0, help="LDS visited-set slots (0 = library default)")
+    ap.add_argument("--visited-kind", type=int, default=0, help="0 library default, 1 direct-mapped cache, 2 probing table")
     ap.add_argument("--pivots", type=int, default=0,
                     help="entry-point stage: scan this many sampled base vectors per query (0 = start at the medoid)")
     ap.add_argument("--n-entry", type=int, default=1, help="initial nodes per query taken from the pivot scan")
@@ -123,13 +124,14 @@ def main():
         ann.ann_build_entry_table(index, args.pivots, st)
         entries = torch.empty((nq, args.n_entry), dtype=torch.int32, device=dev)
 
-    def run_step(ef, mode, pool, counts=None, visited_slots=None):
+    def run_step(ef, mode, pool, counts=None, complete_table=False):
         if entries is not None:
             ann.ann_entry_scan(index, qd, nq, args.n_entry, entries, st)
         ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=mode, out_ids=pool, out_counts=counts,
                              entry_ids=entries, n_entry=args.n_entry if entries is not None else 0, layout=args.layout,
                              expansions_per_step=args.expansions if mode == 1 else 0,
-                             visited_slots=args.visited_slots if visited_slots is None else visited_slots, stream=st)
+                             visited_slots=8192 if complete_table else args.visited_slots,
+                             visited_kind=ann.VISITED_TABLE if complete_table else args.visited_kind, stream=st)
         ann.ann_rerank(index, qd, nq, pool, min(n_rerank, ef), ef, k, out_ids, out_dist, st)
 
     # recall sweep
@@ -143,7 +145,7 @@ def main():
         for mode in modes:
             # counting run with the largest visited table: no rebuilds, so the
             # evaluation counts are those of the algorithm itself
-            run_step(ef, mode, pool, counts, visited_slots=8192)
+            run_step(ef, mode, pool, counts, complete_table=True)
             torch.cuda.synchronize()
             rec = recall_at_k(out_ids.cpu().numpy(), gt)
             c = counts.cpu().numpy().astype(np.int64)
@@ -165,7 +167,7 @@ def main():
         ef, mode = best["ef"], best["mode"]
         pool = torch.empty((nq, ef), dtype=torch.int32, device=dev)
         counts = torch.empty((nq, 4), dtype=torch.int32, device=dev)
-        run_step(ef, mode, pool, counts, visited_slots=8192)
+        run_step(ef, mode, pool, counts, complete_table=True)
         torch.cuda.synchronize()
         chosen = (ef, mode, best["recall"], counts.cpu().numpy().astype(np.int64), 0.0)
     ef, mode, rec, c, _ = chosen
@@ -178,8 +180,8 @@ def main():
     bytes_search = int((c[:, 0] * 4 * adj.shape[1] + c[:, 1] * per_eval).sum() + nq * (d + ef * 4))
     bytes_rerank = nq * (min(n_rerank, ef) * (d * 4 + 4) + d * 4 + k * 8)
 
-    # the configuration that is timed repeats some evaluations when its small
-    # visited table is rebuilt; report how many
+    # the configuration that is timed repeats some evaluations because its small
+    # visited set forgets; report how many
     counts = torch.empty((nq, 4), dtype=torch.int32, device=dev)
     run_step(ef, mode, pool, counts)
     torch.cuda.synchronize()
@@ -204,7 +206,7 @@ def main():
         ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=mode, out_ids=pool,
                              entry_ids=entries, n_entry=args.n_entry if entries is not None else 0, layout=args.layout,
                              expansions_per_step=args.expansions if mode == 1 else 0,
-                             visited_slots=args.visited_slots, stream=st)
+                             visited_slots=args.visited_slots, visited_kind=args.visited_kind, stream=st)
         e_mid[i].record()
         ann.ann_rerank(index, qd, nq, pool, min(n_rerank, ef), ef, k, out_ids, out_dist, st)
     e_end.record()
@@ -249,7 +251,7 @@ def main():
         ann.ann_search_batch(index, q_big, nq * rep, k=k, ef=ef, mode=mode, out_ids=pool_big,
                              entry_ids=entries_big, n_entry=args.n_entry if entries_big is not None else 0, layout=args.layout,
                              expansions_per_step=args.expansions if mode == 1 else 0,
-                             visited_slots=args.visited_slots, stream=st)
+                             visited_slots=args.visited_slots, visited_kind=args.visited_kind, stream=st)
         ann.ann_rerank(index, q_big, nq * rep, pool_big, min(n_rerank, ef), ef, k, ids_big, dist_big, st)
 
     big_step()

@@ -112,10 +112,22 @@ typedef struct {
  *                    expansion; same pool/visited semantics).
  *   expansions_per_step   mode 1 only, 1..4 (0 = library default, 4): the closest
  *                 un-expanded entries expanded together in one step.
- *   visited_slots number of slots of the per-query visited hash table in LDS,
- *                 a power of two, 0 = chosen from ef and degree.  When the
- *                 table fills it is rebuilt from the current pool; this costs
- *                 repeated distance evaluations, never a different result.
+ *   visited_kind, visited_slots   how the visited set V is kept in LDS
+ *                 (visited_slots a power of two <= 8192, 0 = library default).
+ *                 ANN_VISITED_CACHE: a direct-mapped cache of node ids, one probe
+ *                 per test; a node whose slot is taken over by another is
+ *                 forgotten and may be evaluated again.  ANN_VISITED_TABLE: an
+ *                 open-addressing table that holds every evaluated node while it
+ *                 fits and is rebuilt from the current pool when 3/4 full.
+ *                 Forgetting a node costs a repeated distance evaluation, never
+ *                 a different pool: a forgotten node outside the pool is
+ *                 rejected again by a pool maximum that only decreases, one
+ *                 inside the pool is recognised when it is merged.  The
+ *                 exception is the cap m_s, whose choice of neighbours depends
+ *                 on V itself: with m_s below the degree the table is used and
+ *                 the result is the sequential one only for queries that report
+ *                 0 rebuilds in out_counts.  ANN_VISITED_AUTO: the cache, or the
+ *                 table (8192 slots by default) when m_s is active.
  *   alpha_s, m_s  the search-time edge filter of Algorithm 1 (Section 4.3): an
  *                 edge is followed only if its label <= alpha_s, and at most
  *                 m_s unvisited neighbours are taken per expansion, in stored
@@ -125,6 +137,8 @@ typedef struct {
  *                 1: they are read from the redundant copy made by
  *                    ann_build_prs (same results; not with alpha_s / m_s).
  */
+typedef enum { ANN_VISITED_AUTO = 0, ANN_VISITED_CACHE = 1, ANN_VISITED_TABLE = 2 } ann_visited_kind;
+
 typedef struct {
   uint32_t k;
   uint32_t ef;
@@ -134,7 +148,7 @@ typedef struct {
   float alpha_s;
   uint32_t m_s;
   uint32_t layout;
-
+  uint32_t visited_kind; /* ann_visited_kind */
 } ann_search_params;
 
 /*
@@ -227,7 +241,8 @@ ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_
  *   out_counts [nq][4] (NULL allowed): expansions, distance evaluations,
  *              pool size, visited-table rebuilds.
  * Errors: ANN_EINVAL (NULL q/out_ids/params, nq == 0, k == 0, ef < k, unknown
- * mode or layout, visited_slots not a power of two or too small for ef),
+ * mode, layout or visited_kind, visited_slots not a power of two or too small
+ * for ef, ANN_VISITED_CACHE together with m_s below the degree),
  * ANN_ECAPACITY (ef > ANN_MAX_EF, n_entry > ANN_MAX_ENTRIES), ANN_ENOMEM when
  * the per-index workspace has to grow for a larger nq (the only allocation on
  * this path), ANN_EDEVICE.

@@ -48,10 +48,14 @@ class IndexDesc(ctypes.Structure):
                 ("entry_point", ctypes.c_uint32), ("flags", ctypes.c_uint32), ("edge_labels", ctypes.c_void_p)]
 
 
+VISITED_AUTO, VISITED_CACHE, VISITED_TABLE = 0, 1, 2
+
+
 class SearchParams(ctypes.Structure):
     _fields_ = [("k", ctypes.c_uint32), ("ef", ctypes.c_uint32), ("mode", ctypes.c_uint32),
                 ("expansions_per_step", ctypes.c_uint32), ("visited_slots", ctypes.c_uint32),
-                ("alpha_s", ctypes.c_float), ("m_s", ctypes.c_uint32), ("layout", ctypes.c_uint32)]
+                ("alpha_s", ctypes.c_float), ("m_s", ctypes.c_uint32), ("layout", ctypes.c_uint32),
+                ("visited_kind", ctypes.c_uint32)]
 
 
 def _load_library() -> ctypes.CDLL:
@@ -153,10 +157,10 @@ def ann_query_prep(index, level, q, nq, t, s, qlo, stream=None):
 
 
 def ann_search_batch(index, q, nq, *, k, ef, out_ids, out_keys=None, out_idot=None, out_counts=None, mode=0,
-                     expansions_per_step=0, visited_slots=0, alpha_s=0.0, m_s=0, layout=0, entry_ids=None,
+                     expansions_per_step=0, visited_slots=0, alpha_s=0.0, m_s=0, layout=0, visited_kind=0, entry_ids=None,
                      n_entry=0, stream=None):
     p = SearchParams(k=k, ef=ef, mode=mode, expansions_per_step=expansions_per_step, visited_slots=visited_slots,
-                     alpha_s=alpha_s, m_s=m_s, layout=layout)
+                     alpha_s=alpha_s, m_s=m_s, layout=layout, visited_kind=visited_kind)
     _check(_lib.ann_search_batch(index, _ptr(q), nq, ctypes.byref(p), _ptr(entry_ids), n_entry, _ptr(out_ids),
                                  _ptr(out_keys), _ptr(out_idot), _ptr(out_counts), stream))
 

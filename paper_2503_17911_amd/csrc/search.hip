@@ -5,7 +5,9 @@
 //   pool C          sorted array of (key, id) pairs in registers, striped:
 //                   entry i lives in register i/64 of lane i%64.  The low word
 //                   is (id << 1) | expanded, so pairs compare as plain u64.
-//   visited set V   open-addressing hash table in LDS, test-and-set by CAS.
+//   visited set V   in LDS, either a direct-mapped cache of node ids (one
+//                   exchange per test, may forget) or an open-addressing hash
+//                   table with test-and-set by CAS (complete while it fits).
 //   for j in G_i    one lane per adjacency slot: all ids of the row are
 //                   tested against V first, survivors are compacted (the
 //                   "deterministic access" batch filter), and only their code
@@ -51,6 +53,7 @@ struct SearchArgs {
   uint64_t n;
   uint32_t row_stride, n_chunks, degree, metric, tq_stride, n_entry, entry_point, ef, vis_log2, nq, p;
   uint32_t filtered;  // the label test and/or the per-expansion cap m_s is active
+  uint32_t vis_cache;  // visited set is the direct-mapped cache
   uint32_t m_s;
   float alpha_s;
 };
@@ -79,9 +82,14 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
 // candidates (they are back in registers before the scatter starts).
 __host__ __device__ constexpr int merge_buf_entries(int m, int /*pmax*/) { return 64 * m + 64; }
 
-// LDS bytes for one query: merge buffer, visited table, candidate ids.
-__host__ __device__ inline size_t search_smem_bytes(int m, int pmax, uint32_t vis_log2) {
-  return (size_t)merge_buf_entries(m, pmax) * 8 + ((size_t)1 << vis_log2) * 4 + (size_t)(64 * pmax) * 4;
+// Ids of one step's unvisited neighbours: up to pmax rows of `degree` ids.
+__host__ __device__ inline uint32_t cand_entries(uint32_t degree, int pmax) {
+  return (degree <= 32 ? 32u : 64u) * (uint32_t)pmax;
+}
+
+// LDS bytes for one query: merge buffer, visited set, candidate ids, folded query.
+__host__ __device__ inline size_t search_smem_bytes(int m, int pmax, uint32_t vis_log2, uint32_t degree, uint32_t tq_stride) {
+  return (size_t)merge_buf_entries(m, pmax) * 8 + ((size_t)1 << vis_log2) * 4 + (size_t)cand_entries(degree, pmax) * 4 + tq_stride;
 }
 
 template <int BITS, int LPR, int M, int PMAX>
@@ -94,11 +102,11 @@ struct SearchWave {
   const SearchArgs &a;
   uint64_t *mbuf;  // LDS merge scatter buffer, also staging for a step's qualifying candidates
   uint32_t *vis;   // LDS [cap]
-  uint32_t *cand;  // LDS [64*PMAX] unvisited neighbour ids of this step
+  uint32_t *cand;  // LDS: unvisited neighbour ids of this step
+  const int *tql;  // LDS: the folded query, TQW words per 16-byte code chunk
   int lane, sub, grp;
   uint32_t coff[CPL];  // byte offsets of this lane's chunks inside a code row
   uint32_t vis_mask, vis_shift, vis_limit;
-  int tq[CPL][TQW];
   float s, qlo;
   int bias;
   uint32_t pk[M], pv[M];  // pool: ordered key bits; (id << 1) | expanded
@@ -120,17 +128,49 @@ struct SearchWave {
     mbuf = smem;
     vis = reinterpret_cast<uint32_t *>(mbuf + merge_buf_entries(M, PMAX));
     cand = vis + cap;
+    tql = reinterpret_cast<const int *>(cand + cand_entries(a.degree, PMAX));
     vis_mask = cap - 1;
     vis_shift = 32 - a.vis_log2;
-    vis_limit = cap - cap / 4;
+    vis_limit = a.vis_cache ? 0xFFFFFFFFu : cap - cap / 4;  // the cache is never rebuilt
+  }
+
+  // This lane's part of the code/query dot product of one row: its four
+  // chunks against the matching words of the folded query.
+  __device__ __forceinline__ int row_dot(const uint4 (&row)[CPL]) const {
+    int dot = 0;
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) {
+      int t[TQW];
+      const int4 *tp = reinterpret_cast<const int4 *>(tql + (sub + j * LPR) * TQW);
+#pragma unroll
+      for (int w = 0; w < TQW / 4; ++w) {
+        const int4 v = tp[w];
+        t[4 * w] = v.x;
+        t[4 * w + 1] = v.y;
+        t[4 * w + 2] = v.z;
+        t[4 * w + 3] = v.w;
+      }
+      dot += chunk_dot<BITS>(row[j], t);
+    }
+    return dot;
   }
 
   __device__ __forceinline__ void clear_table() {
     for (uint32_t i = lane; i <= vis_mask; i += kWave) vis[i] = kEmpty;
   }
 
+  // Direct-mapped cache: a node's slot holds the last id hashed to it.  The
+  // exchange makes lanes that test the same id in one instruction see each
+  // other.  A displaced id is forgotten; it may come back as a candidate and is
+  // then recognised when it is merged (it equals a pool entry or another
+  // candidate) or rejected again by the pool's last entry.
+  __device__ __forceinline__ bool cache_test_and_set(uint32_t id) {
+    return atomicExch(&vis[(id * 0x9E3779B1u) >> vis_shift], id) != id;
+  }
+
   // true if id was not in the table (and now is)
   __device__ __forceinline__ bool test_and_set(uint32_t id) {
+    if (a.vis_cache) return cache_test_and_set(id);
     // double hashing: the probe stride is odd, so every slot is reached
     const uint32_t h = id * 0x9E3779B1u;
     uint32_t slot = h >> vis_shift;
@@ -145,6 +185,7 @@ struct SearchWave {
 
   // Membership test without insertion.
   __device__ __forceinline__ bool lookup(uint32_t id) {
+    if (a.vis_cache) return vis[(id * 0x9E3779B1u) >> vis_shift] == id;
     const uint32_t h = id * 0x9E3779B1u;
     uint32_t slot = h >> vis_shift;
     const uint32_t stride = ((h >> 4) | 1u) & vis_mask;
@@ -160,6 +201,12 @@ struct SearchWave {
   // the latency of the LDS atomics overlaps.  Bit 0 / bit 1 of the result: id0
   // / id1 was not in the table (and now is).  A lane's two ids may be equal.
   __device__ __forceinline__ int test_and_set2(bool v0, uint32_t id0, bool v1, uint32_t id1) {
+    if (a.vis_cache) {
+      uint32_t o0 = id0, o1 = id1;
+      if (v0) o0 = atomicExch(&vis[(id0 * 0x9E3779B1u) >> vis_shift], id0);
+      if (v1) o1 = atomicExch(&vis[(id1 * 0x9E3779B1u) >> vis_shift], id1);
+      return (o0 != id0 ? 1 : 0) | (o1 != id1 ? 2 : 0);
+    }
     const uint32_t h0 = id0 * 0x9E3779B1u, h1 = id1 * 0x9E3779B1u;
     uint32_t s0 = h0 >> vis_shift, s1 = h1 >> vis_shift;
     const uint32_t st0 = ((h0 >> 4) | 1u) & vis_mask, st1 = ((h1 >> 4) | 1u) & vis_mask;
@@ -227,21 +274,40 @@ struct SearchWave {
   // Merge up to 64 candidates (one per lane where `have`) into the pool.
   __device__ __forceinline__ void merge(bool have, uint32_t ck, uint32_t cv) {
     const uint64_t c64 = pack64(ck, cv);
-    const bool mine = have && c64 < worst;
+    bool mine = have && c64 < worst;
     const uint64_t qm = __ballot(mine);
     if (qm == 0) return;
-    const int n_m = __popcll(qm);
     uint64_t e[M];
-    int above[M];  // candidates greater than this pool entry
+    uint32_t pid[M];  // pool ids in candidate form with the expanded bit set
+    int above[M];     // candidates greater than this pool entry
 #pragma unroll
     for (int r = 0; r < M; ++r) {
       e[r] = pack64(pk[r], pv[r]);
+      pid[r] = pv[r] | 1u;
       above[r] = 0;
     }
     int below_c = 0, below_p = 0;  // candidates / pool entries smaller than this lane's candidate
-    for (uint64_t m = qm; m; m &= m - 1) {
+    uint64_t m = qm;               // candidates still to be ranked
+    uint64_t copies = 0;           // candidates that turned out to be in the pool or among earlier candidates
+    while (m) {
       const int l = __builtin_ctzll(m);
-      const uint64_t s64 = pack64(__builtin_amdgcn_readlane(ck, l), __builtin_amdgcn_readlane(cv, l));
+      m &= m - 1;
+      const uint32_t sv = __builtin_amdgcn_readlane(cv, l);
+      const uint64_t s64 = pack64(__builtin_amdgcn_readlane(ck, l), sv);
+      // A node the visited set has forgotten can come back: as a copy of a pool
+      // entry (dropped) or twice among the candidates (the later ones dropped).
+      uint64_t in_pool = 0;
+#pragma unroll
+      for (int r = 0; r < M; ++r) in_pool |= __ballot(pid[r] == (sv | 1u));
+      const uint64_t twins = __ballot(cv == sv) & m;
+      if (in_pool | twins) {
+        if (in_pool) {
+          copies |= 1ull << l;
+          continue;
+        }
+        m &= ~twins;
+        copies |= twins;
+      }
       int rank = 0;
 #pragma unroll
       for (int r = 0; r < M; ++r) {
@@ -252,6 +318,9 @@ struct SearchWave {
       below_c += s64 < c64 ? 1 : 0;
       below_p = write_lane(below_p, rank, l);
     }
+    mine = mine && ((copies >> lane) & 1ull) == 0;
+    const int n_m = __popcll(__ballot(mine));
+    if (n_m == 0) return;
     // a pool entry moves up by the number of candidates below it (no two
     // (key, id) pairs are equal)
 #pragma unroll
@@ -348,10 +417,7 @@ struct SearchWave {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         if (base + u * G < n_cand) {
-          int dot = 0;
-#pragma unroll
-          for (int j = 0; j < CPL; ++j) dot += chunk_dot<BITS>(rows[u][j], tq[j]);
-          dot = group_sum_i32<LPR>(dot) + bias;
+          const int dot = group_sum_i32<LPR>(row_dot(rows[u])) + bias;
           const float key = key_from_idot(a.metric, s, qlo, dot, nrm[u]);
           const uint64_t c64 = pack64(order_u32(key), vid[u] << 1);
           const bool q = sub == 0 && base + u * G + grp < n_cand && c64 < worst;
@@ -396,10 +462,7 @@ struct SearchWave {
         n_vis += n_new;
         n_dist += n_new;
       }
-      int dot = 0;
-#pragma unroll
-      for (int j = 0; j < CPL; ++j) dot += chunk_dot<BITS>(rows[j], tq[j]);
-      dot = group_sum_i32<LPR>(dot) + bias;
+      const int dot = group_sum_i32<LPR>(row_dot(rows)) + bias;
       const uint32_t vid = (uint32_t)__shfl((int)nb, slot & 63);
       const float key = key_from_idot(a.metric, s, qlo, dot, nrm);
       const uint64_t c64 = pack64(order_u32(key), vid << 1);
@@ -412,12 +475,12 @@ struct SearchWave {
   }
 
   __device__ void run(uint32_t qi) {
-    // this lane's share of the folded query
-#pragma unroll
-    for (int j = 0; j < CPL; ++j) {
-      const int *tqp = reinterpret_cast<const int *>(a.tq + (uint64_t)qi * a.tq_stride + (uint32_t)(sub + j * LPR) * (TQW * 4u));
-#pragma unroll
-      for (int w = 0; w < TQW; ++w) tq[j][w] = tqp[w];
+    // the folded query goes to LDS: it is read again for every group of rows
+    // (keeping it in registers costs a wavefront of occupancy)
+    {
+      const int *src = reinterpret_cast<const int *>(a.tq + (uint64_t)qi * a.tq_stride);
+      int *dst = const_cast<int *>(tql);
+      for (uint32_t i = lane; i < a.tq_stride / 4; i += kWave) dst[i] = src[i];
     }
     s = a.s[qi];
     qlo = a.qlo[qi];
@@ -465,7 +528,7 @@ struct SearchWave {
       }
       if (got == 0) break;
       n_exp += got;
-      if (PMAX > 1 && n_vis + (uint32_t)(got * kWave) > vis_limit) rebuild_table();
+      if (PMAX > 1 && !a.vis_cache && n_vis + (uint32_t)(got * kWave) > vis_limit) rebuild_table();
 
       if (a.prs_codes) {
         int n_q = 0;
@@ -571,8 +634,10 @@ struct SearchWave {
         int dot = 0;
         if (v != kEmpty) {
           const uint8_t *rp = a.codes + (uint64_t)v * a.row_stride;
+          uint4 row[CPL];
 #pragma unroll
-          for (int j = 0; j < CPL; ++j) dot += chunk_dot<BITS>(*reinterpret_cast<const uint4 *>(rp + coff[j]), tq[j]);
+          for (int j = 0; j < CPL; ++j) row[j] = *reinterpret_cast<const uint4 *>(rp + coff[j]);
+          dot = row_dot(row);
         }
         dot = group_sum_i32<LPR>(dot) + bias;
         if (sub == 0 && ci < (int)a.ef) a.out_idot[(uint64_t)qi * a.ef + ci] = v != kEmpty ? dot : 0;
@@ -589,7 +654,7 @@ struct SearchWave {
 };
 
 template <int BITS, int LPR, int M, int PMAX>
-__global__ __launch_bounds__(64) void search_kernel(SearchArgs args) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? 5 : 4))) void search_kernel(SearchArgs args) {
   extern __shared__ uint64_t smem[];
   const uint32_t qi = blockIdx.x;
   if (qi >= args.nq) return;
@@ -599,7 +664,7 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs args) {
 
 template <int BITS, int LPR, int PMAX>
 static ann_status launch_m(const SearchArgs &args, int m, hipStream_t st) {
-  const size_t smem = search_smem_bytes(m, PMAX, args.vis_log2);
+  const size_t smem = search_smem_bytes(m, PMAX, args.vis_log2, args.degree, args.tq_stride);
   switch (m) {
     case 1: search_kernel<BITS, LPR, 1, PMAX><<<args.nq, 64, smem, st>>>(args); break;
     case 2: search_kernel<BITS, LPR, 2, PMAX><<<args.nq, 64, smem, st>>>(args); break;
@@ -652,14 +717,21 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   if (entry_ids && n_entry > ANN_MAX_ENTRIES) return fail(ANN_ECAPACITY, "ann_search_batch: n_entry = %u exceeds ANN_MAX_ENTRIES = %u", n_entry, ANN_MAX_ENTRIES);
 
   const uint32_t ef = params->ef;
-  uint32_t need = 2 * (ef + 64 * p), min_log2 = 0;
+  const bool capped = params->m_s != 0 && params->m_s < index->degree;
+  if (params->visited_kind > ANN_VISITED_TABLE) return fail(ANN_EINVAL, "ann_search_batch: unknown visited_kind %u", params->visited_kind);
+  if (params->visited_kind == ANN_VISITED_CACHE && capped)
+    return fail(ANN_EINVAL, "ann_search_batch: the cap m_s needs ANN_VISITED_TABLE (its choice of neighbours depends on the visited set)");
+  const bool cache = params->visited_kind == ANN_VISITED_CACHE || (params->visited_kind == ANN_VISITED_AUTO && !capped);
+  // the table must hold the pool and one step's candidates below 3/4 load
+  // after a rebuild; the cache has no such minimum
+  uint32_t need = cache ? 64u : 2 * (ef + 64 * p), min_log2 = 0;
   while ((1u << min_log2) < need) ++min_log2;
   uint32_t vis_log2;
   if (params->visited_slots == 0) {
-    // default: the smallest table that works, so that many queries are
-    // resident per compute unit; rebuilds repeat some evaluations but never
-    // change results (measured fastest on 1M x 128 for ef 64..256)
-    uint32_t want = 1024;
+    // defaults: a small cache, so that many queries are resident per compute
+    // unit (measured fastest on 1M x 128 for ef 64..256); the largest table
+    // when the cap is active, so that rebuilds are rare
+    const uint32_t want = cache ? 1024u : (capped ? 8192u : 1024u);
     vis_log2 = 0;
     while ((1u << vis_log2) < want) ++vis_log2;
     if (vis_log2 < min_log2) vis_log2 = min_log2;
@@ -669,8 +741,8 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
     vis_log2 = 0;
     while ((1u << vis_log2) < v) ++vis_log2;
     if (vis_log2 < min_log2) return fail(ANN_EINVAL, "ann_search_batch: visited_slots = %u is below the minimum %u for ef = %u", v, 1u << min_log2, ef);
-    if (vis_log2 > 13) return fail(ANN_ECAPACITY, "ann_search_batch: visited_slots = %u exceeds 8192", v);
   }
+  if (vis_log2 > 13) return fail(ANN_ECAPACITY, "ann_search_batch: the visited set would need more than 8192 slots");
 
   ann_status rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st);
   if (rc != ANN_OK) return rc;
@@ -706,6 +778,7 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   a.entry_point = index->entry_point;
   a.ef = ef;
   a.vis_log2 = vis_log2;
+  a.vis_cache = cache ? 1u : 0u;
   a.nq = nq;
   a.p = p;
   int m = 1;

@@ -109,7 +109,9 @@ class GpuIndex:
         return t.cpu().numpy(), s.cpu().numpy(), qlo.cpu().numpy()
 
     def search(self, Q, ef, k=1, entries=None, want_idot=True, **kw):
-        kw.setdefault("visited_slots", 8192)      # large enough that evaluation counts equal the oracle's
+        if "visited_slots" not in kw and "visited_kind" not in kw:
+            # a complete table, large enough that evaluation counts equal the oracle's
+            kw.update(visited_kind=ann.VISITED_TABLE, visited_slots=8192)
         nq = Q.shape[0]
         qd = dev(Q)
         ids = torch.empty((nq, ef), dtype=torch.int32, device=DEV)

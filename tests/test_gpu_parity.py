@@ -306,12 +306,49 @@ def test_small_visited_table_rebuilds_without_changing_results(H, c1):
     w, X, Q, adj, entry, lv = (c1[k] for k in ("w", "X", "Q", "adj", "entry", "level"))
     ix = H.GpuIndex(X, adj, entry, [lv], oracle.L2)
     orc = oracle.search_batch(lv, w.d, adj, entry, Q, 32)
-    gpu = ix.search(Q, 32, visited_slots=256)
+    gpu = ix.search(Q, 32, visited_kind=H.ann.VISITED_TABLE, visited_slots=256)
     assert_search_equal(gpu, orc, check_counts=False)
     assert gpu[3][:, 3].max() >= 1              # rebuilds happened
     assert (gpu[3][:, 1] >= orc[3][:, 1]).all()  # never fewer evaluations than the oracle
-    big = ix.search(Q, 32, visited_slots=8192)
+    big = ix.search(Q, 32, visited_kind=H.ann.VISITED_TABLE, visited_slots=8192)
     assert_search_equal(big, orc)
+    ix.close()
+
+
+@pytest.mark.parametrize("slots", [64, 256, 1024, 8192])
+@pytest.mark.parametrize("P", [1, 4])
+def test_visited_cache_forgets_without_changing_results(H, c1, slots, P):
+    """The default visited set is a direct-mapped cache that forgets a node when
+    another takes its slot.  A forgotten node is evaluated again and then either
+    rejected by the pool's last entry or recognised as a copy of a pool entry or
+    of another candidate; the pool, keys and expansion count stay those of the
+    oracle, however small the cache."""
+    w, X, Q, adj, entry, lv = (c1[k] for k in ("w", "X", "Q", "adj", "entry", "level"))
+    ix = H.GpuIndex(X, adj, entry, [lv], oracle.L2)
+    for ef in (10, 64, 200):
+        orc = oracle.search_batch(lv, w.d, adj, entry, Q, ef, expansions_per_step=P)
+        gpu = ix.search(Q, ef, mode=int(P > 1), expansions_per_step=P if P > 1 else 0,
+                        visited_kind=H.ann.VISITED_CACHE, visited_slots=slots)
+        assert_search_equal(gpu, orc, check_counts=False)
+        assert (gpu[3][:, 0] == orc[3][:, 0]).all() and (gpu[3][:, 2] == orc[3][:, 2]).all()
+        assert (gpu[3][:, 1] >= orc[3][:, 1]).all()
+        if slots == 64:
+            assert gpu[3][:, 1].sum() > orc[3][:, 1].sum()   # forgetting did happen
+    ix.close()
+
+
+def test_visited_cache_with_repeated_entry_nodes(H, c1):
+    """Initial nodes given twice, or twice with another node of the same cache
+    slot between them, enter the pool once."""
+    w, X, Q, adj, entry, lv = (c1[k] for k in ("w", "X", "Q", "adj", "entry", "level"))
+    ix = H.GpuIndex(X, adj, entry, [lv], oracle.L2)
+    nq = 8
+    rng = np.random.default_rng(5)
+    base = rng.integers(0, w.n, size=(nq, 3)).astype(np.uint32)
+    ent = np.concatenate([base, base[:, ::-1], base[:, :2]], axis=1)      # every id two or three times
+    orc = oracle.search_batch(lv, w.d, adj, entry, Q[:nq], 48, entries=ent)
+    gpu = ix.search(Q[:nq], 48, entries=ent, visited_kind=H.ann.VISITED_CACHE, visited_slots=64)
+    assert_search_equal(gpu, orc, check_counts=False)
     ix.close()
 
 
@@ -358,7 +395,7 @@ def test_bruteforce_matches_fp64_exhaustive_search(H, n, d, nq, k, metric):
 
 def test_c2_full_size_sampled_queries(H):
     """The benchmark workload at full size (1M x 128, SQ8, R=32) in the launch
-    configuration bench.py times (default visited table, both modes): the whole
+    configuration bench.py times (default visited set, both modes): the whole
     10,000-query batch runs on the GPU, a sample of queries is recomputed by the
     oracle one by one, and properties that hold at any size are checked for all."""
     w = inputs.WORKLOADS["c2"]
@@ -376,7 +413,7 @@ def test_c2_full_size_sampled_queries(H):
         assert (ids[sample] == oi).all()
         assert (keys[sample].view(np.uint32) == ok.view(np.uint32)).all()
         assert (counts[sample, 0] == oc[:, 0]).all() and (counts[sample, 2] == oc[:, 2]).all()
-        assert (counts[sample, 1] >= oc[:, 1]).all()        # small table: evaluations may repeat, never go missing
+        assert (counts[sample, 1] >= oc[:, 1]).all()        # forgetful visited set: evaluations may repeat, never go missing
         # every query: full pool, sorted by (key, id), distinct ids in range
         assert (counts[:, 2] == ef).all() and ids.max() < w.n
         assert ((np.diff(keys, axis=1) > 0) | ((np.diff(keys, axis=1) == 0) & (np.diff(ids.astype(np.int64), axis=1) > 0))).all()
