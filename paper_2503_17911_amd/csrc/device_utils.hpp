@@ -37,6 +37,18 @@ __device__ __forceinline__ int group_sum_i32(int v) {
   return v;
 }
 
+// Inclusive prefix sum over the 64 lanes (row shifts inside each row of 16
+// lanes, then the row totals are broadcast to the rows that follow).
+__device__ __forceinline__ int wave_inclusive_scan_i32(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);  // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);  // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);  // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);  // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);  // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);  // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
 __device__ __forceinline__ double xor_lane_f64(double v, int mask) {
   int lo = __double2loint(v), hi = __double2hiint(v);
   lo = xor_lane_i32(lo, mask);

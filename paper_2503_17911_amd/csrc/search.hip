@@ -18,10 +18,13 @@
 //                   reduced across the LPR lanes with DPP.  128-byte rows: two
 //                   lanes per row, 32 rows per instruction group.
 //   insert          all candidates of a step that beat the pool's last entry
-//                   are merged at once: every pool entry counts the candidates
-//                   below it, every candidate counts the pool entries and
-//                   candidates below it, and both scatter to their final
-//                   positions through LDS.
+//                   are merged at once: each candidate finds its rank among
+//                   the pool entries by binary search in a sorted LDS copy of
+//                   the pool and its rank among the other candidates by
+//                   counting; each pool entry moves up by the number of
+//                   candidates below it (prefix sums over a histogram of the
+//                   candidates' ranks); both scatter to their final positions
+//                   through LDS, which leaves the next sorted copy behind.
 // The pool after a step is the ef smallest (key, id) pairs among the old pool
 // and the step's new candidates, which is what sequential insertion in row
 // order gives; so with one expansion per step results equal a sequential
@@ -78,18 +81,22 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
   return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
 
-// The merge scatter buffer doubles as the staging area of a step's qualifying
-// candidates (they are back in registers before the scatter starts).
-__host__ __device__ constexpr int merge_buf_entries(int m, int /*pmax*/) { return 64 * m + 64; }
+// The merge scatter buffer: the sorted pool (64 m slots) plus up to 64
+// candidates.  After a merge it holds the new pool in order.
+__host__ __device__ constexpr int merge_buf_entries(int m) { return 64 * m + 64; }
+// Staging area of a step's qualifying candidates; during a merge (candidates
+// are in registers then) it serves as 2 * 64 m integer counters.
+__host__ __device__ constexpr int stage_entries(int m) { return 64 * m; }
 
 // Ids of one step's unvisited neighbours: up to pmax rows of `degree` ids.
 __host__ __device__ inline uint32_t cand_entries(uint32_t degree, int pmax) {
   return (degree <= 32 ? 32u : 64u) * (uint32_t)pmax;
 }
 
-// LDS bytes for one query: merge buffer, visited set, candidate ids, folded query.
+// LDS bytes for one query: merge buffer, staging, visited set, candidate ids, folded query.
 __host__ __device__ inline size_t search_smem_bytes(int m, int pmax, uint32_t vis_log2, uint32_t degree, uint32_t tq_stride) {
-  return (size_t)merge_buf_entries(m, pmax) * 8 + ((size_t)1 << vis_log2) * 4 + (size_t)cand_entries(degree, pmax) * 4 + tq_stride;
+  return (size_t)(merge_buf_entries(m) + stage_entries(m)) * 8 + ((size_t)1 << vis_log2) * 4 +
+         (size_t)cand_entries(degree, pmax) * 4 + tq_stride;
 }
 
 template <int BITS, int LPR, int M, int PMAX>
@@ -100,7 +107,8 @@ struct SearchWave {
   static constexpr int TQW = TqRegs<BITS>::kWords;
 
   const SearchArgs &a;
-  uint64_t *mbuf;  // LDS merge scatter buffer, also staging for a step's qualifying candidates
+  uint64_t *mbuf;   // LDS: sorted copy of the pool as of the last merge; merge scatter buffer
+  uint64_t *stage;  // LDS: a step's qualifying candidates; counters during a merge
   uint32_t *vis;   // LDS [cap]
   uint32_t *cand;  // LDS: unvisited neighbour ids of this step
   const int *tql;  // LDS: the folded query, TQW words per 16-byte code chunk
@@ -113,7 +121,7 @@ struct SearchWave {
   uint64_t worst;         // pool entry ef-1 (all ones while the pool is not full)
   uint32_t n_exp = 0, n_dist = 0, n_vis = 0, n_rebuild = 0;
 
-  __device__ SearchWave(const SearchArgs &args, uint64_t *smem) : a(args) {
+  __device__ __forceinline__ SearchWave(const SearchArgs &args, uint64_t *smem) : a(args) {
     lane = lane_id();
     sub = lane % LPR;
     grp = lane / LPR;
@@ -126,7 +134,8 @@ struct SearchWave {
     }
     const uint32_t cap = 1u << a.vis_log2;
     mbuf = smem;
-    vis = reinterpret_cast<uint32_t *>(mbuf + merge_buf_entries(M, PMAX));
+    stage = mbuf + merge_buf_entries(M);
+    vis = reinterpret_cast<uint32_t *>(stage + stage_entries(M));
     cand = vis + cap;
     tql = reinterpret_cast<const int *>(cand + cand_entries(a.degree, PMAX));
     vis_mask = cap - 1;
@@ -272,60 +281,70 @@ struct SearchWave {
   }
 
   // Merge up to 64 candidates (one per lane where `have`) into the pool.
+  //
+  // mbuf[0 .. 64 M) is the pool in order as the last merge left it (expanded
+  // marks may be out of date, which no comparison below depends on); slots
+  // behind the pool hold all-ones or entries that were pushed out, all of them
+  // above any candidate that beats the pool's last entry.
   __device__ __forceinline__ void merge(bool have, uint32_t ck, uint32_t cv) {
     const uint64_t c64 = pack64(ck, cv);
     bool mine = have && c64 < worst;
-    const uint64_t qm = __ballot(mine);
-    if (qm == 0) return;
-    uint64_t e[M];
-    uint32_t pid[M];  // pool ids in candidate form with the expanded bit set
-    int above[M];     // candidates greater than this pool entry
+    if (__ballot(mine) == 0) return;
+    // number of pool entries below the candidate: lower bound over slots
+    // 0 .. 64 M - 2 (a candidate that beats the last entry ranks below 64 M)
+    uint32_t pos = 0;  // byte offset into mbuf
 #pragma unroll
-    for (int r = 0; r < M; ++r) {
-      e[r] = pack64(pk[r], pv[r]);
-      pid[r] = pv[r] | 1u;
-      above[r] = 0;
+    for (int step = 32 * M; step >= 1; step >>= 1) {
+      const uint64_t e = *reinterpret_cast<const uint64_t *>(reinterpret_cast<const char *>(mbuf) + pos + (step - 1) * 8);
+      pos += e < c64 ? (uint32_t)step * 8u : 0u;
     }
-    int below_c = 0, below_p = 0;  // candidates / pool entries smaller than this lane's candidate
-    uint64_t m = qm;               // candidates still to be ranked
-    uint64_t copies = 0;           // candidates that turned out to be in the pool or among earlier candidates
-    while (m) {
-      const int l = __builtin_ctzll(m);
-      m &= m - 1;
-      const uint32_t sv = __builtin_amdgcn_readlane(cv, l);
-      const uint64_t s64 = pack64(__builtin_amdgcn_readlane(ck, l), sv);
-      // A node the visited set has forgotten can come back: as a copy of a pool
-      // entry (dropped) or twice among the candidates (the later ones dropped).
-      uint64_t in_pool = 0;
+    // A node the visited set has forgotten can come back.  If it is in the
+    // pool, the entry found is that node (ids are unique in the pool): dropped.
+    const uint32_t at_id = (uint32_t)*reinterpret_cast<const uint64_t *>(reinterpret_cast<const char *>(mbuf) + pos);
+    mine = mine && (at_id | 1u) != (cv | 1u);
+    uint64_t km = __ballot(mine);
+    if (km == 0) return;
+    const int rank_p = (int)(pos >> 3);
+    int *cnt = reinterpret_cast<int *>(stage);
+    int shift[M];
+    int dest;
+    for (;;) {
+      // pool entry i moves up by the number of candidates with rank <= i
 #pragma unroll
-      for (int r = 0; r < M; ++r) in_pool |= __ballot(pid[r] == (sv | 1u));
-      const uint64_t twins = __ballot(cv == sv) & m;
-      if (in_pool | twins) {
-        if (in_pool) {
-          copies |= 1ull << l;
-          continue;
-        }
-        m &= ~twins;
-        copies |= twins;
-      }
-      int rank = 0;
+      for (int r = 0; r < M; ++r) cnt[r * kWave + lane] = 0;
+      __syncthreads();
+      if (mine) atomicAdd(&cnt[rank_p], 1);
+      __syncthreads();
+      int carry = 0;
 #pragma unroll
       for (int r = 0; r < M; ++r) {
-        const bool lt = e[r] < s64;
-        rank += __popcll(__ballot(lt));
-        above[r] += lt ? 1 : 0;
+        shift[r] = wave_inclusive_scan_i32(cnt[r * kWave + lane]) + carry;
+        carry = __builtin_amdgcn_readlane(shift[r], kWave - 1);
       }
-      below_c += s64 < c64 ? 1 : 0;
-      below_p = write_lane(below_p, rank, l);
+      // candidates below this lane's candidate
+      int below_c = 0;
+      for (uint64_t m = km; m; m &= m - 1) {
+        const int l = __builtin_ctzll(m);
+        const uint64_t s64 = pack64(__builtin_amdgcn_readlane(ck, l), __builtin_amdgcn_readlane(cv, l));
+        below_c += s64 < c64 ? 1 : 0;
+      }
+      dest = rank_p + below_c;
+      // The same forgotten node twice among the candidates: equal values get
+      // equal destinations.  One of them stays, the count starts over (rare).
+      __syncthreads();
+      if (mine) cnt[dest] = lane;
+      __syncthreads();
+      const uint64_t lose = __ballot(mine && cnt[dest] != lane);
+      if (lose == 0) break;
+      km &= ~lose;
+      mine = mine && ((lose >> lane) & 1ull) == 0;
+      __syncthreads();
     }
-    mine = mine && ((copies >> lane) & 1ull) == 0;
-    const int n_m = __popcll(__ballot(mine));
-    if (n_m == 0) return;
-    // a pool entry moves up by the number of candidates below it (no two
-    // (key, id) pairs are equal)
+    const int n_m = __popcll(km);
+    // no two (key, id) pairs are equal: the destinations are a permutation
 #pragma unroll
-    for (int r = 0; r < M; ++r) mbuf[r * kWave + lane + (n_m - above[r])] = e[r];
-    if (mine) mbuf[below_p + below_c] = c64;
+    for (int r = 0; r < M; ++r) mbuf[r * kWave + lane + shift[r]] = pack64(pk[r], pv[r]);
+    if (mine) mbuf[dest] = c64;
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < M; ++r) {
@@ -335,6 +354,7 @@ struct SearchWave {
       pv[r] = beyond ? kEmpty : (uint32_t)v;
     }
     __syncthreads();
+    (void)n_m;
     refresh_worst();
   }
 
@@ -373,19 +393,24 @@ struct SearchWave {
     n_cand += c0 + __popcll(fm1);
   }
 
-  // Merge the n_q candidates staged in mbuf[0..n_q) into the pool, 64 at a time
-  // (they are copied to registers first: the merge scatters through mbuf).
-  static constexpr int kStage = 64 * M + 64;
+  // Merge the n_q staged candidates into the pool, 64 at a time (they are
+  // copied to registers first: a merge uses the staging area for its counters).
+  static constexpr int kStage = stage_entries(M);
   __device__ __forceinline__ void merge_staged(int &n_q) {
     if (n_q == 0) return;
     __syncthreads();
-    uint64_t batch[M + 1];
+    uint64_t batch[M];
 #pragma unroll
-    for (int b = 0; b <= M; ++b) batch[b] = b * kWave + lane < n_q ? mbuf[b * kWave + lane] : 0;
+    for (int b = 0; b < M; ++b) batch[b] = b * kWave + lane < n_q ? stage[b * kWave + lane] : 0;
     __syncthreads();
+    // one copy of the merge code, whatever M is: the batch is picked by selects
+#pragma nounroll
+    for (int b = 0; b * kWave < n_q; ++b) {
+      uint64_t c = batch[0];
 #pragma unroll
-    for (int b = 0; b <= M; ++b)
-      if (b * kWave < n_q) merge(b * kWave + lane < n_q, (uint32_t)(batch[b] >> 32), (uint32_t)batch[b]);
+      for (int t = 1; t < M; ++t) c = b == t ? batch[t] : c;
+      merge(b * kWave + lane < n_q, (uint32_t)(c >> 32), (uint32_t)c);
+    }
     n_q = 0;
   }
 
@@ -423,7 +448,7 @@ struct SearchWave {
           const bool q = sub == 0 && base + u * G + grp < n_cand && c64 < worst;
           const uint64_t bm = __ballot(q);
           if (n_q + G > kStage) merge_staged(n_q);  // rare: make room (the pool's last entry only gets smaller)
-          if (q) mbuf[n_q + lanes_below(bm)] = c64;
+          if (q) stage[n_q + lanes_below(bm)] = c64;
           n_q += __popcll(bm);
         }
       }
@@ -469,12 +494,12 @@ struct SearchWave {
       const bool q = sub == 0 && slot < (int)a.degree && ((fm >> (slot & 63)) & 1ull) && c64 < worst;
       const uint64_t bm = __ballot(q);
       if (n_q + G > kStage) merge_staged(n_q);
-      if (q) mbuf[n_q + lanes_below(bm)] = c64;
+      if (q) stage[n_q + lanes_below(bm)] = c64;
       n_q += __popcll(bm);
     }
   }
 
-  __device__ void run(uint32_t qi) {
+  __device__ __forceinline__ void run(uint32_t qi) {
     // the folded query goes to LDS: it is read again for every group of rows
     // (keeping it in registers costs a wavefront of occupancy)
     {
@@ -491,6 +516,8 @@ struct SearchWave {
       pv[r] = kEmpty;
     }
     worst = ~0ull;
+#pragma unroll
+    for (int r = 0; r <= M; ++r) mbuf[r * kWave + lane] = ~0ull;  // the empty pool, in order
     clear_table();
     __syncthreads();
 
@@ -654,7 +681,7 @@ struct SearchWave {
 };
 
 template <int BITS, int LPR, int M, int PMAX>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? 5 : 4))) void search_kernel(SearchArgs args) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? 5 : (M == 4 ? 4 : 3)))) void search_kernel(SearchArgs args) {
   extern __shared__ uint64_t smem[];
   const uint32_t qi = blockIdx.x;
   if (qi >= args.nq) return;
