@@ -1,723 +1,7 @@
-// Batched best-first graph search: Algorithm 1 of the paper ("Deterministic
-// Access Greedy Search"), one query per wavefront.
-//
-// Mapping of the algorithm's steps onto a 64-lane wavefront:
-//   pool C          sorted array of (key, id) pairs in registers, striped:
-//                   entry i lives in register i/64 of lane i%64.  The low word
-//                   is (id << 1) | expanded, so pairs compare as plain u64.
-//   visited set V   in LDS, either a direct-mapped cache of node ids (one
-//                   exchange per test, may forget) or an open-addressing hash
-//                   table with test-and-set by CAS (complete while it fits).
-//   for j in G_i    one lane per adjacency slot: all ids of the row are
-//                   tested against V first, survivors are compacted (the
-//                   "deterministic access" batch filter), and only their code
-//                   rows are fetched.
-//   tau_l           LPR lanes share one code row, four 16-byte chunks per lane
-//                   (interleaved, so one load instruction reads LPR*16
-//                   contiguous bytes of each row); packed int8 dot products,
-//                   reduced across the LPR lanes with DPP.  128-byte rows: two
-//                   lanes per row, 32 rows per instruction group.
-//   insert          all candidates of a step that beat the pool's last entry
-//                   are merged at once: each candidate finds its rank among
-//                   the pool entries by binary search in a sorted LDS copy of
-//                   the pool and its rank among the other candidates by
-//                   counting; each pool entry moves up by the number of
-//                   candidates below it (prefix sums over a histogram of the
-//                   candidates' ranks); both scatter to their final positions
-//                   through LDS, which leaves the next sorted copy behind.
-// The pool after a step is the ef smallest (key, id) pairs among the old pool
-// and the step's new candidates, which is what sequential insertion in row
-// order gives; so with one expansion per step results equal a sequential
-// execution bit for bit.  With P > 1 expansions per step the P closest
-// un-expanded entries are expanded together (rows filtered in that order).
-#include "ann_internal.hpp"
-#include "device_utils.hpp"
+// Host entry point of the batched graph search: argument checks, choice of the
+// visited set and of the kernel family, launch (kernels: search_kernel.hpp).
+#include "search_kernel.hpp"
 
-namespace ann {
-
-constexpr uint32_t kEmpty = 0xFFFFFFFFu;
-
-struct SearchArgs {
-  const uint8_t *codes;
-  const float *norm_term;
-  const uint32_t *adjacency;
-  const uint8_t *tq;
-  const float *s;
-  const float *qlo;
-  const int32_t *sum_t;
-  const uint32_t *entry_ids;
-  const float *labels;  // [n][degree] edge labels or nullptr
-  const uint8_t *prs_codes;  // [n][degree][row_stride] code rows of every node's neighbours, or nullptr
-  const float *prs_norm;     // [n][degree] their norm terms (L2), or nullptr
-  uint32_t *out_ids;
-  float *out_keys;
-  int32_t *out_idot;
-  uint32_t *out_counts;
-  uint64_t n;
-  uint32_t row_stride, n_chunks, degree, metric, tq_stride, n_entry, entry_point, ef, vis_log2, nq, p;
-  uint32_t filtered;  // the label test and/or the per-expansion cap m_s is active
-  uint32_t vis_cache;  // visited set is the direct-mapped cache
-  uint32_t m_s;
-  float alpha_s;
-};
-
-__device__ __forceinline__ uint64_t pack64(uint32_t hi, uint32_t lo) { return ((uint64_t)hi << 32) | lo; }
-
-// v with lane `lane` replaced by the wave-uniform `value` (v_writelane_b32; on
-// this ISA the lane select of a write with a scalar value goes through m0).
-__device__ __forceinline__ int write_lane(int v, int value, int lane) {
-  int saved_m0;
-  asm volatile(
-      "s_mov_b32 %1, m0\n\t"
-      "s_mov_b32 m0, %3\n\t"
-      "v_writelane_b32 %0, %2, m0\n\t"
-      "s_mov_b32 m0, %1"
-      : "+v"(v), "=&s"(saved_m0)
-      : "s"(value), "s"(lane));
-  return v;
-}
-
-__device__ __forceinline__ int lanes_below(uint64_t mask) {
-  return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
-}
-
-// The merge scatter buffer: the sorted pool (64 m slots) plus up to 64
-// candidates.  After a merge it holds the new pool in order.
-__host__ __device__ constexpr int merge_buf_entries(int m) { return 64 * m + 64; }
-// Staging area of a step's qualifying candidates; during a merge (candidates
-// are in registers then) it serves as 2 * 64 m integer counters.
-__host__ __device__ constexpr int stage_entries(int m) { return 64 * m; }
-
-// Ids of one step's unvisited neighbours: up to pmax rows of `degree` ids.
-__host__ __device__ inline uint32_t cand_entries(uint32_t degree, int pmax) {
-  return (degree <= 32 ? 32u : 64u) * (uint32_t)pmax;
-}
-
-// LDS bytes for one query: merge buffer, staging, visited set, candidate ids, folded query.
-__host__ __device__ inline size_t search_smem_bytes(int m, int pmax, uint32_t vis_log2, uint32_t degree, uint32_t tq_stride) {
-  return (size_t)(merge_buf_entries(m) + stage_entries(m)) * 8 + ((size_t)1 << vis_log2) * 4 +
-         (size_t)cand_entries(degree, pmax) * 4 + tq_stride;
-}
-
-template <int BITS, int LPR, int M, int PMAX>
-struct SearchWave {
-  static constexpr int G = kWave / LPR;      // code rows evaluated side by side
-  static constexpr int CPL = 4;              // 16-byte chunks of a row per lane
-  static constexpr int U = PMAX > 1 ? 2 : 1;  // groups of G rows in flight
-  static constexpr int TQW = TqRegs<BITS>::kWords;
-
-  const SearchArgs &a;
-  uint64_t *mbuf;   // LDS: sorted copy of the pool as of the last merge; merge scatter buffer
-  uint64_t *stage;  // LDS: a step's qualifying candidates; counters during a merge
-  uint32_t *vis;   // LDS [cap]
-  uint32_t *cand;  // LDS: unvisited neighbour ids of this step
-  const int *tql;  // LDS: the folded query, TQW words per 16-byte code chunk
-  int lane, sub, grp;
-  uint32_t coff[CPL];  // byte offsets of this lane's chunks inside a code row
-  uint32_t vis_mask, vis_shift, vis_limit;
-  float s, qlo;
-  int bias;
-  uint32_t pk[M], pv[M];  // pool: ordered key bits; (id << 1) | expanded
-  uint64_t worst;         // pool entry ef-1 (all ones while the pool is not full)
-  uint32_t n_exp = 0, n_dist = 0, n_vis = 0, n_rebuild = 0;
-
-  __device__ __forceinline__ SearchWave(const SearchArgs &args, uint64_t *smem) : a(args) {
-    lane = lane_id();
-    sub = lane % LPR;
-    grp = lane / LPR;
-#pragma unroll
-    for (int j = 0; j < CPL; ++j) {
-      // chunks past the end of the row are read from the last chunk instead;
-      // their share of the folded query is zero
-      const uint32_t c = (uint32_t)(sub + j * LPR);
-      coff[j] = (c < a.n_chunks ? c : a.n_chunks - 1) * 16u;
-    }
-    const uint32_t cap = 1u << a.vis_log2;
-    mbuf = smem;
-    stage = mbuf + merge_buf_entries(M);
-    vis = reinterpret_cast<uint32_t *>(stage + stage_entries(M));
-    cand = vis + cap;
-    tql = reinterpret_cast<const int *>(cand + cand_entries(a.degree, PMAX));
-    vis_mask = cap - 1;
-    vis_shift = 32 - a.vis_log2;
-    vis_limit = a.vis_cache ? 0xFFFFFFFFu : cap - cap / 4;  // the cache is never rebuilt
-  }
-
-  // This lane's part of the code/query dot product of one row: its four
-  // chunks against the matching words of the folded query.
-  __device__ __forceinline__ int row_dot(const uint4 (&row)[CPL]) const {
-    int dot = 0;
-#pragma unroll
-    for (int j = 0; j < CPL; ++j) {
-      int t[TQW];
-      const int4 *tp = reinterpret_cast<const int4 *>(tql + (sub + j * LPR) * TQW);
-#pragma unroll
-      for (int w = 0; w < TQW / 4; ++w) {
-        const int4 v = tp[w];
-        t[4 * w] = v.x;
-        t[4 * w + 1] = v.y;
-        t[4 * w + 2] = v.z;
-        t[4 * w + 3] = v.w;
-      }
-      dot += chunk_dot<BITS>(row[j], t);
-    }
-    return dot;
-  }
-
-  __device__ __forceinline__ void clear_table() {
-    for (uint32_t i = lane; i <= vis_mask; i += kWave) vis[i] = kEmpty;
-  }
-
-  // Direct-mapped cache: a node's slot holds the last id hashed to it.  The
-  // exchange makes lanes that test the same id in one instruction see each
-  // other.  A displaced id is forgotten; it may come back as a candidate and is
-  // then recognised when it is merged (it equals a pool entry or another
-  // candidate) or rejected again by the pool's last entry.
-  __device__ __forceinline__ bool cache_test_and_set(uint32_t id) {
-    return atomicExch(&vis[(id * 0x9E3779B1u) >> vis_shift], id) != id;
-  }
-
-  // true if id was not in the table (and now is)
-  __device__ __forceinline__ bool test_and_set(uint32_t id) {
-    if (a.vis_cache) return cache_test_and_set(id);
-    // double hashing: the probe stride is odd, so every slot is reached
-    const uint32_t h = id * 0x9E3779B1u;
-    uint32_t slot = h >> vis_shift;
-    const uint32_t stride = ((h >> 4) | 1u) & vis_mask;
-    for (;;) {
-      uint32_t old = atomicCAS(&vis[slot], kEmpty, id);
-      if (old == kEmpty) return true;
-      if (old == id) return false;
-      slot = (slot + stride) & vis_mask;
-    }
-  }
-
-  // Membership test without insertion.
-  __device__ __forceinline__ bool lookup(uint32_t id) {
-    if (a.vis_cache) return vis[(id * 0x9E3779B1u) >> vis_shift] == id;
-    const uint32_t h = id * 0x9E3779B1u;
-    uint32_t slot = h >> vis_shift;
-    const uint32_t stride = ((h >> 4) | 1u) & vis_mask;
-    for (;;) {
-      const uint32_t cur = vis[slot];
-      if (cur == id) return true;
-      if (cur == kEmpty) return false;
-      slot = (slot + stride) & vis_mask;
-    }
-  }
-
-  // Two ids per lane at once: the two probe sequences advance together, so
-  // the latency of the LDS atomics overlaps.  Bit 0 / bit 1 of the result: id0
-  // / id1 was not in the table (and now is).  A lane's two ids may be equal.
-  __device__ __forceinline__ int test_and_set2(bool v0, uint32_t id0, bool v1, uint32_t id1) {
-    if (a.vis_cache) {
-      uint32_t o0 = id0, o1 = id1;
-      if (v0) o0 = atomicExch(&vis[(id0 * 0x9E3779B1u) >> vis_shift], id0);
-      if (v1) o1 = atomicExch(&vis[(id1 * 0x9E3779B1u) >> vis_shift], id1);
-      return (o0 != id0 ? 1 : 0) | (o1 != id1 ? 2 : 0);
-    }
-    const uint32_t h0 = id0 * 0x9E3779B1u, h1 = id1 * 0x9E3779B1u;
-    uint32_t s0 = h0 >> vis_shift, s1 = h1 >> vis_shift;
-    const uint32_t st0 = ((h0 >> 4) | 1u) & vis_mask, st1 = ((h1 >> 4) | 1u) & vis_mask;
-    int fresh = 0;
-    while (v0 || v1) {
-      uint32_t o0 = 0, o1 = 0;
-      if (v0) o0 = atomicCAS(&vis[s0], kEmpty, id0);
-      if (v1) o1 = atomicCAS(&vis[s1], kEmpty, id1);
-      if (v0) {
-        if (o0 == kEmpty) {
-          fresh |= 1;
-          v0 = false;
-        } else if (o0 == id0) {
-          v0 = false;
-        } else {
-          s0 = (s0 + st0) & vis_mask;
-        }
-      }
-      if (v1) {
-        if (o1 == kEmpty) {
-          fresh |= 2;
-          v1 = false;
-        } else if (o1 == id1) {
-          v1 = false;
-        } else {
-          s1 = (s1 + st1) & vis_mask;
-        }
-      }
-    }
-    return fresh;
-  }
-
-  // The table holds every node whose key has been evaluated, as long as it
-  // fits.  When it is about to pass 3/4 load it is rebuilt from the pool.  A
-  // forgotten node is outside the pool, so it was rejected or evicted by a
-  // pool maximum that has only decreased since: re-evaluating it yields the
-  // same key and the same rejection.  Results do not change; work is repeated.
-  __device__ __forceinline__ void rebuild_table() {
-    __syncthreads();
-    clear_table();
-    __syncthreads();
-    int kept = 0;
-#pragma unroll
-    for (int r = 0; r < M; ++r)
-      if (pk[r] != kEmpty) {
-        test_and_set(pv[r] >> 1);
-        ++kept;
-      }
-    n_vis = (uint32_t)group_sum_i32<64>(kept);
-    ++n_rebuild;
-    __syncthreads();
-  }
-
-  __device__ __forceinline__ void refresh_worst() {
-    const int g = (int)a.ef - 1, rr = g / kWave, rl = g % kWave;
-    uint32_t k_ = pk[0], v_ = pv[0];
-#pragma unroll
-    for (int r = 1; r < M; ++r) {
-      k_ = (rr == r) ? pk[r] : k_;
-      v_ = (rr == r) ? pv[r] : v_;
-    }
-    worst = pack64(__builtin_amdgcn_readlane(k_, rl), __builtin_amdgcn_readlane(v_, rl));
-  }
-
-  // Merge up to 64 candidates (one per lane where `have`) into the pool.
-  //
-  // mbuf[0 .. 64 M) is the pool in order as the last merge left it (expanded
-  // marks may be out of date, which no comparison below depends on); slots
-  // behind the pool hold all-ones or entries that were pushed out, all of them
-  // above any candidate that beats the pool's last entry.
-  __device__ __forceinline__ void merge(bool have, uint32_t ck, uint32_t cv) {
-    const uint64_t c64 = pack64(ck, cv);
-    bool mine = have && c64 < worst;
-    if (__ballot(mine) == 0) return;
-    // number of pool entries below the candidate: lower bound over slots
-    // 0 .. 64 M - 2 (a candidate that beats the last entry ranks below 64 M)
-    uint32_t pos = 0;  // byte offset into mbuf
-#pragma unroll
-    for (int step = 32 * M; step >= 1; step >>= 1) {
-      const uint64_t e = *reinterpret_cast<const uint64_t *>(reinterpret_cast<const char *>(mbuf) + pos + (step - 1) * 8);
-      pos += e < c64 ? (uint32_t)step * 8u : 0u;
-    }
-    // A node the visited set has forgotten can come back.  If it is in the
-    // pool, the entry found is that node (ids are unique in the pool): dropped.
-    const uint32_t at_id = (uint32_t)*reinterpret_cast<const uint64_t *>(reinterpret_cast<const char *>(mbuf) + pos);
-    mine = mine && (at_id | 1u) != (cv | 1u);
-    uint64_t km = __ballot(mine);
-    if (km == 0) return;
-    const int rank_p = (int)(pos >> 3);
-    int *cnt = reinterpret_cast<int *>(stage);
-    int shift[M];
-    int dest;
-    for (;;) {
-      // pool entry i moves up by the number of candidates with rank <= i
-#pragma unroll
-      for (int r = 0; r < M; ++r) cnt[r * kWave + lane] = 0;
-      __syncthreads();
-      if (mine) atomicAdd(&cnt[rank_p], 1);
-      __syncthreads();
-      int carry = 0;
-#pragma unroll
-      for (int r = 0; r < M; ++r) {
-        shift[r] = wave_inclusive_scan_i32(cnt[r * kWave + lane]) + carry;
-        carry = __builtin_amdgcn_readlane(shift[r], kWave - 1);
-      }
-      // candidates below this lane's candidate
-      int below_c = 0;
-      for (uint64_t m = km; m; m &= m - 1) {
-        const int l = __builtin_ctzll(m);
-        const uint64_t s64 = pack64(__builtin_amdgcn_readlane(ck, l), __builtin_amdgcn_readlane(cv, l));
-        below_c += s64 < c64 ? 1 : 0;
-      }
-      dest = rank_p + below_c;
-      // The same forgotten node twice among the candidates: equal values get
-      // equal destinations.  One of them stays, the count starts over (rare).
-      __syncthreads();
-      if (mine) cnt[dest] = lane;
-      __syncthreads();
-      const uint64_t lose = __ballot(mine && cnt[dest] != lane);
-      if (lose == 0) break;
-      km &= ~lose;
-      mine = mine && ((lose >> lane) & 1ull) == 0;
-      __syncthreads();
-    }
-    const int n_m = __popcll(km);
-    // no two (key, id) pairs are equal: the destinations are a permutation
-#pragma unroll
-    for (int r = 0; r < M; ++r) mbuf[r * kWave + lane + shift[r]] = pack64(pk[r], pv[r]);
-    if (mine) mbuf[dest] = c64;
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < M; ++r) {
-      const uint64_t v = mbuf[r * kWave + lane];
-      const bool beyond = r * kWave + lane >= (int)a.ef;  // entries pushed past ef are dropped
-      pk[r] = beyond ? kEmpty : (uint32_t)(v >> 32);
-      pv[r] = beyond ? kEmpty : (uint32_t)v;
-    }
-    __syncthreads();
-    (void)n_m;
-    refresh_worst();
-  }
-
-  // Visited filter and compaction for one list of node ids (one per lane):
-  // unvisited ids are marked and appended to cand[n_cand ..].
-  __device__ __forceinline__ void filter_ids(uint32_t nb, int &n_cand) {
-    const bool valid = nb != kEmpty && nb < a.n;
-    const bool fresh = valid && test_and_set(nb);
-    const uint64_t fm = __ballot(fresh);
-    if (fresh) cand[n_cand + lanes_below(fm)] = nb;
-    n_cand += __popcll(fm);
-  }
-
-  // The same with the cap of Algorithm 1's inner condition |N| < m_s: only the
-  // first m_s unvisited ids (in lane = stored order) are taken and marked;
-  // the others stay unvisited.
-  __device__ __forceinline__ void filter_ids_capped(uint32_t nb, uint32_t m_s, int &n_cand) {
-    const bool valid = nb != kEmpty && nb < a.n;
-    const bool open = valid && !lookup(nb);
-    const uint64_t om = __ballot(open);
-    const bool take = open && (uint32_t)lanes_below(om) < m_s;
-    __syncthreads();
-    const bool fresh = take && test_and_set(nb);
-    const uint64_t fm = __ballot(fresh);
-    if (fresh) cand[n_cand + lanes_below(fm)] = nb;
-    n_cand += __popcll(fm);
-  }
-
-  // Same for two lists at once (list 0's survivors are appended first).
-  __device__ __forceinline__ void filter_ids2(uint32_t nb0, uint32_t nb1, int &n_cand) {
-    const int f = test_and_set2(nb0 != kEmpty && nb0 < a.n, nb0, nb1 != kEmpty && nb1 < a.n, nb1);
-    const uint64_t fm0 = __ballot(f & 1), fm1 = __ballot(f & 2);
-    const int c0 = __popcll(fm0);
-    if (f & 1) cand[n_cand + lanes_below(fm0)] = nb0;
-    if (f & 2) cand[n_cand + c0 + lanes_below(fm1)] = nb1;
-    n_cand += c0 + __popcll(fm1);
-  }
-
-  // Merge the n_q staged candidates into the pool, 64 at a time (they are
-  // copied to registers first: a merge uses the staging area for its counters).
-  static constexpr int kStage = stage_entries(M);
-  __device__ __forceinline__ void merge_staged(int &n_q) {
-    if (n_q == 0) return;
-    __syncthreads();
-    uint64_t batch[M];
-#pragma unroll
-    for (int b = 0; b < M; ++b) batch[b] = b * kWave + lane < n_q ? stage[b * kWave + lane] : 0;
-    __syncthreads();
-    // one copy of the merge code, whatever M is: the batch is picked by selects
-#pragma nounroll
-    for (int b = 0; b * kWave < n_q; ++b) {
-      uint64_t c = batch[0];
-#pragma unroll
-      for (int t = 1; t < M; ++t) c = b == t ? batch[t] : c;
-      merge(b * kWave + lane < n_q, (uint32_t)(c >> 32), (uint32_t)c);
-    }
-    n_q = 0;
-  }
-
-  // tau_l for the n_cand nodes in cand[], then merge the ones that can enter
-  // the pool.
-  __device__ __forceinline__ void evaluate_and_merge(int n_cand) {
-    if (n_cand == 0) return;
-    n_vis += n_cand;
-    n_dist += n_cand;
-    __syncthreads();
-    int n_q = 0;
-    for (int base = 0; base < n_cand; base += G * U) {
-      uint4 rows[U][CPL];
-      float nrm[U];
-      uint32_t vid[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (base + u * G < n_cand) {
-          // lanes past the end of the list recompute its last node; the
-          // duplicate is ignored below, and no branch is needed around loads
-          const int ci = base + u * G + grp;
-          vid[u] = cand[ci < n_cand ? ci : n_cand - 1];
-          const uint8_t *rp = a.codes + (uint64_t)vid[u] * a.row_stride;
-#pragma unroll
-          for (int j = 0; j < CPL; ++j) rows[u][j] = *reinterpret_cast<const uint4 *>(rp + coff[j]);
-          nrm[u] = a.norm_term ? a.norm_term[vid[u]] : 0.0f;
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (base + u * G < n_cand) {
-          const int dot = group_sum_i32<LPR>(row_dot(rows[u])) + bias;
-          const float key = key_from_idot(a.metric, s, qlo, dot, nrm[u]);
-          const uint64_t c64 = pack64(order_u32(key), vid[u] << 1);
-          const bool q = sub == 0 && base + u * G + grp < n_cand && c64 < worst;
-          const uint64_t bm = __ballot(q);
-          if (n_q + G > kStage) merge_staged(n_q);  // rare: make room (the pool's last entry only gets smaller)
-          if (q) stage[n_q + lanes_below(bm)] = c64;
-          n_q += __popcll(bm);
-        }
-      }
-    }
-    merge_staged(n_q);
-  }
-
-  // Expansion with redundantly stored neighbour vectors (the paper's PRS
-  // layout, Section 3.3, with ratio 1): the code rows and norm terms of u's
-  // neighbours lie next to each other in slot order, so they are requested
-  // together with the id row - one memory round trip per expansion instead of
-  // two, sequential instead of scattered reads, and no compaction.  Rows of
-  // visited neighbours are fetched as well; only unvisited ones are counted and
-  // can enter the pool.
-  __device__ __forceinline__ void expand_prs(uint32_t uid, int &n_q) {
-    const uint64_t rowbase = (uint64_t)uid * a.degree;
-    const uint32_t nb = lane < (int)a.degree ? a.adjacency[rowbase + lane] : kEmpty;
-    uint64_t fm = 0;
-    for (int sg = 0; sg < (int)a.degree; sg += G) {
-      const int slot = sg + grp;
-      const uint64_t at = rowbase + (uint32_t)(slot < (int)a.degree ? slot : (int)a.degree - 1);
-      const uint8_t *rp = a.prs_codes + at * a.row_stride;
-      uint4 rows[CPL];
-#pragma unroll
-      for (int j = 0; j < CPL; ++j) rows[j] = *reinterpret_cast<const uint4 *>(rp + coff[j]);
-      const float nrm = a.prs_norm ? a.prs_norm[at] : 0.0f;
-      if (sg == 0) {
-        // all ids of the row against the visited set, while the rows are on their way
-        if (PMAX == 1) {
-          const uint32_t incoming = (uint32_t)__popcll(__ballot(nb != kEmpty));
-          if (n_vis + incoming > vis_limit) rebuild_table();
-        }
-        const bool fresh = nb != kEmpty && nb < a.n && test_and_set(nb);
-        fm = __ballot(fresh);
-        const int n_new = __popcll(fm);
-        n_vis += n_new;
-        n_dist += n_new;
-      }
-      const int dot = group_sum_i32<LPR>(row_dot(rows)) + bias;
-      const uint32_t vid = (uint32_t)__shfl((int)nb, slot & 63);
-      const float key = key_from_idot(a.metric, s, qlo, dot, nrm);
-      const uint64_t c64 = pack64(order_u32(key), vid << 1);
-      const bool q = sub == 0 && slot < (int)a.degree && ((fm >> (slot & 63)) & 1ull) && c64 < worst;
-      const uint64_t bm = __ballot(q);
-      if (n_q + G > kStage) merge_staged(n_q);
-      if (q) stage[n_q + lanes_below(bm)] = c64;
-      n_q += __popcll(bm);
-    }
-  }
-
-  __device__ __forceinline__ void run(uint32_t qi) {
-    // the folded query goes to LDS: it is read again for every group of rows
-    // (keeping it in registers costs a wavefront of occupancy)
-    {
-      const int *src = reinterpret_cast<const int *>(a.tq + (uint64_t)qi * a.tq_stride);
-      int *dst = const_cast<int *>(tql);
-      for (uint32_t i = lane; i < a.tq_stride / 4; i += kWave) dst[i] = src[i];
-    }
-    s = a.s[qi];
-    qlo = a.qlo[qi];
-    bias = BITS == 8 ? 128 * a.sum_t[qi] : 0;
-#pragma unroll
-    for (int r = 0; r < M; ++r) {
-      pk[r] = kEmpty;
-      pv[r] = kEmpty;
-    }
-    worst = ~0ull;
-#pragma unroll
-    for (int r = 0; r <= M; ++r) mbuf[r * kWave + lane] = ~0ull;  // the empty pool, in order
-    clear_table();
-    __syncthreads();
-
-    // initial nodes I: into the pool and into V
-    {
-      uint32_t nb = kEmpty;
-      if (a.entry_ids) {
-        if (lane < (int)a.n_entry) nb = a.entry_ids[(uint64_t)qi * a.n_entry + lane];
-      } else if (lane == 0) {
-        nb = a.entry_point;
-      }
-      int n_cand = 0;
-      filter_ids(nb, n_cand);
-      evaluate_and_merge(n_cand);
-    }
-
-    const int p = PMAX == 1 ? 1 : (int)a.p;
-    uint32_t pre_id = kEmpty, pre_row = kEmpty;  // adjacency row fetched ahead (PMAX == 1)
-    for (;;) {
-      // the p closest un-expanded pool entries; lane e of `picked` gets the e-th
-      uint32_t picked = kEmpty, next_id = kEmpty;
-      int got = 0;
-#pragma unroll
-      for (int r = 0; r < M; ++r) {
-        uint64_t um = __ballot((pv[r] & 1u) == 0);
-        while (um != 0 && got < p) {
-          const int L = __builtin_ctzll(um);
-          um &= um - 1;
-          picked = lane == got ? (uint32_t)__builtin_amdgcn_readlane(pv[r], L) >> 1 : picked;
-          pv[r] |= lane == L ? 1u : 0u;
-          ++got;
-        }
-        if (PMAX == 1 && got == p && next_id == kEmpty && um != 0)
-          next_id = __builtin_amdgcn_readlane(pv[r], __builtin_ctzll(um)) >> 1;
-      }
-      if (got == 0) break;
-      n_exp += got;
-      if (PMAX > 1 && !a.vis_cache && n_vis + (uint32_t)(got * kWave) > vis_limit) rebuild_table();
-
-      if (a.prs_codes) {
-        int n_q = 0;
-        for (int e = 0; e < got; ++e) expand_prs(__builtin_amdgcn_readlane(picked, e), n_q);
-        merge_staged(n_q);
-        continue;
-      }
-      int n_cand = 0;
-      if (a.filtered) {
-        // label test and per-expansion cap: rows one after the other, in
-        // the order of the picked entries
-        for (int e = 0; e < got; ++e) {
-          const uint32_t uid = __builtin_amdgcn_readlane(picked, e);
-          uint32_t nb = kEmpty;
-          if (lane < (int)a.degree) {
-            const uint64_t at = (uint64_t)uid * a.degree + lane;
-            nb = a.adjacency[at];
-            if (a.labels && !(a.labels[at] <= a.alpha_s)) nb = kEmpty;
-          }
-          if (PMAX == 1) {
-            const uint32_t incoming = (uint32_t)__popcll(__ballot(nb != kEmpty));
-            if (n_vis + incoming > vis_limit) rebuild_table();
-          }
-          filter_ids_capped(nb, a.m_s, n_cand);
-        }
-      } else if (PMAX > 1 && a.degree <= 32) {
-        // two adjacency rows per pass: lanes 0-31 take one, lanes 32-63 the next
-        const int slot = lane & 31;
-        uint32_t rows[PMAX / 2 > 0 ? PMAX / 2 : 1];
-#pragma unroll
-        for (int t = 0; t < PMAX / 2; ++t) {
-          rows[t] = kEmpty;
-          if (2 * t < got) {
-            const uint32_t u0 = __builtin_amdgcn_readlane(picked, 2 * t);
-            const uint32_t u1 = __builtin_amdgcn_readlane(picked, 2 * t + 1);
-            const uint32_t uid = lane < 32 ? u0 : u1;
-            if (uid != kEmpty && slot < (int)a.degree) rows[t] = a.adjacency[(uint64_t)uid * a.degree + slot];
-          }
-        }
-#pragma unroll
-        for (int t = 0; t < PMAX / 2; t += 2) {
-          if (t + 1 < PMAX / 2 && 2 * (t + 1) < got)
-            filter_ids2(rows[t], rows[t + 1 < PMAX / 2 ? t + 1 : t], n_cand);
-          else if (2 * t < got)
-            filter_ids(rows[t], n_cand);
-        }
-      } else {
-        uint32_t rows[PMAX];
-#pragma unroll
-        for (int e = 0; e < PMAX; ++e) {
-          rows[e] = kEmpty;
-          if (e < got) {
-            const uint32_t uid = __builtin_amdgcn_readlane(picked, e);
-            if (PMAX == 1 && uid == pre_id)
-              rows[e] = pre_row;
-            else if (lane < (int)a.degree)
-              rows[e] = a.adjacency[(uint64_t)uid * a.degree + lane];
-          }
-        }
-        if (PMAX == 1) {
-          // fetch ahead the row of the entry that is expanded next unless a
-          // candidate of this step overtakes it
-          pre_id = next_id;
-          pre_row = kEmpty;
-          if (next_id != kEmpty && lane < (int)a.degree) pre_row = a.adjacency[(uint64_t)next_id * a.degree + lane];
-        }
-#pragma unroll
-        for (int e = 0; e < PMAX; ++e) {
-          if (e < got) {
-            if (PMAX == 1) {
-              const uint32_t incoming = (uint32_t)__popcll(__ballot(rows[e] != kEmpty));
-              if (n_vis + incoming > vis_limit) rebuild_table();
-            }
-            filter_ids(rows[e], n_cand);
-          }
-        }
-      }
-      evaluate_and_merge(n_cand);
-    }
-
-    // results (pool index r*64 + lane: coalesced)
-    int kept = 0;
-#pragma unroll
-    for (int r = 0; r < M; ++r) {
-      const uint32_t i = r * kWave + lane;
-      const bool live = pk[r] != kEmpty;
-      kept += __popcll(__ballot(live));
-      if (i < a.ef) {
-        a.out_ids[(uint64_t)qi * a.ef + i] = live ? (pv[r] >> 1) : kEmpty;
-        if (a.out_keys) a.out_keys[(uint64_t)qi * a.ef + i] = live ? unorder_f32(pk[r]) : INFINITY;
-      }
-    }
-    if (a.out_idot) {
-      // same arithmetic as during traversal, over the final pool
-      __syncthreads();
-      uint32_t *st_id = reinterpret_cast<uint32_t *>(mbuf);
-#pragma unroll
-      for (int r = 0; r < M; ++r) st_id[r * kWave + lane] = pk[r] != kEmpty ? (pv[r] >> 1) : kEmpty;
-      __syncthreads();
-      for (int base = 0; base < (int)a.ef; base += G) {
-        const int ci = base + grp;
-        const uint32_t v = ci < (int)a.ef ? st_id[ci] : kEmpty;
-        int dot = 0;
-        if (v != kEmpty) {
-          const uint8_t *rp = a.codes + (uint64_t)v * a.row_stride;
-          uint4 row[CPL];
-#pragma unroll
-          for (int j = 0; j < CPL; ++j) row[j] = *reinterpret_cast<const uint4 *>(rp + coff[j]);
-          dot = row_dot(row);
-        }
-        dot = group_sum_i32<LPR>(dot) + bias;
-        if (sub == 0 && ci < (int)a.ef) a.out_idot[(uint64_t)qi * a.ef + ci] = v != kEmpty ? dot : 0;
-      }
-    }
-    if (a.out_counts && lane == 0) {
-      uint32_t *c = a.out_counts + (uint64_t)qi * 4;
-      c[0] = n_exp;
-      c[1] = n_dist;
-      c[2] = (uint32_t)kept;
-      c[3] = n_rebuild;
-    }
-  }
-};
-
-template <int BITS, int LPR, int M, int PMAX>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? 5 : (M == 4 ? 4 : 3)))) void search_kernel(SearchArgs args) {
-  extern __shared__ uint64_t smem[];
-  const uint32_t qi = blockIdx.x;
-  if (qi >= args.nq) return;
-  SearchWave<BITS, LPR, M, PMAX> w(args, smem);
-  w.run(qi);
-}
-
-template <int BITS, int LPR, int PMAX>
-static ann_status launch_m(const SearchArgs &args, int m, hipStream_t st) {
-  const size_t smem = search_smem_bytes(m, PMAX, args.vis_log2, args.degree, args.tq_stride);
-  switch (m) {
-    case 1: search_kernel<BITS, LPR, 1, PMAX><<<args.nq, 64, smem, st>>>(args); break;
-    case 2: search_kernel<BITS, LPR, 2, PMAX><<<args.nq, 64, smem, st>>>(args); break;
-    case 4: search_kernel<BITS, LPR, 4, PMAX><<<args.nq, 64, smem, st>>>(args); break;
-    case 8: search_kernel<BITS, LPR, 8, PMAX><<<args.nq, 64, smem, st>>>(args); break;
-    default: return fail(ANN_EUNSUPPORTED, "no kernel for pool registers per lane = %d", m);
-  }
-  ANN_HIP(hipGetLastError());
-  return ANN_OK;
-}
-
-template <int BITS, int PMAX>
-static ann_status launch_lpr(const SearchArgs &args, uint32_t lpr, int m, hipStream_t st) {
-  switch (lpr) {
-    case 1: return launch_m<BITS, 1, PMAX>(args, m, st);
-    case 2: return launch_m<BITS, 2, PMAX>(args, m, st);
-    case 4: return launch_m<BITS, 4, PMAX>(args, m, st);
-    case 8: return launch_m<BITS, 8, PMAX>(args, m, st);
-    case 16: return launch_m<BITS, 16, PMAX>(args, m, st);
-    default: return fail(ANN_EUNSUPPORTED, "no kernel for %u lanes per code row", lpr);
-  }
-}
-
-constexpr int kMaxExpansionsPerStep = 4;
-
-}  // namespace ann
 
 using namespace ann;
 
@@ -810,8 +94,8 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   a.p = p;
   int m = 1;
   while (64 * m < (int)ef) m <<= 1;
-  if (params->mode == 0)
-    return L.bits == 8 ? launch_lpr<8, 1>(a, L.search_lanes, m, st) : launch_lpr<4, 1>(a, L.search_lanes, m, st);
-  return L.bits == 8 ? launch_lpr<8, kMaxExpansionsPerStep>(a, L.search_lanes, m, st)
-                     : launch_lpr<4, kMaxExpansionsPerStep>(a, L.search_lanes, m, st);
+  const bool multi = params->mode != 0;
+  const bool fast = cache && !a.filtered && !a.prs_codes && (!multi || (index->degree <= 32 && p == (uint32_t)kMaxExpansionsPerStep));
+  return fast ? launch_search_fast(a, L.bits, L.search_lanes, m, multi, st)
+              : launch_search_general(a, L.bits, L.search_lanes, m, multi, st);
 }
