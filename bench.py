@@ -26,6 +26,26 @@ sys.path.insert(0, str(ROOT))
 
 HBM_PEAK_GBS = 8000.0
 
+# Memory-side traffic of one search launch (bytes the L2 read from / wrote to the
+# fabric: rocprofv3 FETCH_SIZE scaled by the factor a plain copy kernel of known
+# size shows for the same counter, 2.0, plus WRITE_SIZE, factor 1.0; the summary
+# is under profiles/).  A measurement belongs to the kernel sources it was taken
+# with and to the default configuration of this script; any change voids it.
+KERNEL_SOURCES = ("paper_2503_17911_amd/csrc/search_kernel.hpp", "paper_2503_17911_amd/csrc/device_utils.hpp",
+                  "paper_2503_17911_amd/csrc/search.hip")
+MEASURED_TRAFFIC = {
+    # sha256 of KERNEL_SOURCES -> bytes per launch on c2, ef=128, multi-expansion, 10,000 queries
+    "2a40675814cf82c0be6a17993b39da8f73e00ee96dabcebb4bb1c46df313d607": 1918258 * 1024 * 2.0 + 5002 * 1024 * 1.0,
+}
+
+
+def kernel_source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        h.update((ROOT / rel).read_bytes())
+    return h.hexdigest()
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -57,7 +77,11 @@ def main():
     ap.add_argument("--n-entry", type=int, default=1, help="initial nodes per query taken from the pivot scan")
     ap.add_argument("--layout", type=int, default=0, help="1: redundant neighbour-code layout (PRS)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--print-kernel-hash", action="store_true", help="print the hash MEASURED_TRAFFIC is keyed by, and exit")
     args = ap.parse_args()
+    if args.print_kernel_hash:
+        print(kernel_source_hash())
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (query sharding across GPUs needs no exchange; "
                  "see DESIGN.md); run with --gpus 1")
@@ -303,6 +327,9 @@ def main():
                     f"{nq / ms_v * 1e3:,.0f} QPS (scan + search + rerank)")
                 break
 
+    default_config = (args.workload == "c2" and not args.n and not args.nq and not args.visited_slots and not args.visited_kind
+                      and not args.pivots and not args.layout and not args.expansions and ef == 128 and mode == 1)
+    traffic = MEASURED_TRAFFIC.get(kernel_source_hash()) if default_config else None
     result = {
         "metric": "queries/sec at recall@10>=0.95 (1M x 128 SQ8, ef sweep)",
         "value": round(qps, 1),
@@ -333,7 +360,7 @@ def main():
                          "note": "set-up, outside the timed region; wall time of the whole call"},
         "roofline": {"bound": "hbm", "kernel": "search_kernel (one expansion per step)" if mode == 0 else "search_kernel (multi-expansion)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": bytes_search, "kernel_ms": round(kernel_ms, 4),
                      "rerank_bytes_per_launch": bytes_rerank, "rerank_ms": round(ms_per_step - search_ms, 4)},
     }
