@@ -35,7 +35,7 @@ KERNEL_SOURCES = ("paper_2503_17911_amd/csrc/search_kernel.hpp", "paper_2503_179
                   "paper_2503_17911_amd/csrc/search.hip")
 MEASURED_TRAFFIC = {
     # sha256 of KERNEL_SOURCES -> bytes per launch on c2, ef=128, multi-expansion, 10,000 queries
-    "2a40675814cf82c0be6a17993b39da8f73e00ee96dabcebb4bb1c46df313d607": 1918258 * 1024 * 2.0 + 5002 * 1024 * 1.0,
+    "f4751bf0791e2effea2e79637daa1eff9a961f53ab608d7b96d3b6a85adddad0": 1918258 * 1024 * 2.0 + 5002 * 1024 * 1.0,
 }
 
 
@@ -76,6 +76,8 @@ def main():
                     help="entry-point stage: scan this many sampled base vectors per query (0 = start at the medoid)")
     ap.add_argument("--n-entry", type=int, default=1, help="initial nodes per query taken from the pivot scan")
     ap.add_argument("--layout", type=int, default=0, help="1: redundant neighbour-code layout (PRS)")
+    ap.add_argument("--coverage", type=float, default=1.0,
+                    help="codebook range: 1 = per-dimension min/max, below 1 = truncated (symmetric order statistics)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--print-kernel-hash", action="store_true", help="print the hash MEASURED_TRAFFIC is keyed by, and exit")
     args = ap.parse_args()
@@ -119,13 +121,27 @@ def main():
     delta = torch.empty(d, dtype=torch.float32, device=dev)
     codes = torch.empty((n, d if bits == 8 else d // 2), dtype=torch.uint8, device=dev)
     norm = torch.empty(n, dtype=torch.float32, device=dev)
-    ann.ann_sq_train(xd, n, d, bits, lo, delta, st)
+    if args.coverage < 1.0:
+        ann.ann_sq_train_truncated(xd, n, d, bits, args.coverage, lo, delta, st)
+    else:
+        ann.ann_sq_train(xd, n, d, bits, lo, delta, st)
     ann.ann_sq_encode(xd, n, d, bits, lo, delta, codes, norm, st)
+    levels = [(bits, codes, lo, delta, norm)]
+    if len(w.bits) > 1:
+        # second, finer code level for the rescore stage of the cascade (low -> higher -> full precision)
+        b2 = w.bits[1]
+        lo2 = torch.empty(d, dtype=torch.float32, device=dev)
+        delta2 = torch.empty(d, dtype=torch.float32, device=dev)
+        codes2 = torch.empty((n, d if b2 == 8 else d // 2), dtype=torch.uint8, device=dev)
+        norm2 = torch.empty(n, dtype=torch.float32, device=dev)
+        ann.ann_sq_train(xd, n, d, b2, lo2, delta2, st)
+        ann.ann_sq_encode(xd, n, d, b2, lo2, delta2, codes2, norm2, st)
+        levels.append((b2, codes2, lo2, delta2, norm2))
     adj_d = torch.from_numpy(adj.view(np.int32)).to(dev)
     index = ann.ann_upload_index(n=n, d=d, degree=adj.shape[1], metric=metric, vectors=xd,
-                                 levels=[(bits, codes, lo, delta, norm)], adjacency=adj_d, entry_point=entry,
+                                 levels=levels, adjacency=adj_d, entry_point=entry,
                                  stream=st)
-    del codes, adj_d
+    del codes, adj_d, levels
     torch.cuda.synchronize()
 
     # exact ground truth (set-up)
@@ -156,7 +172,23 @@ def main():
                              expansions_per_step=args.expansions if mode == 1 else 0,
                              visited_slots=8192 if complete_table else args.visited_slots,
                              visited_kind=ann.VISITED_TABLE if complete_table else args.visited_kind, stream=st)
-        ann.ann_rerank(index, qd, nq, pool, min(n_rerank, ef), ef, k, out_ids, out_dist, st)
+        finish(pool, ef)
+
+    rescored = {}
+
+    def finish(pool, ef, nq_=None, q_=None, ids_=None, dist_=None):
+        """Rescore with the finer code level if the workload has one, then the fp32 rerank."""
+        nq_ = nq if nq_ is None else nq_
+        q_ = qd if q_ is None else q_
+        src = pool
+        if len(w.bits) > 1:
+            key = (nq_, ef)
+            if key not in rescored:
+                rescored[key] = torch.empty((nq_, ef), dtype=torch.int32, device=dev)
+            ann.ann_rescore(index, 1, q_, nq_, pool, ef, ef, rescored[key], None, None, st)
+            src = rescored[key]
+        ann.ann_rerank(index, q_, nq_, src, min(n_rerank, ef), ef, k, out_ids if ids_ is None else ids_,
+                       out_dist if dist_ is None else dist_, st)
 
     # recall sweep
     efs = [args.ef] if args.ef else list(w.ef)
@@ -232,7 +264,7 @@ def main():
                              expansions_per_step=args.expansions if mode == 1 else 0,
                              visited_slots=args.visited_slots, visited_kind=args.visited_kind, stream=st)
         e_mid[i].record()
-        ann.ann_rerank(index, qd, nq, pool, min(n_rerank, ef), ef, k, out_ids, out_dist, st)
+        finish(pool, ef)
     e_end.record()
     torch.cuda.synchronize()
     wall_s = time.perf_counter() - t_wall
@@ -276,7 +308,7 @@ def main():
                              entry_ids=entries_big, n_entry=args.n_entry if entries_big is not None else 0, layout=args.layout,
                              expansions_per_step=args.expansions if mode == 1 else 0,
                              visited_slots=args.visited_slots, visited_kind=args.visited_kind, stream=st)
-        ann.ann_rerank(index, q_big, nq * rep, pool_big, min(n_rerank, ef), ef, k, ids_big, dist_big, st)
+        finish(pool_big, ef, nq * rep, q_big, ids_big, dist_big)
 
     big_step()
     torch.cuda.synchronize()
@@ -304,7 +336,7 @@ def main():
         def variant_step(ef_v, pool_v):
             ann.ann_entry_scan(index, qd, nq, 1, ent, st)
             ann.ann_search_batch(index, qd, nq, k=k, ef=ef_v, mode=1, out_ids=pool_v, entry_ids=ent, n_entry=1, stream=st)
-            ann.ann_rerank(index, qd, nq, pool_v, min(n_rerank, ef_v), ef_v, k, out_ids, out_dist, st)
+            finish(pool_v, ef_v)
 
         for ef_v in efs:
             pool_v = torch.empty((nq, ef_v), dtype=torch.int32, device=dev)
@@ -328,7 +360,8 @@ def main():
                 break
 
     default_config = (args.workload == "c2" and not args.n and not args.nq and not args.visited_slots and not args.visited_kind
-                      and not args.pivots and not args.layout and not args.expansions and ef == 128 and mode == 1)
+                      and not args.pivots and not args.layout and not args.expansions and args.coverage == 1.0
+                      and ef == 128 and mode == 1)
     traffic = MEASURED_TRAFFIC.get(kernel_source_hash()) if default_config else None
     result = {
         "metric": "queries/sec at recall@10>=0.95 (1M x 128 SQ8, ef sweep)",
@@ -366,13 +399,13 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric)
+        result["cpu_baseline"] = cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, args.coverage)
 
     ann.ann_free_index(index)
     print(json.dumps(result), flush=True)
 
 
-def cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric):
+def cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, coverage=1.0):
     """The CPU oracle as it stands (plain C++, -O2, no SIMD intrinsics), timed
     on this host: same workload, same ef, search + rerank, on a bounded sample
     of the queries split over the host's cores (queries are independent)."""
@@ -385,7 +418,7 @@ def cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric):
         cores = os.cpu_count() or 1
     threads = max(1, min(16, cores))
     t0 = time.time()
-    level = oracle.sq_fit(X, w.bits[0])
+    level = oracle.sq_fit(X, w.bits[0], coverage=coverage)
     log(f"[bench] oracle encode {time.time() - t0:.1f}s")
     # size the sample from a short probe so that the timed part is ~15 s of CPU work
     probe = Q[:32]

@@ -40,9 +40,11 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   uint32_t vis_log2;
   if (params->visited_slots == 0) {
     // defaults: a small cache, so that many queries are resident per compute
-    // unit (measured fastest on 1M x 128 for ef 64..256); the largest table
-    // when the cap is active, so that rebuilds are rare
-    const uint32_t want = cache ? 1024u : (capped ? 8192u : 1024u);
+    // unit (1024 slots measured fastest on 1M x 128 SQ8 for ef 64..256; with
+    // wide code rows a repeated evaluation costs more, 2048 slots measured
+    // fastest on 200k x 960 SQ4); the largest table when the cap is active, so
+    // that rebuilds are rare
+    const uint32_t want = cache ? (index->level[0].row_stride >= 256 ? 2048u : 1024u) : (capped ? 8192u : 1024u);
     vis_log2 = 0;
     while ((1u << vis_log2) < want) ++vis_log2;
     if (vis_log2 < min_log2) vis_log2 = min_log2;
