@@ -326,6 +326,27 @@ def main():
         f"{bytes_search * rep / (big_ms * 1e-3) / 1e9:.0f} GB/s algorithmic incl. fold and rerank time")
     del q_big, pool_big, ids_big, dist_big
 
+    # latency of one query alone on the device (batch of 1): folding, search and
+    # rerank launched back to back, host-synchronised; median over 200 queries
+    lat = []
+    pool1 = torch.empty((1, ef), dtype=torch.int32, device=dev)
+    ids1 = torch.empty((1, k), dtype=torch.int32, device=dev)
+    dist1 = torch.empty((1, k), dtype=torch.float32, device=dev)
+    for i in range(220):
+        q1 = qd[i % nq:i % nq + 1]
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ann.ann_search_batch(index, q1, 1, k=k, ef=ef, mode=mode, out_ids=pool1, layout=args.layout,
+                             expansions_per_step=args.expansions if mode == 1 else 0,
+                             visited_slots=args.visited_slots, visited_kind=args.visited_kind, stream=st)
+        finish(pool1, ef, 1, q1, ids1, dist1)
+        torch.cuda.synchronize()
+        if i >= 20:
+            lat.append((time.perf_counter() - t1) * 1e6)
+    lat.sort()
+    lat_med, lat_p99 = lat[len(lat) // 2], lat[int(len(lat) * 0.99)]
+    log(f"[bench] one query alone: median {lat_med:.0f} us, p99 {lat_p99:.0f} us (launch + search + rerank, host-synchronised)")
+
     # variant: per-query entry points from a scan of 1024 sampled base vectors
     # (the entry-point stage) instead of the medoid; same recall target
     variant = None
@@ -385,6 +406,8 @@ def main():
                    "steady_state_8x_batch": {"queries_per_batch": nq * rep, "ms_per_batch": round(big_ms, 4),
                                              "value": round(steady_qps, 1),
                                              "algorithmic_GBps": round(bytes_search * rep / (big_ms * 1e-3) / 1e9, 1)},
+                   "single_query_latency_us": {"median": round(lat_med, 1), "p99": round(lat_p99, 1),
+                                               "what": "batch of 1: fold + search + rerank, host-synchronised"},
                    "entry_stage_variant": variant,
                    "sweep": sweep},
         "ground_truth": {"kernel": "ann_bruteforce_topk (fp32 MFMA tiles + exact re-evaluation)", "bound": "mfma",
