@@ -133,6 +133,15 @@ typedef struct {
  *                 m_s unvisited neighbours are taken per expansion, in stored
  *                 order.  alpha_s = 0 (labels are >= 1): no label test; needs an
  *                 index uploaded with edge_labels otherwise.  m_s = 0: no cap.
+ *   query_order   NULL: workgroup b searches query b.  Otherwise a permutation of
+ *                 0..nq-1 on the device: workgroup b searches query
+ *                 query_order[b] (outputs stay at the query's own index).  A
+ *                 speed knob: results do not depend on it.
+ *   reuse_folded_queries   non-zero: the last folding launched on this index
+ *                 (by ann_entry_scan, ann_query_prep for level 0 or
+ *                 ann_search_batch, on the same stream) was of this same q and
+ *                 nq and q has not changed since; the search skips its own
+ *                 folding pass.  ANN_EINVAL if q or nq differ from that call's.
  *   layout        0: neighbour code rows are gathered from the code table;
  *                 1: they are read from the redundant copy made by
  *                    ann_build_prs (same results; not with alpha_s / m_s).
@@ -149,6 +158,8 @@ typedef struct {
   uint32_t m_s;
   uint32_t layout;
   uint32_t visited_kind; /* ann_visited_kind */
+  const uint32_t *query_order; /* device, [nq], or NULL: see ann_schedule_queries */
+  uint32_t reuse_folded_queries;
 } ann_search_params;
 
 /*
@@ -224,6 +235,22 @@ ann_status ann_build_prs(ann_index *index, void *stream);
 ann_status ann_build_entry_table(ann_index *index, uint32_t n_pivots, void *stream);
 ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_t n_entry,
                           uint32_t *out_entry_ids, void *stream);
+
+/*
+ * Processing order for a batch (a speed knob, for callers that search many
+ * queries at once): queries with equal or close keys are placed so that they
+ * run at the same time on the same accelerator die and share its L2 cache.
+ *   keys       [nq] device: one value per query, equal or close for queries
+ *              that will visit the same part of the graph - e.g. the node id
+ *              of the closest scanned pivot as written by ann_entry_scan with
+ *              n_entry = 1 (then key_range = n).  Keys >= key_range count as
+ *              key_range - 1.
+ *   out_order  [nq] device: a permutation of 0..nq-1 for
+ *              ann_search_params.query_order.
+ * One small kernel on the stream; no allocation.  Errors: ANN_EINVAL.
+ */
+ann_status ann_schedule_queries(const uint32_t *keys, uint32_t nq, uint32_t key_range, uint32_t *out_order,
+                                void *stream);
 
 /*
  * Algorithm 1 ("Deterministic Access Greedy Search") for a batch of queries,

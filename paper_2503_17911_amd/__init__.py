@@ -27,7 +27,7 @@ _STATUS_NAMES = ["ANN_OK", "ANN_EINVAL", "ANN_ENOMEM", "ANN_EDEVICE", "ANN_EUNSU
 
 EXPORTED_SYMBOLS = ["ann_sq_train", "ann_sq_train_truncated", "ann_sq_encode", "ann_upload_index", "ann_free_index", "ann_query_prep",
                     "ann_search_batch", "ann_rescore", "ann_rerank", "ann_bruteforce_topk", "ann_build_entry_table",
-                    "ann_entry_scan", "ann_build_prs", "ann_last_error", "ann_version"]
+                    "ann_entry_scan", "ann_build_prs", "ann_schedule_queries", "ann_last_error", "ann_version"]
 
 
 class AnnError(RuntimeError):
@@ -55,7 +55,8 @@ class SearchParams(ctypes.Structure):
     _fields_ = [("k", ctypes.c_uint32), ("ef", ctypes.c_uint32), ("mode", ctypes.c_uint32),
                 ("expansions_per_step", ctypes.c_uint32), ("visited_slots", ctypes.c_uint32),
                 ("alpha_s", ctypes.c_float), ("m_s", ctypes.c_uint32), ("layout", ctypes.c_uint32),
-                ("visited_kind", ctypes.c_uint32)]
+                ("visited_kind", ctypes.c_uint32), ("query_order", ctypes.c_void_p),
+                ("reuse_folded_queries", ctypes.c_uint32)]
 
 
 def _load_library() -> ctypes.CDLL:
@@ -77,6 +78,7 @@ def _load_library() -> ctypes.CDLL:
     lib.ann_build_prs.argtypes = [vp, vp]
     lib.ann_build_entry_table.argtypes = [vp, u32, vp]
     lib.ann_entry_scan.argtypes = [vp, vp, u32, u32, vp, vp]
+    lib.ann_schedule_queries.argtypes = [vp, u32, u32, vp, vp]
     for name in EXPORTED_SYMBOLS[:-2]:
         getattr(lib, name).restype = i32
     lib.ann_last_error.restype = ctypes.c_char_p
@@ -157,10 +159,12 @@ def ann_query_prep(index, level, q, nq, t, s, qlo, stream=None):
 
 
 def ann_search_batch(index, q, nq, *, k, ef, out_ids, out_keys=None, out_idot=None, out_counts=None, mode=0,
-                     expansions_per_step=0, visited_slots=0, alpha_s=0.0, m_s=0, layout=0, visited_kind=0, entry_ids=None,
+                     expansions_per_step=0, visited_slots=0, alpha_s=0.0, m_s=0, layout=0, visited_kind=0, query_order=None,
+                     reuse_folded_queries=False, entry_ids=None,
                      n_entry=0, stream=None):
     p = SearchParams(k=k, ef=ef, mode=mode, expansions_per_step=expansions_per_step, visited_slots=visited_slots,
-                     alpha_s=alpha_s, m_s=m_s, layout=layout, visited_kind=visited_kind)
+                     alpha_s=alpha_s, m_s=m_s, layout=layout, visited_kind=visited_kind, query_order=_ptr(query_order),
+                     reuse_folded_queries=int(bool(reuse_folded_queries)))
     _check(_lib.ann_search_batch(index, _ptr(q), nq, ctypes.byref(p), _ptr(entry_ids), n_entry, _ptr(out_ids),
                                  _ptr(out_keys), _ptr(out_idot), _ptr(out_counts), stream))
 
@@ -182,6 +186,10 @@ def ann_build_prs(index, stream=None):
 
 def ann_build_entry_table(index, n_pivots, stream=None):
     _check(_lib.ann_build_entry_table(index, n_pivots, stream))
+
+
+def ann_schedule_queries(keys, nq, key_range, out_order, stream=None):
+    _check(_lib.ann_schedule_queries(_ptr(keys), nq, key_range, _ptr(out_order), stream))
 
 
 def ann_entry_scan(index, q, nq, n_entry, out_entry_ids, stream=None):

@@ -30,6 +30,8 @@ struct Workspace {
   float *qlo = nullptr;    // [nq_cap]
   int32_t *sum_t = nullptr;  // [nq_cap]
   uint32_t tq_stride = 0;
+  const float *folded_q = nullptr;  // the batch whose folded form the buffers hold (as last launched)
+  uint32_t folded_nq = 0;
 };
 
 }  // namespace ann

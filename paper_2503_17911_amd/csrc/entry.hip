@@ -24,7 +24,6 @@ __global__ __launch_bounds__(64) void entry_scan_kernel(const uint8_t *__restric
                                                         const int32_t *__restrict__ sum_t, uint32_t nq,
                                                         uint32_t n_entry, uint32_t *__restrict__ out) {
   constexpr int G = kWave / LPR, CPL = 4, TQW = TqRegs<BITS>::kWords;
-  __shared__ uint64_t list[kWave * kScanKeep];
   const uint32_t qi = blockIdx.x;
   if (qi >= nq) return;
   const int lane = threadIdx.x, sub = lane % LPR, grp = lane / LPR;
@@ -61,18 +60,24 @@ __global__ __launch_bounds__(64) void entry_scan_kernel(const uint8_t *__restric
       best[t] = lo;
     }
   }
+  // the n_entry smallest over all lanes, one at a time: every lane offers the
+  // head of its sorted list, the wave takes the minimum, its owner moves on
+  // ((key, id) pairs are distinct except for the all-ones filler)
+  for (uint32_t r = 0; r < n_entry; ++r) {
+    uint64_t m = best[0];
 #pragma unroll
-  for (int t = 0; t < kScanKeep; ++t) list[lane * kScanKeep + t] = best[t];
-  __syncthreads();
-  // rank the 256 survivors; (key, id) pairs are distinct except for the all-ones filler
-  for (int i = lane; i < kWave * kScanKeep; i += kWave) {
-    const uint64_t e = list[i];
-    uint32_t rank = 0;
-    for (int j = 0; j < kWave * kScanKeep; ++j) {
-      const uint64_t o = list[j];
-      rank += (o < e || (o == e && j < i)) ? 1u : 0u;
+    for (int x = 1; x < kWave; x <<= 1) {
+      const uint32_t ohi = (uint32_t)xor_lane_i32((int)(uint32_t)(m >> 32), x);
+      const uint32_t olo = (uint32_t)xor_lane_i32((int)(uint32_t)m, x);
+      const uint64_t o = pack_ki(ohi, olo);
+      m = o < m ? o : m;
     }
-    if (rank < n_entry) out[(uint64_t)qi * n_entry + rank] = e == ~0ull ? ANN_PAD_ID : (uint32_t)e;
+    if (best[0] == m && m != ~0ull) {
+#pragma unroll
+      for (int t = 0; t + 1 < kScanKeep; ++t) best[t] = best[t + 1];
+      best[kScanKeep - 1] = ~0ull;
+    }
+    if (lane == 0) out[(uint64_t)qi * n_entry + r] = m == ~0ull ? ANN_PAD_ID : (uint32_t)m;
   }
 }
 

@@ -57,8 +57,13 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   }
   if (vis_log2 > 13) return fail(ANN_ECAPACITY, "ann_search_batch: the visited set would need more than 8192 slots");
 
-  ann_status rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st);
-  if (rc != ANN_OK) return rc;
+  if (params->reuse_folded_queries) {
+    if (index->ws[0].folded_q != q || index->ws[0].folded_nq != nq)
+      return fail(ANN_EINVAL, "ann_search_batch: reuse_folded_queries, but the last folding on this index was of another batch");
+  } else {
+    ann_status rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st);
+    if (rc != ANN_OK) return rc;
+  }
 
   const LevelDev &L = index->level[0];
   const Workspace &w = index->ws[0];
@@ -71,6 +76,7 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   a.qlo = w.qlo;
   a.sum_t = w.sum_t;
   a.entry_ids = entry_ids;
+  a.order = params->query_order;
   a.prs_codes = params->layout == 1 ? index->prs_codes : nullptr;
   a.prs_norm = params->layout == 1 && index->metric == ANN_L2 ? index->prs_norm : nullptr;
   a.labels = params->alpha_s > 0.0f ? index->labels : nullptr;

@@ -47,6 +47,7 @@ struct SearchArgs {
   const float *qlo;
   const int32_t *sum_t;
   const uint32_t *entry_ids;
+  const uint32_t *order;  // processing order (workgroup -> query) or nullptr
   const float *labels;  // [n][degree] edge labels or nullptr
   const uint8_t *prs_codes;  // [n][degree][row_stride] code rows of every node's neighbours, or nullptr
   const float *prs_norm;     // [n][degree] their norm terms (L2), or nullptr
@@ -728,8 +729,9 @@ struct SearchWave {
 template <int BITS, int LPR, int M, int PMAX, bool FAST>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? (FAST ? (PMAX > 1 ? (BITS == 8 ? 6 : 5) : 8) : 5) : (M == 4 ? 4 : 3)))) void search_kernel(SearchArgs args) {
   extern __shared__ uint64_t smem[];
-  const uint32_t qi = blockIdx.x;
-  if (qi >= args.nq) return;
+  if (blockIdx.x >= args.nq) return;
+  const uint32_t qi = args.order ? args.order[blockIdx.x] : blockIdx.x;
+  if (qi >= args.nq) return;  // not a permutation: skip rather than write out of bounds
   SearchWave<BITS, LPR, M, PMAX, FAST> w(args, smem);
   w.run(qi);
 }

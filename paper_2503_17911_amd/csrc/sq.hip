@@ -227,6 +227,8 @@ ann_status launch_query_prep(ann_index *ix, uint32_t level, const float *q, uint
     query_prep_kernel<4><<<nq, 64, (size_t)ix->d * sizeof(double), st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t, t_plain,
                                             s_out, qlo_out);
   ANN_HIP(hipGetLastError());
+  w.folded_q = q;
+  w.folded_nq = nq;
   return ANN_OK;
 }
 

@@ -428,3 +428,51 @@ def test_c2_full_size_sampled_queries(H):
     H.check_rerank(bid[:20], bdist[:20], tid, tdist.astype(np.float32), rel=1e-6)
     assert oracle.recall(rid[sample], bid) >= 0.95
     ix.close()
+
+
+def test_schedule_groups_queries_by_key_and_deals_them_to_the_dies(H):
+    """ann_schedule_queries: the result is a permutation; read die by die
+    (workgroups b = x, x + 8, x + 16, ... belong to die x) and the dies' runs
+    put one after the other, the queries' key buckets never decrease."""
+    import torch
+    rng = np.random.default_rng(11)
+    for nq, key_range in ((1, 10), (7, 3), (8, 1000), (1000, 1 << 20), (10007, 1_000_000), (70001, 50)):
+        keys = rng.integers(0, key_range + 5, size=nq).astype(np.uint32)      # a few keys beyond the range
+        kd = torch.from_numpy(keys.view(np.int32)).to(H.DEV)
+        order = torch.empty(nq, dtype=torch.int32, device=H.DEV)
+        H.ann.ann_schedule_queries(kd, nq, key_range, order, H.stream_ptr())
+        torch.cuda.synchronize()
+        o = order.cpu().numpy().view(np.uint32).astype(np.int64)
+        assert sorted(o.tolist()) == list(range(nq))
+        runs = np.concatenate([o[x::8] for x in range(8)])
+        buckets = np.minimum(keys[runs].astype(np.int64), key_range - 1) * 4096 // key_range
+        assert (np.diff(buckets) >= 0).all()
+
+
+@pytest.mark.parametrize("P", [1, 4])
+def test_query_order_does_not_change_results(H, c1, P):
+    """Searching the batch in a scheduled order (similar queries together) gives
+    every query the result it has in the natural order: the oracle's."""
+    import torch
+    w, X, Q, adj, entry, lv = (c1[k] for k in ("w", "X", "Q", "adj", "entry", "level"))
+    ix = H.GpuIndex(X, adj, entry, [lv], oracle.L2)
+    nq = Q.shape[0]
+    ent = ix.entry_scan(Q, 64, 1)
+    kd = torch.from_numpy(np.ascontiguousarray(ent[:, 0]).view(np.int32)).to(H.DEV)
+    order = torch.empty(nq, dtype=torch.int32, device=H.DEV)
+    H.ann.ann_schedule_queries(kd, nq, w.n, order, H.stream_ptr())
+    torch.cuda.synchronize()
+    assert sorted(order.cpu().numpy().tolist()) == list(range(nq))
+    orc = oracle.search_batch(lv, w.d, adj, entry, Q, 64, expansions_per_step=P)
+    gpu = ix.search(Q, 64, mode=int(P > 1), expansions_per_step=P if P > 1 else 0, query_order=order)
+    assert_search_equal(gpu, orc)
+    fast = ix.search(Q, 64, mode=int(P > 1), expansions_per_step=P if P > 1 else 0, query_order=order,
+                     visited_kind=H.ann.VISITED_CACHE)
+    assert_search_equal(fast, orc, check_counts=False)
+    # the folding left by the previous call on the same batch is reused
+    again = ix.search(Q, 64, mode=int(P > 1), expansions_per_step=P if P > 1 else 0, query_order=order,
+                      visited_kind=H.ann.VISITED_CACHE, reuse_folded_queries=True, same_queries_as_last_call=True)
+    assert_search_equal(again, orc, check_counts=False)
+    with pytest.raises(H.ann.AnnError):
+        ix.search(Q[:5], 64, reuse_folded_queries=True)
+    ix.close()
