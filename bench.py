@@ -72,7 +72,7 @@ def main():
     ap.add_argument("--mode", type=int, default=-1, help="0 exact, 1 multi-expansion; -1: fastest that meets recall")
     ap.add_argument("--expansions", type=int, default=0, help="expansions per step in mode 1 (0 = library default)")
     ap.add_argument("--visited-slots", type=int, default=0, help="LDS visited-set slots (0 = library default)")
-    ap.add_argument("--visited-kind", type=int, default=0, help="0 library default, 1 direct-mapped cache, 2 probing table")
+    ap.add_argument("--visited-kind", type=int, default=0, help="0 library default, 1 two-way cache, 2 probing table")
     ap.add_argument("--pivots", type=int, default=0,
                     help="entry-point stage: scan this many sampled base vectors per query (0 = start at the medoid)")
     ap.add_argument("--n-entry", type=int, default=1, help="initial nodes per query taken from the pivot scan")

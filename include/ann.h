@@ -114,9 +114,10 @@ typedef struct {
  *                 un-expanded entries expanded together in one step.
  *   visited_kind, visited_slots   how the visited set V is kept in LDS
  *                 (visited_slots a power of two <= 8192, 0 = library default).
- *                 ANN_VISITED_CACHE: a direct-mapped cache of node ids, one probe
- *                 per test; a node whose slot is taken over by another is
- *                 forgotten and may be evaluated again.  ANN_VISITED_TABLE: an
+ *                 ANN_VISITED_CACHE: a two-way set-associative cache of node
+ *                 ids (least recently tested way replaced), at most two probes
+ *                 per test; a node pushed out of its set is forgotten and may
+ *                 be evaluated again.  ANN_VISITED_TABLE: an
  *                 open-addressing table that holds every evaluated node while it
  *                 fits and is rebuilt from the current pool when 3/4 full.
  *                 Forgetting a node costs a repeated distance evaluation, never

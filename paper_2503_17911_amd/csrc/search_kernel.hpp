@@ -5,8 +5,8 @@
 //   pool C          sorted array of (key, id) pairs in registers, striped:
 //                   entry i lives in register i/64 of lane i%64.  The low word
 //                   is (id << 1) | expanded, so pairs compare as plain u64.
-//   visited set V   in LDS, either a direct-mapped cache of node ids (one
-//                   exchange per test, may forget) or an open-addressing hash
+//   visited set V   in LDS, either a two-way cache of node ids (one or two
+//                   exchanges per test, may forget) or an open-addressing hash
 //                   table with test-and-set by CAS (complete while it fits).
 //   for j in G_i    one lane per adjacency slot: all ids of the row are
 //                   tested against V first, survivors are compacted (the
@@ -58,7 +58,7 @@ struct SearchArgs {
   uint64_t n;
   uint32_t row_stride, n_chunks, degree, metric, tq_stride, n_entry, entry_point, ef, vis_log2, nq, p;
   uint32_t filtered;  // the label test and/or the per-expansion cap m_s is active
-  uint32_t vis_cache;  // visited set is the direct-mapped cache
+  uint32_t vis_cache;  // visited set is the two-way cache
   uint32_t m_s;
   float alpha_s;
 };
@@ -108,7 +108,7 @@ __host__ __device__ inline size_t search_smem_bytes(int m, int pmax, bool fast, 
 }
 
 // FAST: the configuration that matters for throughput, with the run-time
-// switches folded away (direct-mapped visited cache, no edge filter, plain
+// switches folded away (two-way visited cache, no edge filter, plain
 // layout, PMAX expansions per step, degree <= 32 when PMAX > 1).  The general
 // kernel (FAST = false) takes every switch from SearchArgs.
 template <int BITS, int LPR, int M, int PMAX, bool FAST>
@@ -188,13 +188,19 @@ struct SearchWave {
     for (uint32_t i = lane; i <= vis_mask; i += kWave) vis[i] = kEmpty;
   }
 
-  // Direct-mapped cache: a node's slot holds the last id hashed to it.  The
-  // exchange makes lanes that test the same id in one instruction see each
-  // other.  A displaced id is forgotten; it may come back as a candidate and is
-  // then recognised when it is merged (it equals a pool entry or another
-  // candidate) or rejected again by the pool's last entry.
+  // Two-way cache of node ids: a set is two adjacent slots, way 0 the more
+  // recently tested.  The id goes into way 0; what it displaces moves to way 1,
+  // and what that displaces is forgotten.  The exchanges make lanes that test
+  // the same id in one instruction see each other (in almost every
+  // interleaving; the merge copes with the rest).  A forgotten id may come back
+  // as a candidate and is then recognised when it is merged (it equals a pool
+  // entry or another candidate) or rejected again by the pool's last entry.
   __device__ __forceinline__ bool cache_test_and_set(uint32_t id) {
-    return atomicExch(&vis[(id * 0x9E3779B1u) >> vis_shift], id) != id;
+    uint32_t *set = &vis[((id * 0x9E3779B1u) >> vis_shift) & ~1u];
+    const uint32_t o0 = atomicExch(set, id);
+    if (o0 == id) return false;
+    if (o0 == kEmpty) return true;  // way 1 is filled only from way 0
+    return atomicExch(set + 1, o0) != id;
   }
 
   // true if id was not in the table (and now is)
@@ -214,7 +220,10 @@ struct SearchWave {
 
   // Membership test without insertion.
   __device__ __forceinline__ bool lookup(uint32_t id) {
-    if (use_cache()) return vis[(id * 0x9E3779B1u) >> vis_shift] == id;
+    if (use_cache()) {
+      const uint32_t *set = &vis[((id * 0x9E3779B1u) >> vis_shift) & ~1u];
+      return set[0] == id || set[1] == id;
+    }
     const uint32_t h = id * 0x9E3779B1u;
     uint32_t slot = h >> vis_shift;
     const uint32_t stride = ((h >> 4) | 1u) & vis_mask;
@@ -231,10 +240,15 @@ struct SearchWave {
   // / id1 was not in the table (and now is).  A lane's two ids may be equal.
   __device__ __forceinline__ int test_and_set2(bool v0, uint32_t id0, bool v1, uint32_t id1) {
     if (use_cache()) {
+      uint32_t *set0 = &vis[((id0 * 0x9E3779B1u) >> vis_shift) & ~1u];
+      uint32_t *set1 = &vis[((id1 * 0x9E3779B1u) >> vis_shift) & ~1u];
       uint32_t o0 = id0, o1 = id1;
-      if (v0) o0 = atomicExch(&vis[(id0 * 0x9E3779B1u) >> vis_shift], id0);
-      if (v1) o1 = atomicExch(&vis[(id1 * 0x9E3779B1u) >> vis_shift], id1);
-      return (o0 != id0 ? 1 : 0) | (o1 != id1 ? 2 : 0);
+      if (v0) o0 = atomicExch(set0, id0);
+      if (v1) o1 = atomicExch(set1, id1);
+      bool f0 = o0 != id0, f1 = o1 != id1;
+      if (f0 && o0 != kEmpty) f0 = atomicExch(set0 + 1, o0) != id0;
+      if (f1 && o1 != kEmpty) f1 = atomicExch(set1 + 1, o1) != id1;
+      return (f0 ? 1 : 0) | (f1 ? 2 : 0);
     }
     const uint32_t h0 = id0 * 0x9E3779B1u, h1 = id1 * 0x9E3779B1u;
     uint32_t s0 = h0 >> vis_shift, s1 = h1 >> vis_shift;

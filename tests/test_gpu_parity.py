@@ -318,7 +318,7 @@ def test_small_visited_table_rebuilds_without_changing_results(H, c1):
 @pytest.mark.parametrize("slots", [64, 256, 1024, 8192])
 @pytest.mark.parametrize("P", [1, 4])
 def test_visited_cache_forgets_without_changing_results(H, c1, slots, P):
-    """The default visited set is a direct-mapped cache that forgets a node when
+    """The default visited set is a small two-way cache that forgets a node when
     another takes its slot.  A forgotten node is evaluated again and then either
     rejected by the pool's last entry or recognised as a copy of a pool entry or
     of another candidate; the pool, keys and expansion count stay those of the
