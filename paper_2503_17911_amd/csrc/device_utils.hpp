@@ -13,7 +13,6 @@ constexpr int kDppQuadXor1 = 0xB1;     // quad_perm:[1,0,3,2]
 constexpr int kDppQuadXor2 = 0x4E;     // quad_perm:[2,3,0,1]
 constexpr int kDppRowHalfMirror = 0x141;
 constexpr int kDppRowMirror = 0x140;
-constexpr int kDppWaveShr1 = 0x138;
 
 template <int CTRL>
 __device__ __forceinline__ int dpp_i32(int v) {

@@ -65,20 +65,6 @@ struct SearchArgs {
 
 __device__ __forceinline__ uint64_t pack64(uint32_t hi, uint32_t lo) { return ((uint64_t)hi << 32) | lo; }
 
-// v with lane `lane` replaced by the wave-uniform `value` (v_writelane_b32; on
-// this ISA the lane select of a write with a scalar value goes through m0).
-__device__ __forceinline__ int write_lane(int v, int value, int lane) {
-  int saved_m0;
-  asm volatile(
-      "s_mov_b32 %1, m0\n\t"
-      "s_mov_b32 m0, %3\n\t"
-      "v_writelane_b32 %0, %2, m0\n\t"
-      "s_mov_b32 m0, %1"
-      : "+v"(v), "=&s"(saved_m0)
-      : "s"(value), "s"(lane));
-  return v;
-}
-
 __device__ __forceinline__ int lanes_below(uint64_t mask) {
   return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
