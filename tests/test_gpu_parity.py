@@ -395,7 +395,7 @@ def test_bruteforce_matches_fp64_exhaustive_search(H, n, d, nq, k, metric):
 
 def test_c2_full_size_sampled_queries(H):
     """The benchmark workload at full size (1M x 128, SQ8, R=32) in the launch
-    configuration bench.py times (default visited set, both modes): the whole
+    configuration bench.py times (default visited set, scheduled batch, both modes): the whole
     10,000-query batch runs on the GPU, a sample of queries is recomputed by the
     oracle one by one, and properties that hold at any size are checked for all."""
     w = inputs.WORKLOADS["c2"]
@@ -406,9 +406,20 @@ def test_c2_full_size_sampled_queries(H):
     assert (codes == lv.codes).all() and (norm.view(np.uint32) == lv.norm_term.view(np.uint32)).all()
     ix = H.GpuIndex(X, adj, entry, [oracle.SQLevel(8, lo, delta, codes, norm)], oracle.L2)
     sample = np.arange(0, w.nq, 97)[:100]
+    # the batch is scheduled as bench.py does it: keys from a scan of 256 pivots, the search reuses the scan's folding
+    import torch
+    ent = ix.entry_scan(Q, 256, 1)
+    order = torch.empty(w.nq, dtype=torch.int32, device=H.DEV)
+    H.ann.ann_schedule_queries(torch.from_numpy(np.ascontiguousarray(ent[:, 0]).view(np.int32)).to(H.DEV), w.nq, w.n,
+                               order, H.stream_ptr())
+    torch.cuda.synchronize()
+    assert sorted(order.cpu().numpy().tolist()) == list(range(w.nq))
     for ef, mode, P in ((128, 0, 1), (128, 1, 4), (256, 1, 4)):
         ids, keys, _, counts = ix.search(Q, ef, k=w.k, want_idot=False, mode=mode, expansions_per_step=P if mode else 0,
-                                         visited_slots=0)
+                                         visited_slots=0, query_order=order)
+        again = ix.search(Q, ef, k=w.k, want_idot=False, mode=mode, expansions_per_step=P if mode else 0,
+                          visited_slots=0, query_order=order, reuse_folded_queries=True, same_queries_as_last_call=True)
+        assert (again[0] == ids).all() and (again[1].view(np.uint32) == keys.view(np.uint32)).all()
         oi, ok, _, oc = oracle.search_batch(lv, w.d, adj, entry, Q[sample], ef, expansions_per_step=P)
         assert (ids[sample] == oi).all()
         assert (keys[sample].view(np.uint32) == ok.view(np.uint32)).all()
