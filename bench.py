@@ -236,6 +236,7 @@ def main():
             torch.cuda.synchronize()
             rec = recall_at_k(out_ids.cpu().numpy(), gt)
             c = counts.cpu().numpy().astype(np.int64)
+            run_step(ef, mode, pool)        # first launch of this kernel variant: not timed
             ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             ev0.record()
             run_step(ef, mode, pool)
