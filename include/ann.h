@@ -134,6 +134,11 @@ typedef struct {
  *                 m_s unvisited neighbours are taken per expansion, in stored
  *                 order.  alpha_s = 0 (labels are >= 1): no label test; needs an
  *                 index uploaded with edge_labels otherwise.  m_s = 0: no cap.
+ *   ef_per_query  NULL: every query uses ef.  Otherwise [nq] on the device: query
+ *                 i runs Algorithm 1 with pool size min(max(ef_per_query[i], 1),
+ *                 ef) - the hook for query-level parameters (Section 4.2, where
+ *                 a classifier picks ef_s per query).  Output rows keep the
+ *                 stride ef; slots past a query's own pool size are padding.
  *   query_order   NULL: workgroup b searches query b.  Otherwise a permutation of
  *                 0..nq-1 on the device: workgroup b searches query
  *                 query_order[b] (outputs stay at the query's own index).  A
@@ -161,6 +166,7 @@ typedef struct {
   uint32_t visited_kind; /* ann_visited_kind */
   const uint32_t *query_order; /* device, [nq], or NULL: see ann_schedule_queries */
   uint32_t reuse_folded_queries;
+  const uint32_t *ef_per_query; /* device, [nq], or NULL */
 } ann_search_params;
 
 /*

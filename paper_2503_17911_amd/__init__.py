@@ -56,7 +56,7 @@ class SearchParams(ctypes.Structure):
                 ("expansions_per_step", ctypes.c_uint32), ("visited_slots", ctypes.c_uint32),
                 ("alpha_s", ctypes.c_float), ("m_s", ctypes.c_uint32), ("layout", ctypes.c_uint32),
                 ("visited_kind", ctypes.c_uint32), ("query_order", ctypes.c_void_p),
-                ("reuse_folded_queries", ctypes.c_uint32)]
+                ("reuse_folded_queries", ctypes.c_uint32), ("ef_per_query", ctypes.c_void_p)]
 
 
 def _load_library() -> ctypes.CDLL:
@@ -160,11 +160,11 @@ def ann_query_prep(index, level, q, nq, t, s, qlo, stream=None):
 
 def ann_search_batch(index, q, nq, *, k, ef, out_ids, out_keys=None, out_idot=None, out_counts=None, mode=0,
                      expansions_per_step=0, visited_slots=0, alpha_s=0.0, m_s=0, layout=0, visited_kind=0, query_order=None,
-                     reuse_folded_queries=False, entry_ids=None,
+                     reuse_folded_queries=False, ef_per_query=None, entry_ids=None,
                      n_entry=0, stream=None):
     p = SearchParams(k=k, ef=ef, mode=mode, expansions_per_step=expansions_per_step, visited_slots=visited_slots,
                      alpha_s=alpha_s, m_s=m_s, layout=layout, visited_kind=visited_kind, query_order=_ptr(query_order),
-                     reuse_folded_queries=int(bool(reuse_folded_queries)))
+                     reuse_folded_queries=int(bool(reuse_folded_queries)), ef_per_query=_ptr(ef_per_query))
     _check(_lib.ann_search_batch(index, _ptr(q), nq, ctypes.byref(p), _ptr(entry_ids), n_entry, _ptr(out_ids),
                                  _ptr(out_keys), _ptr(out_idot), _ptr(out_counts), stream))
 

@@ -77,6 +77,7 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   a.sum_t = w.sum_t;
   a.entry_ids = entry_ids;
   a.order = params->query_order;
+  a.ef_per_query = params->ef_per_query;
   a.prs_codes = params->layout == 1 ? index->prs_codes : nullptr;
   a.prs_norm = params->layout == 1 && index->metric == ANN_L2 ? index->prs_norm : nullptr;
   a.labels = params->alpha_s > 0.0f ? index->labels : nullptr;

@@ -48,6 +48,7 @@ struct SearchArgs {
   const int32_t *sum_t;
   const uint32_t *entry_ids;
   const uint32_t *order;  // processing order (workgroup -> query) or nullptr
+  const uint32_t *ef_per_query;  // [nq] pool size of each query (<= ef) or nullptr
   const float *labels;  // [n][degree] edge labels or nullptr
   const uint8_t *prs_codes;  // [n][degree][row_stride] code rows of every node's neighbours, or nullptr
   const float *prs_norm;     // [n][degree] their norm terms (L2), or nullptr
@@ -124,7 +125,8 @@ struct SearchWave {
   float s, qlo;
   int bias;
   uint32_t pk[M], pv[M];  // pool: ordered key bits; (id << 1) | expanded
-  uint64_t worst;         // pool entry ef-1 (all ones while the pool is not full)
+  uint64_t worst;         // pool entry ef_q-1 (all ones while the pool is not full)
+  int ef_q;               // this query's pool size
   uint32_t n_exp = 0, n_dist = 0, n_vis = 0, n_rebuild = 0;
 
   __device__ __forceinline__ SearchWave(const SearchArgs &args, uint64_t *smem) : a(args) {
@@ -290,7 +292,7 @@ struct SearchWave {
   }
 
   __device__ __forceinline__ void refresh_worst() {
-    const int g = (int)a.ef - 1, rr = g / kWave, rl = g % kWave;
+    const int g = ef_q - 1, rr = g / kWave, rl = g % kWave;
     uint32_t k_ = pk[0], v_ = pv[0];
 #pragma unroll
     for (int r = 1; r < M; ++r) {
@@ -374,7 +376,7 @@ struct SearchWave {
 #pragma unroll
     for (int r = 0; r < M; ++r) {
       const uint64_t v = mbuf[r * kWave + lane];
-      const bool beyond = r * kWave + lane >= (int)a.ef;  // entries pushed past ef are dropped
+      const bool beyond = r * kWave + lane >= ef_q;  // entries pushed past the pool size are dropped
       pk[r] = beyond ? kEmpty : (uint32_t)(v >> 32);
       pv[r] = beyond ? kEmpty : (uint32_t)v;
     }
@@ -532,6 +534,11 @@ struct SearchWave {
       const int *src = reinterpret_cast<const int *>(a.tq + (uint64_t)qi * a.tq_stride);
       int *dst = const_cast<int *>(tql);
       for (uint32_t i = lane; i < a.tq_stride / 4; i += kWave) dst[i] = src[i];
+    }
+    ef_q = (int)a.ef;
+    if (a.ef_per_query) {
+      const uint32_t e = a.ef_per_query[qi];
+      ef_q = e == 0 ? 1 : (e < a.ef ? (int)e : (int)a.ef);
     }
     s = a.s[qi];
     qlo = a.qlo[qi];

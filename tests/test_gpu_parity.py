@@ -487,3 +487,28 @@ def test_query_order_does_not_change_results(H, c1, P):
     with pytest.raises(H.ann.AnnError):
         ix.search(Q[:5], 64, reuse_folded_queries=True)
     ix.close()
+
+
+@pytest.mark.parametrize("P", [1, 4])
+def test_pool_size_per_query(H, c1, P):
+    """ef_per_query: every query is searched with its own pool size (the hook for
+    Section 4.2's query-level ef_s); each row equals the oracle run with that ef."""
+    import torch
+    w, X, Q, adj, entry, lv = (c1[k] for k in ("w", "X", "Q", "adj", "entry", "level"))
+    ix = H.GpuIndex(X, adj, entry, [lv], oracle.L2)
+    nq, ef_max = 40, 128
+    rng = np.random.default_rng(3)
+    efs = rng.integers(1, ef_max + 40, size=nq).astype(np.uint32)      # some above the maximum: clamped
+    efs[:4] = (1, 64, 65, 128)
+    efd = torch.from_numpy(efs.view(np.int32)).to(H.DEV)
+    for kind in (H.ann.VISITED_TABLE, H.ann.VISITED_CACHE):
+        ids, keys, dots, cnt = ix.search(Q[:nq], ef_max, mode=int(P > 1), expansions_per_step=P if P > 1 else 0,
+                                         ef_per_query=efd, visited_kind=kind, visited_slots=8192 if kind == H.ann.VISITED_TABLE else 0)
+        for i in range(nq):
+            e = int(min(efs[i], ef_max))
+            oi, ok, od, oc = oracle.search_batch(lv, w.d, adj, entry, Q[i:i + 1], e, expansions_per_step=P)
+            assert (ids[i, :e] == oi[0]).all() and (ids[i, e:] == PAD).all(), i
+            assert (keys[i, :e].view(np.uint32) == ok[0].view(np.uint32)).all() and np.isinf(keys[i, e:]).all()
+            assert (dots[i, :e] == od[0]).all()
+            assert cnt[i, 0] == oc[0, 0] and cnt[i, 2] == oc[0, 2]
+    ix.close()
