@@ -20,6 +20,10 @@
  *     the host before anything is launched; ann_last_error() then returns a
  *     message (thread-local, valid until the next call on that thread).
  *   - No C++ exception crosses this boundary.
+ *   - One index, one batch at a time: calls that fold queries for an index
+ *     (ann_search_batch, ann_entry_scan, ann_query_prep, ann_rescore) share
+ *     that index's workspace, so two of them must not be in flight at once on
+ *     different streams.  Different indexes are independent.
  */
 #ifndef ANN_H_
 #define ANN_H_
