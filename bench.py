@@ -36,7 +36,7 @@ KERNEL_SOURCES = ("paper_2503_17911_amd/csrc/search_kernel.hpp", "paper_2503_179
                   "paper_2503_17911_amd/csrc/entry.hip")
 MEASURED_TRAFFIC = {
     # sha256 of KERNEL_SOURCES -> bytes per launch on c2, ef=128, multi-expansion, 10,000 queries scheduled by 256 pivots
-    "8e8a5ba9913611ea35445c29137028d60c132b96a9a3b882c0dde5615a9d9f01": 1436379 * 1024 * 2.0 + 5002 * 1024 * 1.0,
+    "c9ed300de9fc992b8b75324c1beded9169d2dfae8680b6fc7879967761380659": 1240171 * 1024 * 2.0 + 5002 * 1024 * 1.0,
 }
 
 
@@ -72,7 +72,7 @@ def main():
     ap.add_argument("--mode", type=int, default=-1, help="0 exact, 1 multi-expansion; -1: fastest that meets recall")
     ap.add_argument("--expansions", type=int, default=0, help="expansions per step in mode 1 (0 = library default)")
     ap.add_argument("--visited-slots", type=int, default=0, help="LDS visited-set slots (0 = library default)")
-    ap.add_argument("--visited-kind", type=int, default=0, help="0 library default, 1 two-way cache, 2 probing table")
+    ap.add_argument("--visited-kind", type=int, default=0, help="0 library default, 1 two-way cache, 2 probing table, 3 two-way cache with whole ids")
     ap.add_argument("--pivots", type=int, default=0,
                     help="entry-point stage: scan this many sampled base vectors per query (0 = start at the medoid)")
     ap.add_argument("--n-entry", type=int, default=1, help="initial nodes per query taken from the pivot scan")
@@ -359,6 +359,7 @@ def main():
     steady_qps = nq * rep / (big_ms * 1e-3)
     log(f"[bench] steady state ({nq * rep} queries per batch): {big_ms:.3f} ms/batch, {steady_qps:,.0f} QPS, "
         f"{bytes_search * rep / (big_ms * 1e-3) / 1e9:.0f} GB/s algorithmic incl. fold and rerank time")
+    q_second, ids_second = q_big[nq:2 * nq].clone(), ids_big[nq:2 * nq].clone()   # another batch and its results
     del q_big, pool_big, ids_big, dist_big
 
     # latency of one query alone on the device (batch of 1): folding, search and
@@ -422,23 +423,15 @@ def main():
                     f"{nq / ms_v * 1e3:,.0f} QPS (scan + search + rerank)")
                 break
 
-    # variant: consecutive batches overlapped on two streams (a second handle on
-    # the same data, because calls on one index share its workspace): the next
-    # batch fills the chip while the previous one drains
+    # variant: consecutive batches overlapped on two streams of the same index
+    # (the index keeps one query workspace per stream): the next batch fills the
+    # chip while the previous one drains
     pipelined = None
     if entries is None and len(w.bits) == 1 and not args.layout:
-        codes_b = torch.empty((n, d if bits == 8 else d // 2), dtype=torch.uint8, device=dev)
-        norm_b = torch.empty(n, dtype=torch.float32, device=dev)
-        ann.ann_sq_encode(xd, n, d, bits, lo, delta, codes_b, norm_b, st)
-        adj_b = torch.from_numpy(adj.view(np.int32)).to(dev)
-        index_b = ann.ann_upload_index(n=n, d=d, degree=adj.shape[1], metric=metric, vectors=xd,
-                                       levels=[(bits, codes_b, lo, delta, norm_b)], adjacency=adj_b, entry_point=entry,
-                                       stream=st)
-        del codes_b, adj_b
+        ann.ann_build_entry_table(index, args.schedule_pivots or 256, st)
         lanes = []
-        for ix_ in (index, index_b):
-            ann.ann_build_entry_table(ix_, args.schedule_pivots or 256, st)
-            lanes.append(dict(ix=ix_, stream=torch.cuda.Stream(),
+        for q_lane, ids_lane in ((qd, ref_ids), (q_second, ids_second)):    # two different batches
+            lanes.append(dict(ix=index, stream=torch.cuda.Stream(), q=q_lane, expect=ids_lane,
                               keys=torch.empty(nq, dtype=torch.int32, device=dev),
                               order=torch.empty(nq, dtype=torch.int32, device=dev),
                               pool=torch.empty((nq, ef), dtype=torch.int32, device=dev),
@@ -448,11 +441,11 @@ def main():
 
         def lane_step(L):
             sp = L["stream"].cuda_stream
-            ann.ann_entry_scan(L["ix"], qd, nq, 1, L["keys"], sp)
+            ann.ann_entry_scan(L["ix"], L["q"], nq, 1, L["keys"], sp)
             ann.ann_schedule_queries(L["keys"], nq, n, L["order"], sp)
-            ann.ann_search_batch(L["ix"], qd, nq, k=k, ef=ef, mode=mode, out_ids=L["pool"], query_order=L["order"],
+            ann.ann_search_batch(L["ix"], L["q"], nq, k=k, ef=ef, mode=mode, out_ids=L["pool"], query_order=L["order"],
                                  reuse_folded_queries=True, stream=sp)
-            ann.ann_rerank(L["ix"], qd, nq, L["pool"], min(n_rerank, ef), ef, k, L["ids"], L["dist"], sp)
+            ann.ann_rerank(L["ix"], L["q"], nq, L["pool"], min(n_rerank, ef), ef, k, L["ids"], L["dist"], sp)
 
         for i in range(4):
             lane_step(lanes[i % 2])
@@ -463,11 +456,10 @@ def main():
             lane_step(lanes[i % 2])
         torch.cuda.synchronize()
         ms_p = (time.perf_counter() - t_p) * 1e3 / n_p
-        assert torch.equal(lanes[0]["ids"], ref_ids) and torch.equal(lanes[1]["ids"], ref_ids)
-        pipelined = {"what": "batches alternate between two streams and two handles on the same data; wall clock over "
+        assert all(torch.equal(L["ids"], L["expect"]) for L in lanes)
+        pipelined = {"what": "two different batches alternate between two streams on the one index; wall clock over "
                              f"{n_p} batches", "ms_per_step": round(ms_p, 4), "value": round(nq / (ms_p * 1e-3), 1)}
         log(f"[bench] two batches in flight (two streams): {ms_p:.3f} ms/step {nq / ms_p * 1e3:,.0f} QPS")
-        ann.ann_free_index(index_b)
 
     # variant: the same index with its nodes renumbered so that the rows of one
     # region of the space lie together (an index-layout choice a builder can

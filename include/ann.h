@@ -20,10 +20,16 @@
  *     the host before anything is launched; ann_last_error() then returns a
  *     message (thread-local, valid until the next call on that thread).
  *   - No C++ exception crosses this boundary.
- *   - One index, one batch at a time: calls that fold queries for an index
- *     (ann_search_batch, ann_entry_scan, ann_query_prep, ann_rescore) share
- *     that index's workspace, so two of them must not be in flight at once on
- *     different streams.  Different indexes are independent.
+ *   - Several batches in flight on one index: calls that fold queries for an
+ *     index (ann_search_batch, ann_entry_scan, ann_query_prep, ann_rescore)
+ *     use a workspace the index keeps per stream, so batches issued on
+ *     different streams may run at the same time, and batches on one stream
+ *     follow each other as stream order says.  An index keeps up to 8 such
+ *     workspaces; a 9th stream takes over the least recently used one after a
+ *     device-wide wait.  A workspace grows (hipMalloc, device-wide wait) when a
+ *     batch is larger than any before it on that stream.  Calls for one index
+ *     may come from several host threads as long as no two of them use the
+ *     same stream at once.
  */
 #ifndef ANN_H_
 #define ANN_H_
@@ -119,9 +125,13 @@ typedef struct {
  *   visited_kind, visited_slots   how the visited set V is kept in LDS
  *                 (visited_slots a power of two <= 8192, 0 = library default).
  *                 ANN_VISITED_CACHE: a two-way set-associative cache of node
- *                 ids (least recently tested way replaced), at most two probes
- *                 per test; a node pushed out of its set is forgotten and may
- *                 be evaluated again.  ANN_VISITED_TABLE: an
+ *                 ids (least recently entered way replaced); a node pushed out
+ *                 of its set is forgotten and may be evaluated again.  A slot
+ *                 holds one set of two 16-bit tags while (n - 1) / visited_slots
+ *                 stays below 65534 (set and tag together still name exactly
+ *                 one node), else a slot holds one node id and a set is two
+ *                 slots; ANN_VISITED_CACHE_WIDE asks for the second form
+ *                 whatever n is.  ANN_VISITED_TABLE: an
  *                 open-addressing table that holds every evaluated node while it
  *                 fits and is rebuilt from the current pool when 3/4 full.
  *                 Forgetting a node costs a repeated distance evaluation, never
@@ -147,16 +157,21 @@ typedef struct {
  *                 0..nq-1 on the device: workgroup b searches query
  *                 query_order[b] (outputs stay at the query's own index).  A
  *                 speed knob: results do not depend on it.
- *   reuse_folded_queries   non-zero: the last folding launched on this index
- *                 (by ann_entry_scan, ann_query_prep for level 0 or
- *                 ann_search_batch, on the same stream) was of this same q and
+ *   reuse_folded_queries   non-zero: the last folding launched for this index
+ *                 on this stream (by ann_entry_scan, ann_query_prep for level 0
+ *                 or ann_search_batch) was of this same q and
  *                 nq and q has not changed since; the search skips its own
  *                 folding pass.  ANN_EINVAL if q or nq differ from that call's.
  *   layout        0: neighbour code rows are gathered from the code table;
  *                 1: they are read from the redundant copy made by
  *                    ann_build_prs (same results; not with alpha_s / m_s).
  */
-typedef enum { ANN_VISITED_AUTO = 0, ANN_VISITED_CACHE = 1, ANN_VISITED_TABLE = 2 } ann_visited_kind;
+typedef enum {
+  ANN_VISITED_AUTO = 0,
+  ANN_VISITED_CACHE = 1,
+  ANN_VISITED_TABLE = 2,
+  ANN_VISITED_CACHE_WIDE = 3
+} ann_visited_kind;
 
 typedef struct {
   uint32_t k;

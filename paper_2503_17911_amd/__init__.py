@@ -48,7 +48,7 @@ class IndexDesc(ctypes.Structure):
                 ("entry_point", ctypes.c_uint32), ("flags", ctypes.c_uint32), ("edge_labels", ctypes.c_void_p)]
 
 
-VISITED_AUTO, VISITED_CACHE, VISITED_TABLE = 0, 1, 2
+VISITED_AUTO, VISITED_CACHE, VISITED_TABLE, VISITED_CACHE_WIDE = 0, 1, 2, 3
 
 
 class SearchParams(ctypes.Structure):

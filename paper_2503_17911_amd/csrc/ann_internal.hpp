@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "ann.h"
 
 namespace ann {
@@ -22,7 +24,7 @@ struct LevelDev {
   float *norm_term = nullptr;  // [n] or nullptr
 };
 
-// Per-index scratch for the folded queries of one batch.
+// Scratch for the folded queries of one batch (one per code level and stream).
 struct Workspace {
   uint32_t nq_cap = 0;
   uint8_t *tq = nullptr;   // [nq_cap][tq_stride] folded query in kernel layout
@@ -32,6 +34,17 @@ struct Workspace {
   uint32_t tq_stride = 0;
   const float *folded_q = nullptr;  // the batch whose folded form the buffers hold (as last launched)
   uint32_t folded_nq = 0;
+};
+
+// The workspaces of the calls issued on one stream.  Work on a stream runs in
+// order, so calls on the same stream may share them; calls on different
+// streams get different sets and may be in flight together.
+constexpr int kMaxStreamWorkspaces = 8;
+struct StreamWorkspaces {
+  hipStream_t stream = nullptr;
+  bool used = false;
+  uint64_t last_use = 0;
+  Workspace ws[ANN_MAX_LEVELS];
 };
 
 }  // namespace ann
@@ -49,7 +62,9 @@ struct ann_index {
   uint32_t *pivot_ids = nullptr;   // [n_pivots] their node ids
   uint32_t n_pivots = 0;
   ann::LevelDev level[ANN_MAX_LEVELS];
-  ann::Workspace ws[ANN_MAX_LEVELS];
+  ann::StreamWorkspaces stream_ws[ann::kMaxStreamWorkspaces];
+  uint64_t ws_clock = 0;
+  std::mutex ws_mutex;  // guards the stream -> workspace table
   int device = 0;
 };
 
@@ -72,8 +87,14 @@ inline uint32_t tq_stride_for(const LevelDev &L) {
   return chunks * (L.bits == 8 ? 16u : 32u);
 }
 
-ann_status ensure_workspace(ann_index *index, uint32_t level, uint32_t nq);
+// The workspace of (level, stream), holding at least nq queries; *out is
+// valid until the index is destroyed or the stream's set is recycled (which
+// happens only when more than kMaxStreamWorkspaces streams have used the index,
+// after a device-wide wait).
+ann_status workspace_for(ann_index *index, uint32_t level, uint32_t nq, hipStream_t stream, Workspace **out);
+// Folds a batch into the workspace of (level, stream) and returns that
+// workspace in *ws_out when ws_out is given.
 ann_status launch_query_prep(ann_index *index, uint32_t level, const float *q, uint32_t nq, int8_t *t_plain,
-                             float *s_out, float *qlo_out, hipStream_t stream);
+                             float *s_out, float *qlo_out, hipStream_t stream, const Workspace **ws_out = nullptr);
 
 }  // namespace ann

@@ -136,10 +136,11 @@ ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_
   if (index->n_pivots == 0) return fail(ANN_EINVAL, "ann_entry_scan: call ann_build_entry_table first");
   if (nq == 0 || n_entry == 0) return fail(ANN_EINVAL, "ann_entry_scan: nq and n_entry must be positive");
   if (n_entry > (uint32_t)kScanKeep) return fail(ANN_ECAPACITY, "ann_entry_scan: n_entry = %u exceeds %d", n_entry, kScanKeep);
-  ann_status rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st);
+  const Workspace *wp = nullptr;
+  ann_status rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st, &wp);
   if (rc != ANN_OK) return rc;
   const LevelDev &L = index->level[0];
-  const Workspace &w = index->ws[0];
+  const Workspace &w = *wp;
 #define ANN_ES(B, P)                                                                                                   \
   entry_scan_kernel<B, P><<<nq, 64, 0, st>>>(index->pivot_codes, index->pivot_norm, index->pivot_ids, index->n_pivots,   \
                                              L.row_stride, L.row_stride / 16, index->metric, w.tq, w.tq_stride, w.s,    \

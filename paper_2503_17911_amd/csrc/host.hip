@@ -129,8 +129,9 @@ void destroy(ann_index *ix) {
     (void)hipFree(ix->level[l].lo);
     (void)hipFree(ix->level[l].delta);
     (void)hipFree(ix->level[l].norm_term);
-    free_workspace(ix->ws[l]);
   }
+  for (StreamWorkspaces &sw : ix->stream_ws)
+    for (Workspace &w : sw.ws) free_workspace(w);
   delete ix;
 }
 
@@ -141,8 +142,33 @@ inline int grid_for(uint64_t total, int block) {
 
 }  // namespace
 
-ann_status ensure_workspace(ann_index *ix, uint32_t level, uint32_t nq) {
-  Workspace &w = ix->ws[level];
+ann_status workspace_for(ann_index *ix, uint32_t level, uint32_t nq, hipStream_t st, Workspace **out) {
+  std::lock_guard<std::mutex> lock(ix->ws_mutex);
+  StreamWorkspaces *sw = nullptr, *free_slot = nullptr, *oldest = nullptr;
+  for (StreamWorkspaces &c : ix->stream_ws) {
+    if (c.used && c.stream == st) {
+      sw = &c;
+      break;
+    }
+    if (!c.used && !free_slot) free_slot = &c;
+    if (c.used && (!oldest || c.last_use < oldest->last_use)) oldest = &c;
+  }
+  if (!sw) {
+    if (free_slot) {
+      sw = free_slot;
+    } else {
+      // every set is taken: hand the least recently used one to this stream,
+      // once nothing on the device can still be reading it
+      ANN_HIP(hipDeviceSynchronize());
+      sw = oldest;
+      for (Workspace &w : sw->ws) w.folded_q = nullptr, w.folded_nq = 0;
+    }
+    sw->used = true;
+    sw->stream = st;
+  }
+  sw->last_use = ++ix->ws_clock;
+  Workspace &w = sw->ws[level];
+  *out = &w;
   if (nq <= w.nq_cap) return ANN_OK;
   // growth is the only allocation on the search path; it waits for work that
   // may still be using the old buffers

@@ -29,10 +29,11 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
 
   const uint32_t ef = params->ef;
   const bool capped = params->m_s != 0 && params->m_s < index->degree;
-  if (params->visited_kind > ANN_VISITED_TABLE) return fail(ANN_EINVAL, "ann_search_batch: unknown visited_kind %u", params->visited_kind);
-  if (params->visited_kind == ANN_VISITED_CACHE && capped)
+  if (params->visited_kind > ANN_VISITED_CACHE_WIDE) return fail(ANN_EINVAL, "ann_search_batch: unknown visited_kind %u", params->visited_kind);
+  const bool wide = params->visited_kind == ANN_VISITED_CACHE_WIDE;
+  if ((params->visited_kind == ANN_VISITED_CACHE || wide) && capped)
     return fail(ANN_EINVAL, "ann_search_batch: the cap m_s needs ANN_VISITED_TABLE (its choice of neighbours depends on the visited set)");
-  const bool cache = params->visited_kind == ANN_VISITED_CACHE || (params->visited_kind == ANN_VISITED_AUTO && !capped);
+  const bool cache = params->visited_kind == ANN_VISITED_CACHE || wide || (params->visited_kind == ANN_VISITED_AUTO && !capped);
   // the table must hold the pool and one step's candidates below 3/4 load
   // after a rebuild; the cache has no such minimum
   uint32_t need = cache ? 64u : 2 * (ef + 64 * p), min_log2 = 0;
@@ -57,16 +58,21 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   }
   if (vis_log2 > 13) return fail(ANN_ECAPACITY, "ann_search_batch: the visited set would need more than 8192 slots");
 
+  const Workspace *wp = nullptr;
   if (params->reuse_folded_queries) {
-    if (index->ws[0].folded_q != q || index->ws[0].folded_nq != nq)
-      return fail(ANN_EINVAL, "ann_search_batch: reuse_folded_queries, but the last folding on this index was of another batch");
+    Workspace *mine = nullptr;
+    ann_status rc = workspace_for(index, 0, nq, st, &mine);
+    if (rc != ANN_OK) return rc;
+    if (mine->folded_q != q || mine->folded_nq != nq)
+      return fail(ANN_EINVAL, "ann_search_batch: reuse_folded_queries, but the last folding for this index on this stream was of another batch");
+    wp = mine;
   } else {
-    ann_status rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st);
+    ann_status rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st, &wp);
     if (rc != ANN_OK) return rc;
   }
 
   const LevelDev &L = index->level[0];
-  const Workspace &w = index->ws[0];
+  const Workspace &w = *wp;
   SearchArgs a{};
   a.codes = L.codes;
   a.norm_term = index->metric == ANN_L2 ? L.norm_term : nullptr;
@@ -99,12 +105,15 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   a.ef = ef;
   a.vis_log2 = vis_log2;
   a.vis_cache = cache ? 1u : 0u;
+  // 16-bit tags (twice the entries in the same memory) while (set, tag) can name every node
+  const bool packed = cache && !wide && ((index->n - 1) >> vis_log2) + 1 < 0xFFFFu;
+  a.vis_packed = packed ? 1u : 0u;
   a.nq = nq;
   a.p = p;
   int m = 1;
   while (64 * m < (int)ef) m <<= 1;
   const bool multi = params->mode != 0;
-  const bool fast = cache && !a.filtered && !a.prs_codes && (!multi || (index->degree <= 32 && p == (uint32_t)kMaxExpansionsPerStep));
+  const bool fast = packed && !a.filtered && !a.prs_codes && (!multi || (index->degree <= 32 && p == (uint32_t)kMaxExpansionsPerStep));
   return fast ? launch_search_fast(a, L.bits, L.search_lanes, m, multi, st)
               : launch_search_general(a, L.bits, L.search_lanes, m, multi, st);
 }

@@ -60,6 +60,7 @@ struct SearchArgs {
   uint32_t row_stride, n_chunks, degree, metric, tq_stride, n_entry, entry_point, ef, vis_log2, nq, p;
   uint32_t filtered;  // the label test and/or the per-expansion cap m_s is active
   uint32_t vis_cache;  // visited set is the two-way cache
+  uint32_t vis_packed;  // the cache keeps 16-bit tags, two ways to a word (needs (n - 1 >> vis_log2) + 1 < 0xFFFF)
   uint32_t m_s;
   float alpha_s;
 };
@@ -109,6 +110,7 @@ struct SearchWave {
   __device__ __forceinline__ uint32_t &cand_at(int i) const { return cand[FAST ? 2 * i + 1 : i]; }
 
   __device__ __forceinline__ bool use_cache() const { return FAST || a.vis_cache != 0; }
+  __device__ __forceinline__ bool use_packed() const { return FAST || a.vis_packed != 0; }
   __device__ __forceinline__ bool use_prs() const { return !FAST && a.prs_codes != nullptr; }
   __device__ __forceinline__ bool use_filter() const { return !FAST && a.filtered != 0; }
   __device__ __forceinline__ bool use_pairs() const { return PMAX > 1 && (FAST || a.degree <= 32); }
@@ -176,19 +178,51 @@ struct SearchWave {
     for (uint32_t i = lane; i <= vis_mask; i += kWave) vis[i] = kEmpty;
   }
 
-  // Two-way cache of node ids: a set is two adjacent slots, way 0 the more
-  // recently tested.  The id goes into way 0; what it displaces moves to way 1,
-  // and what that displaces is forgotten.  The exchanges make lanes that test
-  // the same id in one instruction see each other (in almost every
-  // interleaving; the merge copes with the rest).  A forgotten id may come back
-  // as a candidate and is then recognised when it is merged (it equals a pool
-  // entry or another candidate) or rejected again by the pool's last entry.
-  __device__ __forceinline__ bool cache_test_and_set(uint32_t id) {
+  // Two-way cache of node ids with full-width entries: a set is two adjacent
+  // slots, way 0 the more recently tested.  The id goes into way 0; what it
+  // displaces moves to way 1, and what that displaces is forgotten.  The
+  // exchanges make lanes that test the same id in one instruction see each
+  // other (in almost every interleaving; the merge copes with the rest).  A
+  // forgotten id may come back as a candidate and is then recognised when it
+  // is merged (it equals a pool entry or another candidate) or rejected again
+  // by the pool's last entry.
+  __device__ __forceinline__ bool wide_cache_test_and_set(uint32_t id) {
     uint32_t *set = &vis[((id * 0x9E3779B1u) >> vis_shift) & ~1u];
     const uint32_t o0 = atomicExch(set, id);
     if (o0 == id) return false;
     if (o0 == kEmpty) return true;  // way 1 is filled only from way 0
     return atomicExch(set + 1, o0) != id;
+  }
+
+  // The same cache with twice the entries in the same memory: a set is one
+  // word, way 0 its low half and way 1 its high half, and an entry is the
+  // 16-bit tag (id >> log2 sets) + 1.  The set index is the id's low bits
+  // mixed with a hash of the tag, so (set, tag) still names exactly one id:
+  // a hit is never a different node.  0xFFFF marks an empty way.
+  __device__ __forceinline__ uint32_t *packed_set(uint32_t id, uint32_t &tag) const {
+    const uint32_t hi = id >> a.vis_log2;
+    tag = hi + 1u;
+    return &vis[(id ^ ((hi * 0x9E3779B1u) >> vis_shift)) & vis_mask];
+  }
+  static __device__ __forceinline__ bool packed_hit(uint32_t word, uint32_t tag) {
+    return (word & 0xFFFFu) == tag || (word >> 16) == tag;
+  }
+  __device__ __forceinline__ bool packed_cache_test_and_set(uint32_t id) {
+    uint32_t tag;
+    uint32_t *set = packed_set(id, tag);
+    uint32_t seen = *set;
+    for (;;) {
+      if (packed_hit(seen, tag)) return false;
+      // the new tag becomes way 0, way 0 moves to way 1, way 1 is forgotten;
+      // a lane that lost the word to another lane looks at what that one wrote
+      const uint32_t was = atomicCAS(set, seen, (seen << 16) | tag);
+      if (was == seen) return true;
+      seen = was;
+    }
+  }
+
+  __device__ __forceinline__ bool cache_test_and_set(uint32_t id) {
+    return use_packed() ? packed_cache_test_and_set(id) : wide_cache_test_and_set(id);
   }
 
   // true if id was not in the table (and now is)
@@ -209,6 +243,11 @@ struct SearchWave {
   // Membership test without insertion.
   __device__ __forceinline__ bool lookup(uint32_t id) {
     if (use_cache()) {
+      if (use_packed()) {
+        uint32_t tag;
+        const uint32_t *set = packed_set(id, tag);
+        return packed_hit(*set, tag);
+      }
       const uint32_t *set = &vis[((id * 0x9E3779B1u) >> vis_shift) & ~1u];
       return set[0] == id || set[1] == id;
     }
@@ -227,6 +266,30 @@ struct SearchWave {
   // the latency of the LDS atomics overlaps.  Bit 0 / bit 1 of the result: id0
   // / id1 was not in the table (and now is).  A lane's two ids may be equal.
   __device__ __forceinline__ int test_and_set2(bool v0, uint32_t id0, bool v1, uint32_t id1) {
+    if (use_cache() && use_packed()) {
+      uint32_t t0, t1;
+      uint32_t *set0 = packed_set(id0, t0), *set1 = packed_set(id1, t1);
+      uint32_t seen0 = v0 ? *set0 : 0u, seen1 = v1 ? *set1 : 0u;
+      int fresh = 0;
+      while (v0 || v1) {
+        v0 = v0 && !packed_hit(seen0, t0);
+        v1 = v1 && !packed_hit(seen1, t1);
+        uint32_t was0 = seen0, was1 = seen1;
+        if (v0) was0 = atomicCAS(set0, seen0, (seen0 << 16) | t0);
+        if (v1) was1 = atomicCAS(set1, seen1, (seen1 << 16) | t1);
+        if (v0 && was0 == seen0) {
+          fresh |= 1;
+          v0 = false;
+        }
+        if (v1 && was1 == seen1) {
+          fresh |= 2;
+          v1 = false;
+        }
+        seen0 = was0;
+        seen1 = was1;
+      }
+      return fresh;
+    }
     if (use_cache()) {
       uint32_t *set0 = &vis[((id0 * 0x9E3779B1u) >> vis_shift) & ~1u];
       uint32_t *set1 = &vis[((id1 * 0x9E3779B1u) >> vis_shift) & ~1u];

@@ -215,11 +215,12 @@ __global__ __launch_bounds__(64) void query_prep_kernel(const float *__restrict_
 }
 
 ann_status launch_query_prep(ann_index *ix, uint32_t level, const float *q, uint32_t nq, int8_t *t_plain, float *s_out,
-                             float *qlo_out, hipStream_t st) {
-  ann_status rc = ensure_workspace(ix, level, nq);
+                             float *qlo_out, hipStream_t st, const Workspace **ws_out) {
+  Workspace *wp = nullptr;
+  ann_status rc = workspace_for(ix, level, nq, st, &wp);
   if (rc != ANN_OK) return rc;
   const LevelDev &L = ix->level[level];
-  Workspace &w = ix->ws[level];
+  Workspace &w = *wp;
   if (L.bits == 8)
     query_prep_kernel<8><<<nq, 64, (size_t)ix->d * sizeof(double), st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t, t_plain,
                                             s_out, qlo_out);
@@ -229,6 +230,7 @@ ann_status launch_query_prep(ann_index *ix, uint32_t level, const float *q, uint
   ANN_HIP(hipGetLastError());
   w.folded_q = q;
   w.folded_nq = nq;
+  if (ws_out) *ws_out = wp;
   return ANN_OK;
 }
 

@@ -61,7 +61,7 @@ def test_host_side_argument_checks():
         ann.ann_search_batch(1, 1, 1, k=10, ef=64, out_ids=1, visited_kind=ann.VISITED_TABLE, visited_slots=128)
     assert "minimum" in str(e.value)
     with pytest.raises(ann.AnnError) as e:
-        ann.ann_search_batch(1, 1, 1, k=10, ef=64, out_ids=1, visited_kind=3)
+        ann.ann_search_batch(1, 1, 1, k=10, ef=64, out_ids=1, visited_kind=4)
     assert "visited_kind" in str(e.value)
     with pytest.raises(ann.AnnError) as e:
         ann.ann_search_batch(1, 1, 1, k=10, ef=64, out_ids=1, visited_slots=16384)

@@ -332,13 +332,15 @@ def test_visited_cache_forgets_without_changing_results(H, c1, slots, P):
     ix = H.GpuIndex(X, adj, entry, [lv], oracle.L2)
     for ef in (10, 64, 200):
         orc = oracle.search_batch(lv, w.d, adj, entry, Q, ef, expansions_per_step=P)
-        gpu = ix.search(Q, ef, mode=int(P > 1), expansions_per_step=P if P > 1 else 0,
-                        visited_kind=H.ann.VISITED_CACHE, visited_slots=slots)
-        assert_search_equal(gpu, orc, check_counts=False)
-        assert (gpu[3][:, 0] == orc[3][:, 0]).all() and (gpu[3][:, 2] == orc[3][:, 2]).all()
-        assert (gpu[3][:, 1] >= orc[3][:, 1]).all()
-        if slots == 64:
-            assert gpu[3][:, 1].sum() > orc[3][:, 1].sum()   # forgetting did happen
+        # both forms of the cache: 16-bit tags two to a slot, and whole ids
+        for kind in (H.ann.VISITED_CACHE, H.ann.VISITED_CACHE_WIDE):
+            gpu = ix.search(Q, ef, mode=int(P > 1), expansions_per_step=P if P > 1 else 0,
+                            visited_kind=kind, visited_slots=slots)
+            assert_search_equal(gpu, orc, check_counts=False)
+            assert (gpu[3][:, 0] == orc[3][:, 0]).all() and (gpu[3][:, 2] == orc[3][:, 2]).all()
+            assert (gpu[3][:, 1] >= orc[3][:, 1]).all()
+            if slots == 64 and ef > 10:
+                assert gpu[3][:, 1].sum() > orc[3][:, 1].sum()   # forgetting did happen
     ix.close()
 
 
@@ -352,8 +354,9 @@ def test_visited_cache_with_repeated_entry_nodes(H, c1):
     base = rng.integers(0, w.n, size=(nq, 3)).astype(np.uint32)
     ent = np.concatenate([base, base[:, ::-1], base[:, :2]], axis=1)      # every id two or three times
     orc = oracle.search_batch(lv, w.d, adj, entry, Q[:nq], 48, entries=ent)
-    gpu = ix.search(Q[:nq], 48, entries=ent, visited_kind=H.ann.VISITED_CACHE, visited_slots=64)
-    assert_search_equal(gpu, orc, check_counts=False)
+    for kind in (H.ann.VISITED_CACHE, H.ann.VISITED_CACHE_WIDE):
+        gpu = ix.search(Q[:nq], 48, entries=ent, visited_kind=kind, visited_slots=64)
+        assert_search_equal(gpu, orc, check_counts=False)
     ix.close()
 
 
@@ -491,6 +494,68 @@ def test_query_order_does_not_change_results(H, c1, P):
     assert_search_equal(again, orc, check_counts=False)
     with pytest.raises(H.ann.AnnError):
         ix.search(Q[:5], 64, reuse_folded_queries=True)
+    ix.close()
+
+
+def test_batches_in_flight_on_two_streams(H, c1):
+    """Two different batches issued on two streams of one index, neither waiting
+    for the other, each get the oracle's result: the folded queries of one do
+    not overwrite the other's.  The second pass reuses each stream's folding,
+    which the other stream's batch must have left alone."""
+    import torch
+    w, X, Q, adj, entry, lv = (c1[k] for k in ("w", "X", "Q", "adj", "entry", "level"))
+    ix = H.GpuIndex(X, adj, entry, [lv], oracle.L2)
+    ef = 64
+    batches = [np.ascontiguousarray(Q[:60]), np.ascontiguousarray(Q[60:100])]
+    assert batches[1].shape[0] == 40
+    lanes = []
+    for b in batches:
+        nq = b.shape[0]
+        lanes.append(dict(q=H.dev(b), nq=nq, stream=torch.cuda.Stream(),
+                          ids=torch.empty((nq, ef), dtype=torch.int32, device=H.DEV),
+                          keys=torch.empty((nq, ef), dtype=torch.float32, device=H.DEV)))
+    torch.cuda.synchronize()
+    for reuse in (False, True, True):
+        for L in lanes:
+            L["ids"].fill_(-1)
+        torch.cuda.synchronize()
+        for L in lanes:
+            H.ann.ann_search_batch(ix.handle, L["q"], L["nq"], k=1, ef=ef, mode=1, expansions_per_step=4,
+                                   out_ids=L["ids"], out_keys=L["keys"], reuse_folded_queries=reuse,
+                                   stream=L["stream"].cuda_stream)
+        torch.cuda.synchronize()
+        for L, b in zip(lanes, batches):
+            oi, ok, od, oc = oracle.search_batch(lv, w.d, adj, entry, b, ef, expansions_per_step=4)
+            np.testing.assert_array_equal(H.as_u32(L["ids"]), oi)
+            np.testing.assert_array_equal(L["keys"].cpu().numpy(), ok)
+    # a folding made on one stream is not taken for the other stream's
+    with pytest.raises(H.ann.AnnError):
+        H.ann.ann_search_batch(ix.handle, lanes[0]["q"], lanes[0]["nq"], k=1, ef=ef, out_ids=lanes[0]["ids"],
+                               reuse_folded_queries=True, stream=lanes[1]["stream"].cuda_stream)
+    ix.close()
+
+
+def test_more_streams_than_workspaces(H, c1):
+    """An index keeps a bounded number of per-stream workspaces; streams beyond
+    that take over an old one and still get the oracle's result."""
+    import torch
+    w, X, Q, adj, entry, lv = (c1[k] for k in ("w", "X", "Q", "adj", "entry", "level"))
+    ix = H.GpuIndex(X, adj, entry, [lv], oracle.L2)
+    ef, nq = 32, 9
+    assert Q.shape[0] >= 11 * nq
+    streams = [torch.cuda.Stream() for _ in range(11)]
+    assert len({s.cuda_stream for s in streams}) == len(streams)
+    outs = []
+    for i, s in enumerate(streams):
+        q = H.dev(np.ascontiguousarray(Q[i * nq:(i + 1) * nq]))
+        ids = torch.empty((nq, ef), dtype=torch.int32, device=H.DEV)
+        torch.cuda.synchronize()
+        H.ann.ann_search_batch(ix.handle, q, nq, k=1, ef=ef, out_ids=ids, stream=s.cuda_stream)
+        outs.append((q, ids))
+    torch.cuda.synchronize()
+    for i, (q, ids) in enumerate(outs):
+        oi, ok, od, oc = oracle.search_batch(lv, w.d, adj, entry, Q[i * nq:(i + 1) * nq], ef)
+        np.testing.assert_array_equal(H.as_u32(ids), oi)
     ix.close()
 
 
