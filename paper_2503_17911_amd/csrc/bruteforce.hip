@@ -205,6 +205,229 @@ __global__ __launch_bounds__(256) void bf_tile_kernel(const float *__restrict__ 
   }
 }
 
+
+// ---------------------------------------------------------------------------
+// Larger tiles for the common case (d a multiple of 4, moderate k): a
+// workgroup of four wavefronts computes 64 WR queries x 64 WC base rows per
+// tile, every wavefront a 64 x 64 block as 2 x 2 MFMA 32x32 accumulators, so
+// four matrix instructions in a row never wait for each other and one LDS read
+// feeds two of them.  Rows are staged K-contiguous (pitch KC + 4 floats: 16-byte
+// LDS reads and writes without bank conflicts); the two halves of a wavefront
+// take the two halves of a K chunk, which only changes the order in which the
+// products are added.  The next chunk is fetched into registers before the
+// chunk's matrix work and written to the other LDS buffer after it: one barrier
+// per chunk.
+//
+// Top-k: per query a threshold and a buffer of cb (score, id) entries.  A score
+// below the threshold is appended; a row whose buffer is more than half way
+// from kp to cb is cut back to its kp best (threshold = the kp-th), by the
+// wavefront that owns the row.  An append that finds the buffer full stays
+// pending and is tried again after the cut.
+template <int WR, int WC, int KC, int EPL>
+__global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__ X, const float *__restrict__ xnorm,
+                                                       uint64_t n, uint32_t d, const float *__restrict__ Q, uint32_t nq,
+                                                       uint32_t metric, uint64_t rows_per_slab, uint32_t kp, uint32_t cb,
+                                                       uint32_t *__restrict__ cand_out /*[nq][slabs][kp]*/) {
+  constexpr int QT = 64 * WR, BT = 64 * WC, ROWS = QT + BT, P = KC + 4;
+  constexpr int C4 = KC / 4;            // float4 per staged row
+  constexpr int RP = 256 / C4;          // rows staged per pass of the workgroup
+  constexpr int NLD = ROWS / RP;        // passes
+  static_assert(WR * WC == 4 && ROWS % RP == 0 && QT % RP == 0, "tile shape");
+  extern __shared__ float smem_f[];
+  float *stage_buf = smem_f;                                // [2][ROWS][P]
+  float *thr = stage_buf + 2 * ROWS * P;                    // [QT]
+  uint32_t *cnt = reinterpret_cast<uint32_t *>(thr + QT);   // [QT]
+  uint64_t *buf = reinterpret_cast<uint64_t *>(cnt + QT);   // [QT][cb]
+
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int wr = wave / WC, wc = wave % WC, half = lane / 32, l32 = lane % 32;
+  const uint32_t q0 = blockIdx.x * QT;
+  const uint32_t slab = blockIdx.y, n_slabs = gridDim.y;
+  const uint64_t b_begin = (uint64_t)slab * rows_per_slab;
+  const uint64_t b_end = b_begin + rows_per_slab < n ? b_begin + rows_per_slab : n;
+  const uint32_t limit = kp + (cb - kp) / 2;   // a longer buffer is cut back
+
+  for (int r = tid; r < QT; r += 256) {
+    thr[r] = q0 + r < nq ? INFINITY : -INFINITY;   // rows past the batch never take anything
+    cnt[r] = 0;
+  }
+
+  const int s_row = tid / C4, s_col = (tid % C4) * 4;
+  float4 reg[NLD];
+  auto fetch = [&](uint64_t t0, uint32_t k0) {
+    const uint32_t kk = k0 + s_col;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int row = s_row + RP * i;   // a pass is all queries or all base rows (QT % RP == 0)
+      reg[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (row < QT) {
+        const uint32_t qi = q0 + row;
+        if (qi < nq && kk < d) reg[i] = *reinterpret_cast<const float4 *>(Q + (uint64_t)qi * d + kk);
+      } else {
+        const uint64_t bi = t0 + (row - QT);
+        if (bi < b_end && kk < d) reg[i] = *reinterpret_cast<const float4 *>(X + bi * d + kk);
+      }
+    }
+  };
+  auto stage = [&](int b) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i)
+      *reinterpret_cast<float4 *>(stage_buf + ((size_t)b * ROWS + s_row + RP * i) * P + s_col) = reg[i];
+  };
+
+  // Cut row `row` back to its kp smallest entries (ids differ, so no ties).
+  auto cut = [&](int row) {
+    const uint32_t c = cnt[row] < cb ? cnt[row] : cb;
+    if (c <= kp) {
+      if (lane == 0) cnt[row] = c;
+      return;
+    }
+    uint64_t *list = buf + (size_t)row * cb;
+    uint64_t mine[EPL];
+    uint32_t rank[EPL];
+#pragma unroll
+    for (int u = 0; u < EPL; ++u) {
+      const uint32_t i = lane + u * kWave;
+      mine[u] = i < c ? list[i] : ~0ull;
+      rank[u] = 0;
+    }
+    for (uint32_t j = 0; j < c; ++j) {
+      const uint64_t o = list[j];
+#pragma unroll
+      for (int u = 0; u < EPL; ++u) rank[u] += o < mine[u] ? 1u : 0u;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int u = 0; u < EPL; ++u) {
+      const uint32_t i = lane + u * kWave;
+      if (i < c && rank[u] < kp) {
+        list[rank[u]] = mine[u];
+        if (rank[u] == kp - 1) thr[row] = unorder_f32((uint32_t)(mine[u] >> 32));
+      }
+    }
+    if (lane == 0) cnt[row] = kp;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  };
+  // every row over `over` entries is cut by the wavefront that owns it (row % 4 == wave)
+  auto cut_rows_over = [&](uint32_t over) {
+    const int mine_row = wave + 4 * lane;   // lanes 0 .. QT/4-1 each look at one row
+    const bool need = lane < QT / 4 && cnt[mine_row] > over;
+    for (uint64_t m = __ballot(need); m; m &= m - 1) cut(wave + 4 * __builtin_ctzll(m));
+  };
+
+  const uint32_t n_chunks = (d + KC - 1) / KC;
+  const float scale = metric == ANN_L2 ? -2.0f : -1.0f;
+  int cur = 0;
+  if (b_begin < b_end) {
+    fetch(b_begin, 0);
+    stage(0);
+  }
+  __syncthreads();
+
+  for (uint64_t t0 = b_begin; t0 < b_end; t0 += BT) {
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+    // norm terms of this lane's two columns; +inf keeps columns past the end out
+    float xn[2];
+    uint64_t col_id[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      col_id[b] = t0 + wc * 64 + b * 32 + l32;
+      xn[b] = col_id[b] < b_end ? (metric == ANN_L2 ? xnorm[col_id[b]] : 0.f) : INFINITY;
+    }
+    for (uint32_t c = 0; c < n_chunks; ++c) {
+      const bool last_chunk = c + 1 == n_chunks;
+      const uint64_t nt0 = last_chunk ? t0 + BT : t0;
+      const bool more = nt0 < b_end;
+      if (more) fetch(nt0, last_chunk ? 0 : (c + 1) * KC);
+      const float *ap = stage_buf + ((size_t)cur * ROWS + wr * 64 + l32) * P + half * (KC / 2);
+      const float *bp = stage_buf + ((size_t)cur * ROWS + QT + wc * 64 + l32) * P + half * (KC / 2);
+#pragma unroll
+      for (int j = 0; j < KC / 8; ++j) {
+        const float4 a0 = *reinterpret_cast<const float4 *>(ap + 4 * j);
+        const float4 a1 = *reinterpret_cast<const float4 *>(ap + 32 * P + 4 * j);
+        const float4 b0 = *reinterpret_cast<const float4 *>(bp + 4 * j);
+        const float4 b1 = *reinterpret_cast<const float4 *>(bp + 32 * P + 4 * j);
+        const float av0[4] = {a0.x, a0.y, a0.z, a0.w}, av1[4] = {a1.x, a1.y, a1.z, a1.w};
+        const float bv0[4] = {b0.x, b0.y, b0.z, b0.w}, bv1[4] = {b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0[e], bv0[e], acc[0][0], 0, 0, 0);
+          acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0[e], bv1[e], acc[0][1], 0, 0, 0);
+          acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av1[e], bv0[e], acc[1][0], 0, 0, 0);
+          acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av1[e], bv1[e], acc[1][1], 0, 0, 0);
+        }
+      }
+      if (more) stage(cur ^ 1);
+      __syncthreads();
+      cur ^= 1;
+    }
+
+    // acc[a][b][i] is query row wr*64 + a*32 + 8*(i/4) + 4*half + i%4 against
+    // base column col_id[b].  Bit b*16 + i of pend[a]: that score is below its
+    // row's threshold and not yet in the buffer.
+    uint32_t pend[2] = {0u, 0u};
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 t4 = *reinterpret_cast<const float4 *>(thr + wr * 64 + a * 32 + 8 * g + 4 * half);
+        const float tv[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+            pend[a] |= fmaf(scale, acc[a][b][4 * g + e], xn[b]) < tv[e] ? 1u << (b * 16 + 4 * g + e) : 0u;
+      }
+    bool any = (pend[0] | pend[1]) != 0;
+    if (__syncthreads_or(any ? 1 : 0) == 0) continue;   // nothing for any row of the tile
+    for (;;) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const uint32_t bit = 1u << (b * 16 + i);
+            if (pend[a] & bit) {
+              const int row = wr * 64 + a * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+              const float score = fmaf(scale, acc[a][b][i], xn[b]);
+              if (score < thr[row]) {   // the threshold may have dropped since the bit was set
+                const uint32_t pos = atomicAdd(&cnt[row], 1u);
+                if (pos < cb) {
+                  buf[(size_t)row * cb + pos] = ((uint64_t)order_u32(score) << 32) | (uint32_t)col_id[b];
+                  pend[a] &= ~bit;
+                }
+              } else {
+                pend[a] &= ~bit;
+              }
+            }
+          }
+      __syncthreads();
+      cut_rows_over(limit);
+      any = (pend[0] | pend[1]) != 0;
+      if (__syncthreads_or(any ? 1 : 0) == 0) break;
+    }
+  }
+  __syncthreads();
+  cut_rows_over(kp);
+  __syncthreads();
+  // hand the survivors of this slab to the exact stage
+  for (int e = tid; e < QT * (int)kp; e += 256) {
+    const int row = e / kp, j = e % kp;
+    const uint32_t qi = q0 + row;
+    if (qi < nq)
+      cand_out[((uint64_t)qi * n_slabs + slab) * kp + j] = (uint32_t)j < cnt[row] ? (uint32_t)buf[(size_t)row * cb + j] : ANN_PAD_ID;
+  }
+}
+
 }  // namespace ann
 
 using namespace ann;
@@ -219,26 +442,53 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   if (d > 2048) return fail(ANN_ECAPACITY, "ann_bruteforce_topk: d = %u exceeds 2048", d);
 
   const uint32_t kp = k + 8;               // candidates kept per (query, slab): k plus a margin for fp32 score error
-  const uint32_t cb = kp + kBT;            // buffer: survivors plus one tile of pushes
-  if (cb > 8 * kWave) return fail(ANN_ECAPACITY, "ann_bruteforce_topk: internal buffer too small for k = %u", k);
-  const uint32_t q_tiles = (nq + kQT - 1) / kQT;
-  // enough workgroups to fill the chip, at most 4096 exact re-evaluations per query
+  // Tile shape: 128 queries x 128 base rows with a 64-entry buffer per query
+  // while k is small, 64 x 256 with a longer buffer for larger k, and the
+  // 32 x 128 kernel with scalar staging for what is left (d not a multiple of
+  // 4, k above 152).
+  int shape = 0;
+  uint32_t cb = kp + kBT, q_rows = kQT, b_rows = kBT;
+  // rows can be read 16 bytes at a time
+  const bool vec4 = d % 4 == 0 && (reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(q)) % 16 == 0;
+  if (vec4 && kp + 32 <= 64) {
+    shape = 1;
+    cb = 64;
+    q_rows = 128;
+    b_rows = 128;
+  } else if (vec4 && kp + 32 <= 192) {
+    shape = 2;
+    cb = kp + 48 <= 192 ? kp + 48 : 192;
+    q_rows = 64;
+    b_rows = 256;
+  }
+  if (shape == 0 && cb > 8 * kWave) return fail(ANN_ECAPACITY, "ann_bruteforce_topk: internal buffer too small for k = %u", k);
+  const uint32_t q_tiles = (nq + q_rows - 1) / q_rows;
+  const uint64_t tiles = (n + b_rows - 1) / b_rows;
+  // slabs of base rows: about four workgroups per compute unit over the whole
+  // grid (256 units), at most 4096 exact re-evaluations per query
   uint32_t slabs = (1024 + q_tiles - 1) / q_tiles;
-  const uint64_t tiles = (n + kBT - 1) / kBT;
   if (slabs > tiles) slabs = (uint32_t)tiles;
   if (slabs * kp > 4096) slabs = 4096 / kp;
   if (slabs < 1) slabs = 1;
-  uint64_t rows_per_slab = ((tiles + slabs - 1) / slabs) * kBT;
+  uint64_t rows_per_slab = ((tiles + slabs - 1) / slabs) * b_rows;
   slabs = (uint32_t)((n + rows_per_slab - 1) / rows_per_slab);
 
   float *xnorm = nullptr;
   uint32_t *cand = nullptr;
-  const size_t smem = (size_t)2 * (kQT + kBT) * kLd * sizeof(float) + kQT * (sizeof(float) + sizeof(uint32_t)) +
-                      (size_t)kQT * cb * sizeof(uint64_t);
-  const bool vec4 = d % 4 == 0;
-  hipError_t e = hipFuncSetAttribute(vec4 ? reinterpret_cast<const void *>(bf_tile_kernel<true>)
-                                          : reinterpret_cast<const void *>(bf_tile_kernel<false>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  size_t smem;
+  const void *fn;
+  if (shape == 1) {
+    smem = (size_t)2 * 256 * (32 + 4) * sizeof(float) + 128 * 8 + (size_t)128 * cb * sizeof(uint64_t);
+    fn = reinterpret_cast<const void *>(bf_block_kernel<2, 2, 32, 1>);
+  } else if (shape == 2) {
+    smem = (size_t)2 * 320 * (16 + 4) * sizeof(float) + 64 * 8 + (size_t)64 * cb * sizeof(uint64_t);
+    fn = reinterpret_cast<const void *>(bf_block_kernel<1, 4, 16, 3>);
+  } else {
+    smem = (size_t)2 * (kQT + kBT) * kLd * sizeof(float) + kQT * (sizeof(float) + sizeof(uint32_t)) +
+           (size_t)kQT * cb * sizeof(uint64_t);
+    fn = vec4 ? reinterpret_cast<const void *>(bf_tile_kernel<true>) : reinterpret_cast<const void *>(bf_tile_kernel<false>);
+  }
+  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
   ANN_HIP(hipMalloc((void **)&cand, (size_t)nq * slabs * kp * sizeof(uint32_t)));
   if (metric == ANN_L2) {
@@ -249,14 +499,19 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
     }
     row_norm_kernel<<<2048, 256, 0, st>>>(x, n, d, xnorm);
   }
-  if (vec4)
-    bf_tile_kernel<true><<<dim3(q_tiles, slabs), 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
+  const dim3 grid(q_tiles, slabs);
+  if (shape == 1)
+    bf_block_kernel<2, 2, 32, 1><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
+  else if (shape == 2)
+    bf_block_kernel<1, 4, 16, 3><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
+  else if (vec4)
+    bf_tile_kernel<true><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
   else
-    bf_tile_kernel<false><<<dim3(q_tiles, slabs), 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
+    bf_tile_kernel<false><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
   e = hipGetLastError();
   ann_status rc = e == hipSuccess ? rerank_device(x, n, d, metric, q, nq, cand, slabs * kp, slabs * kp, k, out_ids,
                                                   out_dist, st)
-                                  : hip_fail(e, "bf_tile_kernel launch");
+                                  : hip_fail(e, "brute-force tile kernel launch");
   hipError_t e2 = hipStreamSynchronize(st);
   (void)hipFree(cand);
   (void)hipFree(xnorm);

@@ -389,7 +389,8 @@ def test_rerank_and_rescore(H, metric):
 
 @pytest.mark.parametrize("n,d,nq,k,metric", [(4000, 64, 70, 10, "l2"), (3001, 128, 33, 10, "ip"),
                                               (2500, 100, 5, 100, "l2"), (130, 960, 40, 10, "l2"),
-                                              (50, 16, 3, 64, "ip")])
+                                              (50, 16, 3, 64, "ip"), (3000, 30, 20, 10, "l2"),
+                                              (3000, 64, 20, 200, "l2"), (40000, 32, 300, 10, "ip")])
 def test_bruteforce_matches_fp64_exhaustive_search(H, n, d, nq, k, metric):
     w = inputs.Workload("bf", n, d, 9, 0.3, nq, seed=n + d, normalize=(metric == "ip"))
     X, Q = inputs.base_vectors(w), inputs.queries(w)
@@ -399,6 +400,20 @@ def test_bruteforce_matches_fp64_exhaustive_search(H, n, d, nq, k, metric):
     kk = min(k, n)
     H.check_rerank(gid[:, :kk], gdist[:, :kk], oid, odist.astype(np.float32), rel=1e-6)
     assert (gid[:, kk:] == PAD).all() and np.isinf(gdist[:, kk:]).all()
+
+
+@pytest.mark.parametrize("k", [10, 100])
+def test_bruteforce_with_base_rows_ordered_from_far_to_near(H, k):
+    """The worst order for a streaming top-k: every later base row is closer to
+    the queries than the earlier ones, so nearly every score beats the running
+    threshold and the candidate buffers overflow and are cut back all the time."""
+    w = inputs.Workload("bf", 30000, 32, 1, 0.3, 150, seed=77)       # one cluster: all queries near its centre
+    X, Q = inputs.base_vectors(w), inputs.queries(w)
+    far_first = np.argsort(-((X - Q.mean(0)) ** 2).sum(1), kind="stable")
+    X = np.ascontiguousarray(X[far_first])
+    gid, gdist = H.gpu_bruteforce(X, Q, k, oracle.L2)
+    oid, odist = oracle.bruteforce_topk(X, Q, k, metric=oracle.L2)
+    H.check_rerank(gid, gdist, oid, odist.astype(np.float32), rel=1e-6)
 
 
 def test_c2_full_size_sampled_queries(H):
