@@ -428,6 +428,261 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
   }
 }
 
+
+// ---------------------------------------------------------------------------
+// Small k: a 128 x 128 tile per workgroup of eight wavefronts (two per SIMD, so
+// that one's LDS and barrier waits are covered by the other's matrix work),
+// every wavefront a 32 x 64 block (two MFMA 32x32 accumulators), with the top-k
+// state owned by single wavefronts so that nothing after the matrix work needs
+// a barrier.  Each wavefront keeps, for each of its 32 query rows, its own list
+// of the best candidates among the base columns it has seen (two lists per
+// query and slab, both handed to the exact stage).
+//
+// The accumulators take one more matrix step per tile whose only non-zero
+// products are 1 x (-|x|^2 / 2) (L2; 0 for inner product; -inf for columns past
+// the end), so that score = scale * acc with scale = -2 / -1, and "score below
+// the row's threshold" is one compare, acc > u[row] with u = thr / scale.
+// Hits are rare once the thresholds have settled.  A pass over the
+// accumulators writes the hits to a staging list in LDS (in element order, at
+// most kStageCap per pass); the flush takes them, one per lane, into their
+// rows' lists (LDS atomic for the slot); a list found full is cut back to its
+// kp best (rank counting over lanes), which lowers the row's threshold, and the
+// hit is tried again.
+constexpr int kOwnList = 32;     // entries per (row, wavefront) list
+constexpr int kStageCap = 128;   // staged hits per wavefront and pass
+constexpr int kOwnWaves = 8, kOwnRows = 32;   // wavefronts per workgroup, query rows per wavefront
+
+// number of set bits of mask below this lane's
+__device__ __forceinline__ int bf_lanes_below(uint64_t mask) {
+  return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+template <int KC>
+__global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X, const float *__restrict__ xnorm,
+                                                     uint64_t n, uint32_t d, const float *__restrict__ Q, uint32_t nq,
+                                                     uint32_t metric, uint64_t rows_per_slab, uint32_t kp,
+                                                     uint32_t *__restrict__ cand_out /*[nq][slabs][2][kp]*/) {
+  constexpr int WC = 2, QT = 128, BT = 128, ROWS = QT + BT, P = KC + 4, NT = 64 * kOwnWaves;
+  constexpr int C4 = KC / 4, RP = NT / C4, NLD = ROWS / RP;
+  constexpr int NR = kOwnWaves * kOwnRows;   // (row, wavefront) lists per workgroup
+  static_assert(ROWS % RP == 0 && QT % RP == 0 && kOwnWaves / WC * kOwnRows == QT, "tile shape");
+  extern __shared__ float smem_f[];
+  float *stage_buf = smem_f;                                                  // [2][ROWS][P]
+  float *u_all = stage_buf + 2 * ROWS * P;                                    // [NR]  acc must exceed this
+  uint32_t *thr_all = reinterpret_cast<uint32_t *>(u_all + NR);               // [NR]  ordered score an entry must be below
+  uint32_t *cnt_all = thr_all + NR;                                           // [NR]
+  uint64_t *list_all = reinterpret_cast<uint64_t *>(cnt_all + NR);            // [NR][kOwnList]
+  uint64_t *st_all = list_all + (size_t)NR * kOwnList;                        // [kOwnWaves][kStageCap]
+  uint8_t *st_row_all = reinterpret_cast<uint8_t *>(st_all + kOwnWaves * kStageCap);
+
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int wr = wave / WC, wc = wave % WC, half = lane / 32, l32 = lane % 32;
+  const uint32_t q0 = blockIdx.x * QT;
+  const uint32_t slab = blockIdx.y, n_slabs = gridDim.y;
+  const uint64_t b_begin = (uint64_t)slab * rows_per_slab;
+  const uint64_t b_end = b_begin + rows_per_slab < n ? b_begin + rows_per_slab : n;
+  const float scale = metric == ANN_L2 ? -2.0f : -1.0f;
+  const float inv_scale = metric == ANN_L2 ? -0.5f : -1.0f;
+
+  // this wavefront's state (its rows are queries q0 + wr*32 + 0..31)
+  float *u = u_all + wave * kOwnRows;
+  uint32_t *thr = thr_all + wave * kOwnRows;
+  uint32_t *cnt = cnt_all + wave * kOwnRows;
+  uint64_t *list = list_all + (size_t)wave * kOwnRows * kOwnList;
+  uint64_t *st = st_all + (size_t)wave * kStageCap;
+  uint8_t *st_row = st_row_all + (size_t)wave * kStageCap;
+  if (lane < kOwnRows) {
+    const bool live = q0 + wr * kOwnRows + lane < nq;
+    u[lane] = live ? -INFINITY : INFINITY;   // rows past the batch never take anything
+    thr[lane] = order_u32(INFINITY);
+    cnt[lane] = 0;
+  }
+
+  const int s_row = tid / C4, s_col = (tid % C4) * 4;
+  float4 reg[NLD];
+  auto fetch = [&](uint64_t t0, uint32_t k0) {
+    const uint32_t kk = k0 + s_col;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int row = s_row + RP * i;   // a pass is all queries or all base rows (QT % RP == 0)
+      reg[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (row < QT) {
+        const uint32_t qi = q0 + row;
+        if (qi < nq && kk < d) reg[i] = *reinterpret_cast<const float4 *>(Q + (uint64_t)qi * d + kk);
+      } else {
+        const uint64_t bi = t0 + (row - QT);
+        if (bi < b_end && kk < d) reg[i] = *reinterpret_cast<const float4 *>(X + bi * d + kk);
+      }
+    }
+  };
+  auto stage = [&](int b) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i)
+      *reinterpret_cast<float4 *>(stage_buf + ((size_t)b * ROWS + s_row + RP * i) * P + s_col) = reg[i];
+  };
+  auto wave_sync = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+
+  // Cut list `row` (c entries, c <= kOwnList) back to its kp smallest; returns the new length.
+  auto cut = [&](int row, uint32_t c) -> uint32_t {
+    uint64_t *l = list + (size_t)row * kOwnList;
+    const uint64_t mine = (uint32_t)lane < c ? l[lane < kOwnList ? lane : 0] : ~0ull;
+    const uint32_t mhi = (uint32_t)(mine >> 32), mlo = (uint32_t)mine;
+    uint32_t rank = 0;
+#pragma unroll
+    for (int j = 0; j < kOwnList; ++j) {
+      const uint64_t o = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mhi, j) << 32) |
+                         (uint32_t)__builtin_amdgcn_readlane((int)mlo, j);
+      rank += o < mine ? 1u : 0u;   // ids differ, so no two entries are equal
+    }
+    wave_sync();
+    if ((uint32_t)lane < c && rank < kp) {
+      l[rank] = mine;
+      if (rank == kp - 1) {
+        thr[row] = mhi;
+        u[row] = unorder_f32(mhi) * inv_scale;
+      }
+    }
+    wave_sync();
+    return c < kp ? c : kp;
+  };
+
+  const uint32_t n_chunks = (d + KC - 1) / KC;
+  int cur = 0;
+  if (b_begin < b_end) {
+    fetch(b_begin, 0);
+    stage(0);
+  }
+  __syncthreads();
+
+  for (uint64_t t0 = b_begin; t0 < b_end; t0 += BT) {
+    floatx16 acc[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
+    // the extra matrix step's B operand, and the ids of this lane's two columns
+    float ext[2];
+    uint32_t col_id[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const uint64_t ci = t0 + wc * 64 + b * 32 + l32;
+      col_id[b] = (uint32_t)ci;
+      ext[b] = ci < b_end ? (metric == ANN_L2 ? -0.5f * xnorm[ci] : 0.f) : -INFINITY;
+      if (half) ext[b] = 0.f;   // second K slot of the step: 0 x 0
+    }
+    for (uint32_t c = 0; c < n_chunks; ++c) {
+      const bool last_chunk = c + 1 == n_chunks;
+      const uint64_t nt0 = last_chunk ? t0 + BT : t0;
+      const bool more = nt0 < b_end;
+      if (more) fetch(nt0, last_chunk ? 0 : (c + 1) * KC);
+      const float *ap = stage_buf + ((size_t)cur * ROWS + wr * kOwnRows + l32) * P + half * (KC / 2);
+      const float *bp = stage_buf + ((size_t)cur * ROWS + QT + wc * 64 + l32) * P + half * (KC / 2);
+#pragma unroll
+      for (int j = 0; j < KC / 8; ++j) {
+        const float4 a0 = *reinterpret_cast<const float4 *>(ap + 4 * j);
+        const float4 b0 = *reinterpret_cast<const float4 *>(bp + 4 * j);
+        const float4 b1 = *reinterpret_cast<const float4 *>(bp + 32 * P + 4 * j);
+        const float av0[4] = {a0.x, a0.y, a0.z, a0.w};
+        const float bv0[4] = {b0.x, b0.y, b0.z, b0.w}, bv1[4] = {b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0[e], bv0[e], acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0[e], bv1[e], acc[1], 0, 0, 0);
+        }
+      }
+      if (more) stage(cur ^ 1);
+      __syncthreads();
+      cur ^= 1;
+    }
+    {
+      const float one = half ? 0.f : 1.f;
+#pragma unroll
+      for (int b = 0; b < 2; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(one, ext[b], acc[b], 0, 0, 0);
+    }
+
+    // acc[b][i]: row 8*(i/4) + 4*half + i%4 of this wavefront against column col_id[b]
+    int start = 0;   // first element (g, e, b in loop order) not yet taken
+    for (;;) {
+      uint32_t n_st = 0;
+      int next_start = -1;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 u4 = *reinterpret_cast<const float4 *>(u + 8 * g + 4 * half);
+        const float uv[4] = {u4.x, u4.y, u4.z, u4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int b = 0; b < 2; ++b) {
+            const int elem = (g * 4 + e) * 2 + b;
+            const float v = acc[b][4 * g + e];
+            const bool hit = v > uv[e];
+            const uint64_t m = __ballot(hit);
+            if (m != 0 && elem >= start && next_start < 0) {
+              const uint32_t cm = (uint32_t)__popcll(m);
+              if (n_st + cm > (uint32_t)kStageCap) {
+                next_start = elem;   // no room: this element and the later ones wait for the next pass
+              } else {
+                if (hit) {
+                  const uint32_t pos = n_st + (uint32_t)bf_lanes_below(m);
+                  st[pos] = ((uint64_t)order_u32(scale * v) << 32) | col_id[b];
+                  st_row[pos] = (uint8_t)(8 * g + 4 * half + e);
+                }
+                n_st += cm;
+              }
+            }
+          }
+      }
+      if (n_st == 0) break;   // (with nothing staged there was room)
+      wave_sync();
+      // flush: every lane takes one staged hit into its row's list; a list
+      // that is full is cut back to its kp best and the hit is tried again
+      for (uint32_t base = 0; base < n_st; base += kWave) {
+        const uint32_t idx = base + lane;
+        const bool valid = idx < n_st;
+        const uint64_t ent = valid ? st[idx] : ~0ull;
+        const int erow = valid ? st_row[idx] : 0;
+        bool pending = valid && (uint32_t)(ent >> 32) < thr[erow];
+        while (__ballot(pending)) {
+          if (pending) {
+            const uint32_t pos = atomicAdd(&cnt[erow], 1u);
+            if (pos < (uint32_t)kOwnList) {
+              list[(size_t)erow * kOwnList + pos] = ent;
+              pending = false;
+            }
+          }
+          wave_sync();
+          uint64_t todo = __ballot(pending);
+          if (todo == 0) break;
+          while (todo) {
+            const int row = __builtin_amdgcn_readlane(erow, __builtin_ctzll(todo));
+            todo &= ~__ballot(pending && erow == row);
+            const uint32_t c = cut(row, kOwnList);   // the count ran past the list's end: the list is full
+            if (lane == 0) cnt[row] = c;
+          }
+          wave_sync();
+          pending = pending && (uint32_t)(ent >> 32) < thr[erow];
+        }
+      }
+      if (next_start < 0) break;
+      start = next_start;
+    }
+  }
+  // every list down to kp, then to the exact stage
+  wave_sync();
+  for (int row = 0; row < kOwnRows; ++row) {
+    uint32_t c = cnt[row] < (uint32_t)kOwnList ? cnt[row] : (uint32_t)kOwnList;
+    if (c > kp) c = cut(row, c);
+    const uint32_t qi = q0 + wr * kOwnRows + row;
+    if (qi < nq && (uint32_t)lane < kp)
+      cand_out[(((uint64_t)qi * n_slabs + slab) * WC + wc) * kp + lane] =
+          (uint32_t)lane < c ? (uint32_t)list[(size_t)row * kOwnList + lane] : ANN_PAD_ID;
+  }
+}
+
 }  // namespace ann
 
 using namespace ann;
@@ -442,15 +697,22 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   if (d > 2048) return fail(ANN_ECAPACITY, "ann_bruteforce_topk: d = %u exceeds 2048", d);
 
   const uint32_t kp = k + 8;               // candidates kept per (query, slab): k plus a margin for fp32 score error
-  // Tile shape: 128 queries x 128 base rows with a 64-entry buffer per query
-  // while k is small, 64 x 256 with a longer buffer for larger k, and the
-  // 32 x 128 kernel with scalar staging for what is left (d not a multiple of
+  // Tile shape: 128 queries x 128 base rows, with lists owned by single
+  // wavefronts for k up to 16 and a shared 64-entry buffer per query for k up
+  // to 24; 64 x 256 with a longer buffer for larger k; and the 32 x 128 kernel with scalar staging for what is left (d not a multiple of
   // 4, k above 152).
   int shape = 0;
   uint32_t cb = kp + kBT, q_rows = kQT, b_rows = kBT;
   // rows can be read 16 bytes at a time
   const bool vec4 = d % 4 == 0 && (reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(q)) % 16 == 0;
-  if (vec4 && kp + 32 <= 64) {
+  uint32_t lists = 1;   // candidate lists per (query, slab)
+  if (vec4 && kp + 8 <= (uint32_t)kOwnList) {
+    shape = 3;
+    cb = kOwnList;
+    q_rows = 128;
+    b_rows = 128;
+    lists = 2;
+  } else if (vec4 && kp + 32 <= 64) {
     shape = 1;
     cb = 64;
     q_rows = 128;
@@ -468,7 +730,7 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   // grid (256 units), at most 4096 exact re-evaluations per query
   uint32_t slabs = (1024 + q_tiles - 1) / q_tiles;
   if (slabs > tiles) slabs = (uint32_t)tiles;
-  if (slabs * kp > 4096) slabs = 4096 / kp;
+  if (slabs * lists * kp > 4096) slabs = 4096 / (lists * kp);
   if (slabs < 1) slabs = 1;
   uint64_t rows_per_slab = ((tiles + slabs - 1) / slabs) * b_rows;
   slabs = (uint32_t)((n + rows_per_slab - 1) / rows_per_slab);
@@ -477,7 +739,11 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   uint32_t *cand = nullptr;
   size_t smem;
   const void *fn;
-  if (shape == 1) {
+  if (shape == 3) {
+    smem = (size_t)2 * 256 * (32 + 4) * sizeof(float) + 3 * 256 * 4 + (size_t)256 * kOwnList * sizeof(uint64_t) +
+           (size_t)kOwnWaves * kStageCap * (sizeof(uint64_t) + 1);
+    fn = reinterpret_cast<const void *>(bf_own_kernel<32>);
+  } else if (shape == 1) {
     smem = (size_t)2 * 256 * (32 + 4) * sizeof(float) + 128 * 8 + (size_t)128 * cb * sizeof(uint64_t);
     fn = reinterpret_cast<const void *>(bf_block_kernel<2, 2, 32, 1>);
   } else if (shape == 2) {
@@ -490,7 +756,7 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   }
   hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
-  ANN_HIP(hipMalloc((void **)&cand, (size_t)nq * slabs * kp * sizeof(uint32_t)));
+  ANN_HIP(hipMalloc((void **)&cand, (size_t)nq * slabs * lists * kp * sizeof(uint32_t)));
   if (metric == ANN_L2) {
     e = hipMalloc((void **)&xnorm, (size_t)n * sizeof(float));
     if (e != hipSuccess) {
@@ -500,7 +766,9 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
     row_norm_kernel<<<2048, 256, 0, st>>>(x, n, d, xnorm);
   }
   const dim3 grid(q_tiles, slabs);
-  if (shape == 1)
+  if (shape == 3)
+    bf_own_kernel<32><<<grid, 64 * kOwnWaves, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cand);
+  else if (shape == 1)
     bf_block_kernel<2, 2, 32, 1><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
   else if (shape == 2)
     bf_block_kernel<1, 4, 16, 3><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
@@ -509,7 +777,7 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   else
     bf_tile_kernel<false><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
   e = hipGetLastError();
-  ann_status rc = e == hipSuccess ? rerank_device(x, n, d, metric, q, nq, cand, slabs * kp, slabs * kp, k, out_ids,
+  ann_status rc = e == hipSuccess ? rerank_device(x, n, d, metric, q, nq, cand, slabs * lists * kp, slabs * lists * kp, k, out_ids,
                                                   out_dist, st)
                                   : hip_fail(e, "brute-force tile kernel launch");
   hipError_t e2 = hipStreamSynchronize(st);
