@@ -20,6 +20,11 @@ constexpr int kBT = 128;   // base vectors per tile (4 wavefronts x 32)
 constexpr int kKC = 32;    // K chunk staged in LDS
 constexpr int kLd = kKC + 1;  // padded row length (floats): conflict-free column reads
 
+__global__ void fill_u32_kernel(uint32_t *__restrict__ p, uint32_t n, uint32_t v) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
 __global__ void row_norm_kernel(const float *__restrict__ x, uint64_t n, uint32_t d, float *__restrict__ out) {
   const int lane = threadIdx.x % kWave;
   const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
@@ -461,6 +466,7 @@ template <int KC>
 __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X, const float *__restrict__ xnorm,
                                                      uint64_t n, uint32_t d, const float *__restrict__ Q, uint32_t nq,
                                                      uint32_t metric, uint64_t rows_per_slab, uint32_t kp,
+                                                     uint32_t *__restrict__ bound /*[nq]*/,
                                                      uint32_t *__restrict__ cand_out /*[nq][slabs][2][kp]*/) {
   constexpr int WC = 2, QT = 128, BT = 128, ROWS = QT + BT, P = KC + 4, NT = 64 * kOwnWaves;
   constexpr int C4 = KC / 4, RP = NT / C4, NLD = ROWS / RP;
@@ -499,26 +505,40 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
   }
 
   const int s_row = tid / C4, s_col = (tid % C4) * 4;
-  float4 reg[NLD];
-  auto fetch = [&](uint64_t t0, uint32_t k0) {
+  // two sets of staging registers: a chunk is fetched two steps before it is
+  // multiplied (one step does not cover the latency of a row that comes from HBM)
+  float4 reg_a[NLD], reg_b[NLD];
+  uint32_t keep_a = 0, keep_b = 0;   // bit i: reg[i] lies inside the arrays
+  // Loads are unconditional (addresses clamped into the arrays) so that they
+  // are issued back to back; what lies outside is zeroed when it is staged.
+  auto fetch = [&](float4 (&reg)[NLD], uint32_t &keep, uint64_t t0, uint32_t k0) {
     const uint32_t kk = k0 + s_col;
+    const bool k_in = kk < d;
+    const uint32_t kc = k_in ? kk : 0;
+    keep = 0;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int row = s_row + RP * i;   // a pass is all queries or all base rows (QT % RP == 0)
-      reg[i] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (row < QT) {
         const uint32_t qi = q0 + row;
-        if (qi < nq && kk < d) reg[i] = *reinterpret_cast<const float4 *>(Q + (uint64_t)qi * d + kk);
+        const bool in = qi < nq && k_in;
+        reg[i] = *reinterpret_cast<const float4 *>(Q + (uint64_t)(qi < nq ? qi : nq - 1) * d + kc);
+        keep |= in ? 1u << i : 0u;
       } else {
         const uint64_t bi = t0 + (row - QT);
-        if (bi < b_end && kk < d) reg[i] = *reinterpret_cast<const float4 *>(X + bi * d + kk);
+        const bool in = bi < b_end && k_in;
+        reg[i] = *reinterpret_cast<const float4 *>(X + (bi < b_end ? bi : b_end - 1) * d + kc);
+        keep |= in ? 1u << i : 0u;
       }
     }
   };
-  auto stage = [&](int b) {
+  auto stage = [&](const float4 (&reg)[NLD], uint32_t keep, int b) {
 #pragma unroll
-    for (int i = 0; i < NLD; ++i)
-      *reinterpret_cast<float4 *>(stage_buf + ((size_t)b * ROWS + s_row + RP * i) * P + s_col) = reg[i];
+    for (int i = 0; i < NLD; ++i) {
+      const bool in = (keep >> i) & 1u;
+      const float4 v = make_float4(in ? reg[i].x : 0.f, in ? reg[i].y : 0.f, in ? reg[i].z : 0.f, in ? reg[i].w : 0.f);
+      *reinterpret_cast<float4 *>(stage_buf + ((size_t)b * ROWS + s_row + RP * i) * P + s_col) = v;
+    }
   };
   auto wave_sync = [&]() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -544,6 +564,7 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
       if (rank == kp - 1) {
         thr[row] = mhi;
         u[row] = unorder_f32(mhi) * inv_scale;
+        atomicMin(&bound[q0 + wr * kOwnRows + row], mhi);   // (a list is only ever filled for a query of the batch)
       }
     }
     wave_sync();
@@ -552,59 +573,76 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
 
   const uint32_t n_chunks = (d + KC - 1) / KC;
   int cur = 0;
+  // the next (tile, chunk) to fetch; at the top of a step it is two steps ahead
+  // and the other register set holds the step in between
+  uint64_t f_t0 = b_begin;
+  uint32_t f_c = 0;
+  auto advance = [&]() {
+    if (++f_c == n_chunks) {
+      f_c = 0;
+      f_t0 += BT;
+    }
+  };
   if (b_begin < b_end) {
-    fetch(b_begin, 0);
-    stage(0);
+    fetch(reg_a, keep_a, f_t0, 0);
+    advance();
+    stage(reg_a, keep_a, 0);
+    fetch(reg_a, keep_a, f_t0, f_c * KC);   // (past the end: clamped loads that are never staged)
+    advance();
   }
   __syncthreads();
 
-  for (uint64_t t0 = b_begin; t0 < b_end; t0 += BT) {
-    floatx16 acc[2];
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
-    // the extra matrix step's B operand, and the ids of this lane's two columns
-    float ext[2];
-    uint32_t col_id[2];
+  // the tile being multiplied, its chunk, its accumulators
+  uint64_t t0 = b_begin;
+  uint32_t c = 0;
+  floatx16 acc[2];
+  float xn[2];         // norm terms of this lane's two columns (loaded at the start of a tile, used at its end)
+  uint32_t col_id[2];  // their ids
+  uint32_t shared_thr;  // lanes 0..31: the bound other lists have published for this lane's row (same timing)
+  const uint32_t my_q = q0 + wr * kOwnRows + (lane < kOwnRows ? lane : 0);
+  auto begin_tile = [&]() {
+    shared_thr = bound[my_q < nq ? my_q : nq - 1];
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
       const uint64_t ci = t0 + wc * 64 + b * 32 + l32;
       col_id[b] = (uint32_t)ci;
-      ext[b] = ci < b_end ? (metric == ANN_L2 ? -0.5f * xnorm[ci] : 0.f) : -INFINITY;
-      if (half) ext[b] = 0.f;   // second K slot of the step: 0 x 0
+      xn[b] = xnorm[ci < b_end ? ci : b_end - 1];   // (any readable array of n floats when the metric has no norm term)
     }
-    for (uint32_t c = 0; c < n_chunks; ++c) {
-      const bool last_chunk = c + 1 == n_chunks;
-      const uint64_t nt0 = last_chunk ? t0 + BT : t0;
-      const bool more = nt0 < b_end;
-      if (more) fetch(nt0, last_chunk ? 0 : (c + 1) * KC);
-      const float *ap = stage_buf + ((size_t)cur * ROWS + wr * kOwnRows + l32) * P + half * (KC / 2);
-      const float *bp = stage_buf + ((size_t)cur * ROWS + QT + wc * 64 + l32) * P + half * (KC / 2);
-#pragma unroll
-      for (int j = 0; j < KC / 8; ++j) {
-        const float4 a0 = *reinterpret_cast<const float4 *>(ap + 4 * j);
-        const float4 b0 = *reinterpret_cast<const float4 *>(bp + 4 * j);
-        const float4 b1 = *reinterpret_cast<const float4 *>(bp + 32 * P + 4 * j);
-        const float av0[4] = {a0.x, a0.y, a0.z, a0.w};
-        const float bv0[4] = {b0.x, b0.y, b0.z, b0.w}, bv1[4] = {b1.x, b1.y, b1.z, b1.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0[e], bv0[e], acc[0], 0, 0, 0);
-          acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0[e], bv1[e], acc[1], 0, 0, 0);
-        }
-      }
-      if (more) stage(cur ^ 1);
-      __syncthreads();
-      cur ^= 1;
-    }
+  };
+
+  auto finish_tile = [&]() {
     {
+      // the extra matrix step: (1, 0) x (ext, 0) over its two K slots
       const float one = half ? 0.f : 1.f;
 #pragma unroll
-      for (int b = 0; b < 2; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(one, ext[b], acc[b], 0, 0, 0);
+      for (int b = 0; b < 2; ++b) {
+        float ext = col_id[b] < b_end ? (metric == ANN_L2 ? -0.5f * xn[b] : 0.f) : -INFINITY;
+        if (half) ext = 0.f;
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(one, ext, acc[b], 0, 0, 0);
+      }
     }
-
+    // The kp-th best score of any list of a query bounds the query's kp-th best
+    // overall, so the lists of a query (other slabs, the other wavefront) share
+    // the smallest threshold any of them has reached.
+    if (lane < kOwnRows && my_q < nq && shared_thr < thr[lane]) {
+      thr[lane] = shared_thr;
+      u[lane] = unorder_f32(shared_thr) * inv_scale;
+    }
+    wave_sync();
     // acc[b][i]: row 8*(i/4) + 4*half + i%4 of this wavefront against column col_id[b]
+    {
+      bool any = false;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 u4 = *reinterpret_cast<const float4 *>(u + 8 * g + 4 * half);
+        const float uv[4] = {u4.x, u4.y, u4.z, u4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) any |= acc[0][4 * g + e] > uv[e] || acc[1][4 * g + e] > uv[e];
+      }
+      if (__ballot(any) == 0) return;
+    }
     int start = 0;   // first element (g, e, b in loop order) not yet taken
     for (;;) {
       uint32_t n_st = 0;
@@ -660,8 +698,8 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
           while (todo) {
             const int row = __builtin_amdgcn_readlane(erow, __builtin_ctzll(todo));
             todo &= ~__ballot(pending && erow == row);
-            const uint32_t c = cut(row, kOwnList);   // the count ran past the list's end: the list is full
-            if (lane == 0) cnt[row] = c;
+            const uint32_t left = cut(row, kOwnList);   // the count ran past the list's end: the list is full
+            if (lane == 0) cnt[row] = left;
           }
           wave_sync();
           pending = pending && (uint32_t)(ent >> 32) < thr[erow];
@@ -669,6 +707,49 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
       }
       if (next_start < 0) break;
       start = next_start;
+    }
+  };
+
+  // One chunk: fetch the chunk two steps ahead into r_fetch, multiply the
+  // staged one, stage the next from r_stage.  Returns whether a step follows.
+  auto one_step = [&](const float4 (&r_stage)[NLD], uint32_t k_stage, float4 (&r_fetch)[NLD], uint32_t &k_fetch) -> bool {
+    const bool last_chunk = c + 1 == n_chunks;
+    const bool more = !last_chunk || t0 + BT < b_end;
+    fetch(r_fetch, k_fetch, f_t0, f_c * KC);   // (past the end: clamped loads that are never staged)
+    advance();
+    const float *ap = stage_buf + ((size_t)cur * ROWS + wr * kOwnRows + l32) * P + half * (KC / 2);
+    const float *bp = stage_buf + ((size_t)cur * ROWS + QT + wc * 64 + l32) * P + half * (KC / 2);
+#pragma unroll
+    for (int j = 0; j < KC / 8; ++j) {
+      const float4 a0 = *reinterpret_cast<const float4 *>(ap + 4 * j);
+      const float4 b0 = *reinterpret_cast<const float4 *>(bp + 4 * j);
+      const float4 b1 = *reinterpret_cast<const float4 *>(bp + 32 * P + 4 * j);
+      const float av0[4] = {a0.x, a0.y, a0.z, a0.w};
+      const float bv0[4] = {b0.x, b0.y, b0.z, b0.w}, bv1[4] = {b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0[e], bv0[e], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0[e], bv1[e], acc[1], 0, 0, 0);
+      }
+    }
+    if (more) stage(r_stage, k_stage, cur ^ 1);
+    __syncthreads();
+    cur ^= 1;
+    if (last_chunk) {
+      finish_tile();
+      t0 += BT;
+      c = 0;
+      if (more) begin_tile();
+    } else {
+      ++c;
+    }
+    return more;
+  };
+  if (b_begin < b_end) {
+    begin_tile();
+    for (;;) {
+      if (!one_step(reg_a, keep_a, reg_b, keep_b)) break;
+      if (!one_step(reg_b, keep_b, reg_a, keep_a)) break;
     }
   }
   // every list down to kp, then to the exact stage
@@ -756,7 +837,11 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   }
   hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
-  ANN_HIP(hipMalloc((void **)&cand, (size_t)nq * slabs * lists * kp * sizeof(uint32_t)));
+  // candidates, then one shared bound per query (own-list kernel)
+  const size_t n_cand_words = (size_t)nq * slabs * lists * kp;
+  ANN_HIP(hipMalloc((void **)&cand, (n_cand_words + nq) * sizeof(uint32_t)));
+  uint32_t *bound = cand + n_cand_words;
+  if (shape == 3) fill_u32_kernel<<<(nq + 255) / 256, 256, 0, st>>>(bound, nq, 0xFF800000u);   // +inf in score order
   if (metric == ANN_L2) {
     e = hipMalloc((void **)&xnorm, (size_t)n * sizeof(float));
     if (e != hipSuccess) {
@@ -767,7 +852,8 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   }
   const dim3 grid(q_tiles, slabs);
   if (shape == 3)
-    bf_own_kernel<32><<<grid, 64 * kOwnWaves, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cand);
+    bf_own_kernel<32><<<grid, 64 * kOwnWaves, smem, st>>>(x, metric == ANN_L2 ? xnorm : x, n, d, q, nq, metric, rows_per_slab, kp,
+                                                          bound, cand);
   else if (shape == 1)
     bf_block_kernel<2, 2, 32, 1><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
   else if (shape == 2)
