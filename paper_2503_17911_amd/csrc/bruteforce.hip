@@ -447,14 +447,13 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
 // products are 1 x (-|x|^2 / 2) (L2; 0 for inner product; -inf for columns past
 // the end), so that score = scale * acc with scale = -2 / -1, and "score below
 // the row's threshold" is one compare, acc > u[row] with u = thr / scale.
-// Hits are rare once the thresholds have settled.  A pass over the
-// accumulators writes the hits to a staging list in LDS (in element order, at
-// most kStageCap per pass); the flush takes them, one per lane, into their
-// rows' lists (LDS atomic for the slot); a list found full is cut back to its
-// kp best (rank counting over lanes), which lowers the row's threshold, and the
-// hit is tried again.
+// Hits are rare once the thresholds have settled: every lane collects a bit
+// mask of its hits and the wavefront takes them one per lane and round into
+// their rows' lists (LDS atomic for the slot); a list found full is cut back to
+// its kp best (rank counting over lanes), which lowers the row's threshold, and
+// the hit is tried again.  The lists of one query (its slabs, its two
+// wavefronts) publish their thresholds in global memory and use the smallest.
 constexpr int kOwnList = 32;     // entries per (row, wavefront) list
-constexpr int kStageCap = 128;   // staged hits per wavefront and pass
 constexpr int kOwnWaves = 8, kOwnRows = 32;   // wavefronts per workgroup, query rows per wavefront
 
 // number of set bits of mask below this lane's
@@ -478,8 +477,6 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
   uint32_t *thr_all = reinterpret_cast<uint32_t *>(u_all + NR);               // [NR]  ordered score an entry must be below
   uint32_t *cnt_all = thr_all + NR;                                           // [NR]
   uint64_t *list_all = reinterpret_cast<uint64_t *>(cnt_all + NR);            // [NR][kOwnList]
-  uint64_t *st_all = list_all + (size_t)NR * kOwnList;                        // [kOwnWaves][kStageCap]
-  uint8_t *st_row_all = reinterpret_cast<uint8_t *>(st_all + kOwnWaves * kStageCap);
 
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int wr = wave / WC, wc = wave % WC, half = lane / 32, l32 = lane % 32;
@@ -495,8 +492,6 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
   uint32_t *thr = thr_all + wave * kOwnRows;
   uint32_t *cnt = cnt_all + wave * kOwnRows;
   uint64_t *list = list_all + (size_t)wave * kOwnRows * kOwnList;
-  uint64_t *st = st_all + (size_t)wave * kStageCap;
-  uint8_t *st_row = st_row_all + (size_t)wave * kStageCap;
   if (lane < kOwnRows) {
     const bool live = q0 + wr * kOwnRows + lane < nq;
     u[lane] = live ? -INFINITY : INFINITY;   // rows past the batch never take anything
@@ -631,82 +626,54 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
       u[lane] = unorder_f32(shared_thr) * inv_scale;
     }
     wave_sync();
-    // acc[b][i]: row 8*(i/4) + 4*half + i%4 of this wavefront against column col_id[b]
-    {
-      bool any = false;
+    // acc[b][i]: row 8*(i/4) + 4*half + i%4 of this wavefront against column col_id[b].
+    // Bit 2*i + b of hits: that score is below its row's threshold.
+    uint32_t hits = 0;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 u4 = *reinterpret_cast<const float4 *>(u + 8 * g + 4 * half);
-        const float uv[4] = {u4.x, u4.y, u4.z, u4.w};
+    for (int g = 0; g < 4; ++g) {
+      const float4 u4 = *reinterpret_cast<const float4 *>(u + 8 * g + 4 * half);
+      const float uv[4] = {u4.x, u4.y, u4.z, u4.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) any |= acc[0][4 * g + e] > uv[e] || acc[1][4 * g + e] > uv[e];
-      }
-      if (__ballot(any) == 0) return;
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) hits |= acc[b][4 * g + e] > uv[e] ? 1u << (2 * (4 * g + e) + b) : 0u;
     }
-    int start = 0;   // first element (g, e, b in loop order) not yet taken
-    for (;;) {
-      uint32_t n_st = 0;
-      int next_start = -1;
+    // One hit per lane and round: into the row's list (LDS atomic for the
+    // slot); a list found full is cut back to its kp best, which lowers the
+    // row's threshold, and the hit is tried again.
+    while (__ballot(hits != 0)) {
+      const bool active = hits != 0;
+      const int bit = active ? __builtin_ctz(hits) : 0;
+      hits &= hits - 1;
+      float v = 0.f;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 u4 = *reinterpret_cast<const float4 *>(u + 8 * g + 4 * half);
-        const float uv[4] = {u4.x, u4.y, u4.z, u4.w};
+      for (int i = 0; i < 16; ++i)
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-#pragma unroll
-          for (int b = 0; b < 2; ++b) {
-            const int elem = (g * 4 + e) * 2 + b;
-            const float v = acc[b][4 * g + e];
-            const bool hit = v > uv[e];
-            const uint64_t m = __ballot(hit);
-            if (m != 0 && elem >= start && next_start < 0) {
-              const uint32_t cm = (uint32_t)__popcll(m);
-              if (n_st + cm > (uint32_t)kStageCap) {
-                next_start = elem;   // no room: this element and the later ones wait for the next pass
-              } else {
-                if (hit) {
-                  const uint32_t pos = n_st + (uint32_t)bf_lanes_below(m);
-                  st[pos] = ((uint64_t)order_u32(scale * v) << 32) | col_id[b];
-                  st_row[pos] = (uint8_t)(8 * g + 4 * half + e);
-                }
-                n_st += cm;
-              }
-            }
+        for (int b = 0; b < 2; ++b) v = bit == 2 * i + b ? acc[b][i] : v;
+      const int i_el = bit >> 1;
+      const int erow = 8 * (i_el >> 2) + 4 * half + (i_el & 3);
+      const uint64_t ent = ((uint64_t)order_u32(scale * v) << 32) | ((bit & 1) ? col_id[1] : col_id[0]);
+      bool pending = active && (uint32_t)(ent >> 32) < thr[erow];
+      while (__ballot(pending)) {
+        if (pending) {
+          const uint32_t pos = atomicAdd(&cnt[erow], 1u);
+          if (pos < (uint32_t)kOwnList) {
+            list[(size_t)erow * kOwnList + pos] = ent;
+            pending = false;
           }
-      }
-      if (n_st == 0) break;   // (with nothing staged there was room)
-      wave_sync();
-      // flush: every lane takes one staged hit into its row's list; a list
-      // that is full is cut back to its kp best and the hit is tried again
-      for (uint32_t base = 0; base < n_st; base += kWave) {
-        const uint32_t idx = base + lane;
-        const bool valid = idx < n_st;
-        const uint64_t ent = valid ? st[idx] : ~0ull;
-        const int erow = valid ? st_row[idx] : 0;
-        bool pending = valid && (uint32_t)(ent >> 32) < thr[erow];
-        while (__ballot(pending)) {
-          if (pending) {
-            const uint32_t pos = atomicAdd(&cnt[erow], 1u);
-            if (pos < (uint32_t)kOwnList) {
-              list[(size_t)erow * kOwnList + pos] = ent;
-              pending = false;
-            }
-          }
-          wave_sync();
-          uint64_t todo = __ballot(pending);
-          if (todo == 0) break;
-          while (todo) {
-            const int row = __builtin_amdgcn_readlane(erow, __builtin_ctzll(todo));
-            todo &= ~__ballot(pending && erow == row);
-            const uint32_t left = cut(row, kOwnList);   // the count ran past the list's end: the list is full
-            if (lane == 0) cnt[row] = left;
-          }
-          wave_sync();
-          pending = pending && (uint32_t)(ent >> 32) < thr[erow];
         }
+        wave_sync();
+        uint64_t todo = __ballot(pending);
+        if (todo == 0) break;
+        while (todo) {
+          const int row = __builtin_amdgcn_readlane(erow, __builtin_ctzll(todo));
+          todo &= ~__ballot(pending && erow == row);
+          const uint32_t left = cut(row, kOwnList);   // the count ran past the list's end: the list is full
+          if (lane == 0) cnt[row] = left;
+        }
+        wave_sync();
+        pending = pending && (uint32_t)(ent >> 32) < thr[erow];
       }
-      if (next_start < 0) break;
-      start = next_start;
     }
   };
 
@@ -821,8 +788,7 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   size_t smem;
   const void *fn;
   if (shape == 3) {
-    smem = (size_t)2 * 256 * (32 + 4) * sizeof(float) + 3 * 256 * 4 + (size_t)256 * kOwnList * sizeof(uint64_t) +
-           (size_t)kOwnWaves * kStageCap * (sizeof(uint64_t) + 1);
+    smem = (size_t)2 * 256 * (32 + 4) * sizeof(float) + 3 * 256 * 4 + (size_t)256 * kOwnList * sizeof(uint64_t);
     fn = reinterpret_cast<const void *>(bf_own_kernel<32>);
   } else if (shape == 1) {
     smem = (size_t)2 * 256 * (32 + 4) * sizeof(float) + 128 * 8 + (size_t)128 * cb * sizeof(uint64_t);
