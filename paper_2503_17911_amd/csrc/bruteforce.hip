@@ -774,9 +774,29 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   if (shape == 0 && cb > 8 * kWave) return fail(ANN_ECAPACITY, "ann_bruteforce_topk: internal buffer too small for k = %u", k);
   const uint32_t q_tiles = (nq + q_rows - 1) / q_rows;
   const uint64_t tiles = (n + b_rows - 1) / b_rows;
-  // slabs of base rows: about four workgroups per compute unit over the whole
-  // grid (256 units), at most 4096 exact re-evaluations per query
-  uint32_t slabs = (1024 + q_tiles - 1) / q_tiles;
+  // Slabs of base rows: the grid (query tiles x slabs) should fill the chip a
+  // whole number of times - workgroups take equal time, so three left over for
+  // a fifth turn cost as much as a full one.  Among 3 to 8 turns take the one
+  // whose last turn is fullest (one workgroup per compute unit with the large
+  // tiles' LDS, two with the small tile).
+  int n_cu = 256;
+  {
+    int dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (n_cu <= 0) n_cu = 256;
+  }
+  const uint32_t slots = (uint32_t)n_cu * (shape == 0 ? 2u : 1u);
+  uint32_t slabs = 1;
+  double best_fill = 0.0;
+  for (uint32_t turns = 3; turns <= 8; ++turns) {
+    const uint32_t s_ = slots * turns / q_tiles;
+    if (s_ == 0) continue;
+    const double fill = (double)q_tiles * s_ / ((double)slots * turns);
+    if (fill > best_fill + 0.01) {
+      best_fill = fill;
+      slabs = s_;
+    }
+  }
   if (slabs > tiles) slabs = (uint32_t)tiles;
   if (slabs * lists * kp > 4096) slabs = 4096 / (lists * kp);
   if (slabs < 1) slabs = 1;
