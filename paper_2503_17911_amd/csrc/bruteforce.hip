@@ -4,6 +4,14 @@
 // k + margin candidates per (query, base slab); the candidates of all slabs
 // are then re-evaluated directly in fp64 (rerank kernel) and sorted by
 // (distance, id), so the decomposed fp32 scores only ever select candidates.
+//
+// Three tile kernels, chosen by ann_bruteforce_topk: bf_own_kernel (k <= 16,
+// d % 4 == 0: 128 x 128 tiles, eight wavefronts, per-wavefront candidate
+// lists), bf_block_kernel (k <= 152: 128 x 128 or 64 x 256 tiles, four
+// wavefronts, one buffer per query) and bf_tile_kernel (anything: 32 x 128
+// tiles, scalar staging).  In the first two the slabs of a query publish their
+// kp-th best score in global memory and every slab filters with the smallest:
+// the kp-th best of a part bounds the kp-th best of the whole.
 #include "ann_internal.hpp"
 #include "device_utils.hpp"
 
@@ -232,6 +240,7 @@ template <int WR, int WC, int KC, int EPL>
 __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__ X, const float *__restrict__ xnorm,
                                                        uint64_t n, uint32_t d, const float *__restrict__ Q, uint32_t nq,
                                                        uint32_t metric, uint64_t rows_per_slab, uint32_t kp, uint32_t cb,
+                                                       uint32_t *__restrict__ bound /*[nq]*/,
                                                        uint32_t *__restrict__ cand_out /*[nq][slabs][kp]*/) {
   constexpr int QT = 64 * WR, BT = 64 * WC, ROWS = QT + BT, P = KC + 4;
   constexpr int C4 = KC / 4;            // float4 per staged row
@@ -308,7 +317,11 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
       const uint32_t i = lane + u * kWave;
       if (i < c && rank[u] < kp) {
         list[rank[u]] = mine[u];
-        if (rank[u] == kp - 1) thr[row] = unorder_f32((uint32_t)(mine[u] >> 32));
+        if (rank[u] == kp - 1) {
+          thr[row] = unorder_f32((uint32_t)(mine[u] >> 32));
+          // the kp-th best of one slab bounds the kp-th best overall: the slabs of a query share the smallest
+          if (q0 + row < nq) atomicMin(&bound[q0 + row], (uint32_t)(mine[u] >> 32));
+        }
       }
     }
     if (lane == 0) cnt[row] = kp;
@@ -347,6 +360,8 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
       col_id[b] = t0 + wc * 64 + b * 32 + l32;
       xn[b] = col_id[b] < b_end ? (metric == ANN_L2 ? xnorm[col_id[b]] : 0.f) : INFINITY;
     }
+    // what the other slabs of this thread's query have published (used after the matrix work)
+    const uint32_t shared_thr = bound[q0 + tid < nq ? q0 + tid : nq - 1];
     for (uint32_t c = 0; c < n_chunks; ++c) {
       const bool last_chunk = c + 1 == n_chunks;
       const uint64_t nt0 = last_chunk ? t0 + BT : t0;
@@ -378,6 +393,8 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
     // acc[a][b][i] is query row wr*64 + a*32 + 8*(i/4) + 4*half + i%4 against
     // base column col_id[b].  Bit b*16 + i of pend[a]: that score is below its
     // row's threshold and not yet in the buffer.
+    if (tid < QT && q0 + tid < nq && unorder_f32(shared_thr) < thr[tid]) thr[tid] = unorder_f32(shared_thr);
+    __syncthreads();
     uint32_t pend[2] = {0u, 0u};
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -506,23 +523,30 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
   uint32_t keep_a = 0, keep_b = 0;   // bit i: reg[i] lies inside the arrays
   // Loads are unconditional (addresses clamped into the arrays) so that they
   // are issued back to back; what lies outside is zeroed when it is staged.
+  // An address is a base common to the workgroup (the tile's first row) plus
+  // a 32-bit offset of the thread (row inside the tile, column).
+  const float *q_base = Q + (uint64_t)q0 * d;
+  const uint32_t q_last = nq - 1 - q0;   // last row of the batch, counted from the tile's first
   auto fetch = [&](float4 (&reg)[NLD], uint32_t &keep, uint64_t t0, uint32_t k0) {
     const uint32_t kk = k0 + s_col;
     const bool k_in = kk < d;
     const uint32_t kc = k_in ? kk : 0;
+    const uint64_t t0c = t0 < b_end ? t0 : b_end - 1;
+    const float *x_base = X + t0c * d;
+    const uint64_t left = b_end - 1 - t0c;
+    const uint32_t x_last = left < (uint64_t)BT ? (uint32_t)left : (uint32_t)BT;   // last row of the slab, counted from the tile's first
     keep = 0;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const int row = s_row + RP * i;   // a pass is all queries or all base rows (QT % RP == 0)
-      if (row < QT) {
-        const uint32_t qi = q0 + row;
-        const bool in = qi < nq && k_in;
-        reg[i] = *reinterpret_cast<const float4 *>(Q + (uint64_t)(qi < nq ? qi : nq - 1) * d + kc);
+      const uint32_t row = (uint32_t)(s_row + RP * i);   // a pass is all queries or all base rows (QT % RP == 0)
+      if (row < (uint32_t)QT) {
+        const bool in = row <= q_last && k_in;
+        reg[i] = *reinterpret_cast<const float4 *>(q_base + ((row < q_last ? row : q_last) * d + kc));
         keep |= in ? 1u << i : 0u;
       } else {
-        const uint64_t bi = t0 + (row - QT);
-        const bool in = bi < b_end && k_in;
-        reg[i] = *reinterpret_cast<const float4 *>(X + (bi < b_end ? bi : b_end - 1) * d + kc);
+        const uint32_t r = row - QT;
+        const bool in = t0 < b_end && r <= x_last && k_in;
+        reg[i] = *reinterpret_cast<const float4 *>(x_base + ((r < x_last ? r : x_last) * d + kc));
         keep |= in ? 1u << i : 0u;
       }
     }
@@ -823,11 +847,11 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   }
   hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
-  // candidates, then one shared bound per query (own-list kernel)
+  // candidates, then one shared bound per query (the large-tile kernels)
   const size_t n_cand_words = (size_t)nq * slabs * lists * kp;
   ANN_HIP(hipMalloc((void **)&cand, (n_cand_words + nq) * sizeof(uint32_t)));
   uint32_t *bound = cand + n_cand_words;
-  if (shape == 3) fill_u32_kernel<<<(nq + 255) / 256, 256, 0, st>>>(bound, nq, 0xFF800000u);   // +inf in score order
+  if (shape != 0) fill_u32_kernel<<<(nq + 255) / 256, 256, 0, st>>>(bound, nq, 0xFF800000u);   // +inf in score order
   if (metric == ANN_L2) {
     e = hipMalloc((void **)&xnorm, (size_t)n * sizeof(float));
     if (e != hipSuccess) {
@@ -841,9 +865,9 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
     bf_own_kernel<32><<<grid, 64 * kOwnWaves, smem, st>>>(x, metric == ANN_L2 ? xnorm : x, n, d, q, nq, metric, rows_per_slab, kp,
                                                           bound, cand);
   else if (shape == 1)
-    bf_block_kernel<2, 2, 32, 1><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
+    bf_block_kernel<2, 2, 32, 1><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, bound, cand);
   else if (shape == 2)
-    bf_block_kernel<1, 4, 16, 3><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
+    bf_block_kernel<1, 4, 16, 3><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, bound, cand);
   else if (vec4)
     bf_tile_kernel<true><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
   else
