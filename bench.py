@@ -83,6 +83,9 @@ def main():
     ap.add_argument("--coverage", type=float, default=1.0,
                     help="codebook range: 1 = per-dimension min/max, below 1 = truncated (symmetric order statistics)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--bruteforce", action="store_true",
+                    help="time the exact brute-force search alone (the ground-truth stage) on the workload's vectors "
+                         "and queries, k = 10 on the whole batch and k = 100 on a fifth of it, print one JSON line, exit")
     ap.add_argument("--print-kernel-hash", action="store_true", help="print the hash MEASURED_TRAFFIC is keyed by, and exit")
     args = ap.parse_args()
     if args.print_kernel_hash:
@@ -108,6 +111,9 @@ def main():
     metric = ann.L2 if w.metric == "l2" else ann.IP
     bits = w.bits[0]
     k, n_rerank = w.k, w.rerank_mult * w.k
+    if args.bruteforce:
+        bruteforce_only(w, metric)
+        return
 
     t0 = time.time()
     X = inputs.base_vectors(w)
@@ -576,6 +582,32 @@ def main():
 
     ann.ann_free_index(index)
     print(json.dumps(result), flush=True)
+
+
+def bruteforce_only(w, metric):
+    """Whole-call time of ann_bruteforce_topk (best of five, host clock) for two values of k."""
+    import torch
+
+    import inputs
+    import paper_2503_17911_amd as ann
+    dev = "cuda:0"
+    st = torch.cuda.current_stream().cuda_stream
+    xd = torch.from_numpy(inputs.base_vectors(w)).to(dev)
+    qd = torch.from_numpy(inputs.queries(w)).to(dev)
+    out = {"workload": f"{w.name}: N={w.n} d={w.d} {w.metric}", "peak_TFLOPs": 157.3, "runs": []}
+    for k, nq in ((10, w.nq), (100, max(1, w.nq // 5))):
+        ids = torch.empty((nq, k), dtype=torch.int32, device=dev)
+        dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
+        best = float("inf")
+        for _ in range(6):      # the first call is a warm-up
+            t0 = time.perf_counter()
+            ann.ann_bruteforce_topk(xd, w.n, w.d, qd, nq, k, metric, ids, dist, st)
+            torch.cuda.synchronize()
+            best = min(best, time.perf_counter() - t0) if _ else best
+        tf = 2.0 * w.n * nq * w.d / best / 1e12
+        log(f"[bench] brute force k={k}: {nq} x {w.n} x {w.d} in {best * 1e3:.1f} ms = {tf:.1f} TFLOP/s")
+        out["runs"].append({"k": k, "nq": nq, "ms": round(best * 1e3, 2), "TFLOPs": round(tf, 1), "frac": round(tf / 157.3, 3)})
+    print(json.dumps(out), flush=True)
 
 
 def cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, coverage=1.0):
