@@ -563,7 +563,7 @@ def main():
                    "renumbered_nodes_variant": relabel,
                    "two_batches_in_flight": pipelined,
                    "sweep": sweep},
-        "ground_truth": {"kernel": "ann_bruteforce_topk (fp32 MFMA tiles + exact re-evaluation)", "bound": "mfma",
+        "ground_truth": {"kernel": "ann_bruteforce_topk (fp32 MFMA 128x128 tiles, shared top-k bounds, exact re-evaluation)", "bound": "mfma",
                          "seconds": round(bf_s, 4), "achieved": round(2 * n * nq * d / bf_s / 1e12, 1),
                          "peak": 157.3, "unit": "TFLOP/s", "frac": round(2 * n * nq * d / bf_s / 1e12 / 157.3, 3),
                          "note": "set-up, outside the timed region; wall time of the whole call"},
