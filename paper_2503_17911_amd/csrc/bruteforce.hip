@@ -749,9 +749,12 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
     uint32_t c = cnt[row] < (uint32_t)kOwnList ? cnt[row] : (uint32_t)kOwnList;
     if (c > kp) c = cut(row, c);
     const uint32_t qi = q0 + wr * kOwnRows + row;
-    if (qi < nq && (uint32_t)lane < kp)
-      cand_out[(((uint64_t)qi * n_slabs + slab) * WC + wc) * kp + lane] =
-          (uint32_t)lane < c ? (uint32_t)list[(size_t)row * kOwnList + lane] : ANN_PAD_ID;
+    if (qi < nq && (uint32_t)lane < kp) {
+      // an entry above what the query's lists have agreed on by now is not among its kp best
+      const uint64_t ent = list[(size_t)row * kOwnList + lane];
+      const bool keep = (uint32_t)lane < c && (uint32_t)(ent >> 32) <= bound[qi];
+      cand_out[(((uint64_t)qi * n_slabs + slab) * WC + wc) * kp + lane] = keep ? (uint32_t)ent : ANN_PAD_ID;
+    }
   }
 }
 

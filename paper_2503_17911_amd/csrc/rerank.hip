@@ -48,6 +48,7 @@ __global__ __launch_bounds__(64) void rerank_kernel(const float *__restrict__ X,
   for (uint32_t j = lane; j < d; j += kWave) qs[j] = Q[(uint64_t)qi * d + j];
   __syncthreads();
   const uint32_t *cand = cand_ids + (uint64_t)qi * cand_stride;
+  uint32_t n_valid = 0;   // candidates that name a node: their entries are kept in order at the front of the list
   for (uint32_t base = 0; base < n_cand; base += G) {
     const uint32_t ci = base + grp;
     uint32_t v = ci < n_cand ? cand[ci] : kNone;
@@ -85,21 +86,29 @@ __global__ __launch_bounds__(64) void rerank_kernel(const float *__restrict__ X,
       }
     }
     acc = group_sum_f64<LPR>(acc);
-    if (chunk == 0 && ci < n_cand) {
+    const bool have = chunk == 0 && v != kNone;
+    const uint64_t hm = __ballot(have);
+    if (have) {
       float dist = (float)(metric == ANN_L2 ? acc : -acc);
       uint32_t b = __float_as_uint(dist);
       if ((b & 0x7FFFFFFFu) == 0) dist = 0.0f;
-      list[ci] = v == kNone ? ~0ull : pack_vi(order_u32(dist), v);
+      const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(hm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hm, 0u));
+      list[n_valid + below] = pack_vi(order_u32(dist), v);
     }
+    n_valid += (uint32_t)__popcll(hm);
   }
   __syncthreads();
-  rank_all(list, n_cand, lane, [&](uint32_t rank, uint32_t, uint64_t e) {
+  // only the entries that name a node are ranked (padding sorts last anyway)
+  rank_all(list, n_valid, lane, [&](uint32_t rank, uint32_t, uint64_t e) {
     if (rank < k) {
-      const bool none = e == ~0ull;
-      out_ids[(uint64_t)qi * k + rank] = none ? kNone : (uint32_t)e;
-      out_dist[(uint64_t)qi * k + rank] = none ? INFINITY : unorder_f32((uint32_t)(e >> 32));
+      out_ids[(uint64_t)qi * k + rank] = (uint32_t)e;
+      out_dist[(uint64_t)qi * k + rank] = unorder_f32((uint32_t)(e >> 32));
     }
   });
+  for (uint32_t r = n_valid + lane; r < k; r += kWave) {
+    out_ids[(uint64_t)qi * k + r] = kNone;
+    out_dist[(uint64_t)qi * k + r] = INFINITY;
+  }
 }
 
 // ------------------------------------------------------------------ rescore
