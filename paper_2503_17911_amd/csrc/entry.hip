@@ -81,6 +81,150 @@ __global__ __launch_bounds__(64) void entry_scan_kernel(const uint8_t *__restric
   }
 }
 
+// The same scan for the common case (8-bit codes, one entry per query, d <=
+// 256) as a dense contraction on the matrix cores, with the query folding in
+// front of it: a workgroup of four wavefronts takes 32 queries, folds them
+// (the arithmetic of query_prep_kernel, step for step, so the folded queries
+// it leaves in the workspace are the same bytes), and multiplies them against
+// the pivot table with v_mfma_i32_32x32x16_i8 (integer, hence exact: the keys
+// and the choice are those of entry_scan_kernel).  Wavefront w takes the pivot
+// blocks w, w + 4, ...; every lane keeps the best pivot of its column for its
+// 16 rows; the columns are reduced by lane exchanges, the wavefronts in LDS.
+typedef int intx16 __attribute__((ext_vector_type(16)));
+constexpr int kFsQueries = 32, kFsThreads = 256, kFsMaxD = 256;
+
+__global__ __launch_bounds__(kFsThreads) void fold_scan_kernel(
+    const float *__restrict__ q, uint32_t nq, uint32_t d, const float *__restrict__ lo, const float *__restrict__ delta,
+    uint8_t *__restrict__ tq, uint32_t tq_stride, float *__restrict__ s_ws, float *__restrict__ qlo_ws,
+    int32_t *__restrict__ sum_t_ws, const uint8_t *__restrict__ pcodes, const float *__restrict__ pnorm,
+    const uint32_t *__restrict__ pids, uint32_t n_pivots, uint32_t row_stride, uint32_t metric,
+    uint32_t *__restrict__ out) {
+  extern __shared__ double smem_d[];
+  const uint32_t pp = d + 1;                       // row pitch of prod (doubles): the serial sums of 32 lanes hit 32 banks
+  const uint32_t tp = row_stride + 8;              // row pitch of tql (bytes)
+  double *prod = smem_d;                                             // [32][pp]
+  uint64_t *red = reinterpret_cast<uint64_t *>(prod + kFsQueries * pp);  // [4][32]
+  float *s_l = reinterpret_cast<float *>(red + 4 * kFsQueries);      // [32]
+  float *qlo_l = s_l + kFsQueries;                                   // [32]
+  int *bias_l = reinterpret_cast<int *>(qlo_l + kFsQueries);         // [32]
+  uint8_t *tql = reinterpret_cast<uint8_t *>(bias_l + kFsQueries);   // [32][tp], 8-byte aligned rows
+
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const uint32_t q0 = blockIdx.x * kFsQueries;
+
+  // ---- folding: eight threads per query, dimension j of thread part p: j % 8 == p
+  {
+    const int qr = tid / 8, part = tid % 8;
+    const uint32_t qi = q0 + qr < nq ? q0 + qr : nq - 1;
+    const float *qrow = q + (uint64_t)qi * d;
+    float amax = 0.0f;
+    for (uint32_t j = part; j < d; j += 8) amax = fmaxf(amax, fabsf(__fmul_rn(delta[j], qrow[j])));
+#pragma unroll
+    for (int m = 1; m < 8; m <<= 1) amax = fmaxf(amax, __int_as_float(xor_lane_i32(__float_as_int(amax), m)));
+    float s = 1.0f, r = 0.0f;
+    if (amax > 0.0f) {
+      s = __fdiv_rn(amax, 127.0f);
+      r = __fdiv_rn(127.0f, amax);
+    }
+    int sum = 0;
+    for (uint32_t j = part; j < row_stride; j += 8) {
+      int ti = 0;
+      if (j < d) {
+        const float a = __fmul_rn(delta[j], qrow[j]);
+        ti = __float2int_rn(__fmul_rn(a, r));  // round half to even
+        ti = ti > 127 ? 127 : (ti < -127 ? -127 : ti);
+        prod[qr * pp + j] = (double)qrow[j] * (double)lo[j];
+      }
+      tql[qr * tp + j] = (uint8_t)(int8_t)ti;
+      sum += ti;
+    }
+#pragma unroll
+    for (int m = 1; m < 8; m <<= 1) sum += xor_lane_i32(sum, m);
+    if (part == 0) {
+      s_l[qr] = s;
+      bias_l[qr] = 128 * sum;
+      if (q0 + qr < nq) {
+        s_ws[q0 + qr] = s;
+        sum_t_ws[q0 + qr] = sum;
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < kFsQueries) {
+    // every product of two floats is exact in fp64; added in dimension order, which fixes the rounding
+    double acc = 0.0;
+    for (uint32_t j = 0; j < d; ++j) acc += prod[tid * pp + j];
+    const float qlo = (float)acc;
+    qlo_l[tid] = qlo;
+    if (q0 + tid < nq) qlo_ws[q0 + tid] = qlo;
+  }
+  // the folded queries in the layout the search kernels load (8-bit: dimension order, zero-padded)
+  for (uint32_t e = tid; e < kFsQueries * (tq_stride / 8); e += kFsThreads) {
+    const uint32_t qr = e / (tq_stride / 8), c8 = e % (tq_stride / 8);
+    if (q0 + qr < nq) {
+      const uint64_t v = c8 * 8 < row_stride ? *reinterpret_cast<const uint64_t *>(tql + qr * tp + c8 * 8) : 0ull;
+      *reinterpret_cast<uint64_t *>(tq + (uint64_t)(q0 + qr) * tq_stride + c8 * 8) = v;
+    }
+  }
+  __syncthreads();
+
+  // ---- scan.  acc[i] is query row 8*(i/4) + 4*half + i%4 against the pivot of column lane % 32.
+  const int half = lane / 32, l32 = lane % 32;
+  float s_r[16], qlo_r[16];
+  int bias_r[16];
+  uint64_t best[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int row = 8 * (i / 4) + 4 * half + (i % 4);
+    s_r[i] = s_l[row];
+    qlo_r[i] = qlo_l[row];
+    bias_r[i] = bias_l[row];
+    best[i] = ~0ull;
+  }
+  const uint32_t steps = row_stride / 16;
+  const uint32_t p_blocks = (n_pivots + 31) / 32;
+  for (uint32_t pb = wave; pb < p_blocks; pb += 4) {
+    const uint32_t pi = pb * 32 + l32;
+    const uint32_t pc = pi < n_pivots ? pi : n_pivots - 1;
+    const uint8_t *prow = pcodes + (uint64_t)pc * row_stride + 8 * half;
+    const uint8_t *arow = tql + l32 * tp + 8 * half;
+    intx16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0;
+    for (uint32_t st = 0; st < steps; ++st) {
+      const long a = *reinterpret_cast<const long *>(arow + 16 * st);
+      const long b = *reinterpret_cast<const long *>(prow + 16 * st);
+      acc = __builtin_amdgcn_mfma_i32_32x32x16_i8(a, b, acc, 0, 0, 0);
+    }
+    const float norm = pnorm ? pnorm[pc] : 0.0f;
+    const uint32_t id = pids[pc];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float key = key_from_idot(metric, s_r[i], qlo_r[i], acc[i] + bias_r[i], norm);
+      const uint64_t c = pi < n_pivots ? pack_ki(order_u32(key), id) : ~0ull;
+      best[i] = c < best[i] ? c : best[i];
+    }
+  }
+  // the best over the 32 columns of a half, then over the wavefronts
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    uint64_t m = best[i];
+#pragma unroll
+    for (int x = 1; x < 32; x <<= 1) {
+      const uint64_t o = pack_ki((uint32_t)xor_lane_i32((int)(uint32_t)(m >> 32), x), (uint32_t)xor_lane_i32((int)(uint32_t)m, x));
+      m = o < m ? o : m;
+    }
+    if (l32 == 0) red[wave * kFsQueries + 8 * (i / 4) + 4 * half + (i % 4)] = m;
+  }
+  __syncthreads();
+  if (tid < kFsQueries && q0 + tid < nq) {
+    uint64_t m = red[tid];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) m = red[w * kFsQueries + tid] < m ? red[w * kFsQueries + tid] : m;
+    out[q0 + tid] = m == ~0ull ? ANN_PAD_ID : (uint32_t)m;
+  }
+}
+
 __global__ void gather_pivots_kernel(const uint8_t *__restrict__ codes, const float *__restrict__ norm,
                                      uint64_t n, uint32_t n_pivots, uint32_t row_stride,
                                      uint8_t *__restrict__ pcodes, float *__restrict__ pnorm,
@@ -137,9 +281,29 @@ ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_
   if (nq == 0 || n_entry == 0) return fail(ANN_EINVAL, "ann_entry_scan: nq and n_entry must be positive");
   if (n_entry > (uint32_t)kScanKeep) return fail(ANN_ECAPACITY, "ann_entry_scan: n_entry = %u exceeds %d", n_entry, kScanKeep);
   const Workspace *wp = nullptr;
+  const LevelDev &L = index->level[0];
+  if (L.bits == 8 && n_entry == 1 && index->d <= (uint32_t)kFsMaxD) {
+    // folding and scan in one launch, on the matrix cores
+    Workspace *fw = nullptr;
+    ann_status rc = workspace_for(index, 0, nq, st, &fw);
+    if (rc != ANN_OK) return rc;
+    const size_t smem = (size_t)kFsQueries * (index->d + 1) * sizeof(double) + 4 * kFsQueries * sizeof(uint64_t) +
+                        3 * kFsQueries * 4 + (size_t)kFsQueries * (L.row_stride + 8);
+    if (smem > 48 * 1024) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fold_scan_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    }
+    fold_scan_kernel<<<(nq + kFsQueries - 1) / kFsQueries, kFsThreads, smem, st>>>(
+        q, nq, index->d, L.lo, L.delta, fw->tq, fw->tq_stride, fw->s, fw->qlo, fw->sum_t, index->pivot_codes,
+        index->pivot_norm, index->pivot_ids, index->n_pivots, L.row_stride, index->metric, out_entry_ids);
+    ANN_HIP(hipGetLastError());
+    fw->folded_q = q;
+    fw->folded_nq = nq;
+    return ANN_OK;
+  }
   ann_status rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st, &wp);
   if (rc != ANN_OK) return rc;
-  const LevelDev &L = index->level[0];
   const Workspace &w = *wp;
 #define ANN_ES(B, P)                                                                                                   \
   entry_scan_kernel<B, P><<<nq, 64, 0, st>>>(index->pivot_codes, index->pivot_norm, index->pivot_ids, index->n_pivots,   \

@@ -195,7 +195,7 @@ def test_entry_scan_and_search_from_scanned_entries(H, n, d, R, metric, bits):
     m = metric_id(metric)
     lv = oracle.sq_fit(X, bits)
     ix = H.GpuIndex(X, adj, 0, [lv], m)
-    for P, E in ((257, 4), (n, 1), (3, 4)):
+    for P, E in ((257, 4), (n, 1), (3, 4), (257, 1), (3, 1), (64, 2)):
         want = oracle.entry_scan(lv, d, Q, P, E, metric=m)
         got = ix.entry_scan(Q, P, E)
         assert (got == want).all()
