@@ -137,6 +137,7 @@ class GpuIndex:
         nq = Q.shape[0]
         ann.ann_build_entry_table(self.handle, n_pivots, stream_ptr())
         qd = dev(Q)
+        self._last_qd = qd          # a search may reuse the folding this scan leaves (same_queries_as_last_call)
         out = torch.empty((nq, n_entry), dtype=torch.int32, device=DEV)
         ann.ann_entry_scan(self.handle, qd, nq, n_entry, out, stream_ptr())
         torch.cuda.synchronize()

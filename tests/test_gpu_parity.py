@@ -189,7 +189,8 @@ def test_redundant_layout_gives_identical_results(H, n, d, R, nq, metric, bits, 
 
 
 @pytest.mark.parametrize("n,d,R,metric,bits", [(5000, 128, 32, "l2", 8), (2000, 960, 16, "l2", 4), (3000, 96, 32, "ip", 8),
-                                                 (300, 16, 4, "ip", 8)])
+                                                 (300, 16, 4, "ip", 8), (1500, 256, 16, "l2", 8), (1200, 300, 8, "l2", 8),
+                                                 (900, 100, 8, "ip", 8)])
 def test_entry_scan_and_search_from_scanned_entries(H, n, d, R, metric, bits):
     w, X, Q, adj = small_case(n, d, R, 20, seed=n + 7, metric=metric, bits=bits, normalize=(metric == "ip"))
     m = metric_id(metric)
@@ -200,6 +201,9 @@ def test_entry_scan_and_search_from_scanned_entries(H, n, d, R, metric, bits):
         got = ix.entry_scan(Q, P, E)
         assert (got == want).all()
         orc = oracle.search_batch(lv, d, adj, 0, Q, 40, metric=m, entries=want)
+        # the first search takes the folded queries the scan left behind, the second folds them itself
+        gpu = ix.search(Q, 40, entries=got, reuse_folded_queries=True, same_queries_as_last_call=True)
+        assert_search_equal(gpu, orc)
         gpu = ix.search(Q, 40, entries=got)
         assert_search_equal(gpu, orc)
     ix.close()
