@@ -219,6 +219,67 @@ __global__ __launch_bounds__(256) void bf_tile_kernel(const float *__restrict__ 
 }
 
 
+// Global -> LDS staging of one K chunk of a tile (QT query rows, then BT base
+// rows) by NT threads.  Rows are staged K-contiguous with pitch KC + 4 floats:
+// LDS is written and read 16 bytes at a time without bank conflicts.  The loads
+// are unconditional, with addresses clamped into the arrays (conditional loads
+// make the compiler wait for every outstanding load at each of them), and are
+// issued back to back; what lies outside the arrays is zeroed when the
+// registers are written to LDS.  An address is a base common to the workgroup
+// (the tile's first row) plus a 32-bit offset of the thread.
+template <int QT, int BT, int KC, int NT>
+struct TileStager {
+  static constexpr int ROWS = QT + BT, P = KC + 4;
+  static constexpr int C4 = KC / 4;      // float4 per staged row
+  static constexpr int RP = NT / C4;     // rows staged per pass of the workgroup
+  static constexpr int NLD = ROWS / RP;  // passes
+  static_assert(ROWS % RP == 0 && QT % RP == 0, "a pass is all queries or all base rows");
+  const float *q_base, *x;
+  float *stage_buf;   // [2][ROWS][P]
+  uint64_t b_end;     // end of the slab
+  uint32_t d, q_last; // q_last: last row of the batch, counted from the tile's first
+  int s_row, s_col;
+
+  __device__ __forceinline__ TileStager(const float *Q, const float *X, float *lds, uint32_t q0, uint32_t nq, uint32_t dim,
+                                        uint64_t slab_end, int tid)
+      : q_base(Q + (uint64_t)q0 * dim), x(X), stage_buf(lds), b_end(slab_end), d(dim), q_last(nq - 1 - q0),
+        s_row(tid / C4), s_col((tid % C4) * 4) {}
+
+  // rows of the tile that starts at base row t0 (at or past the slab's end: clamped loads, nothing kept), columns k0 ..
+  __device__ __forceinline__ void fetch(float4 (&reg)[NLD], uint32_t &keep, uint64_t t0, uint32_t k0) const {
+    const uint32_t kk = k0 + s_col;
+    const bool k_in = kk < d;
+    const uint32_t kc = k_in ? kk : 0;
+    const uint64_t t0c = t0 < b_end ? t0 : b_end - 1;
+    const float *x_base = x + t0c * d;
+    const uint64_t left = b_end - 1 - t0c;
+    const uint32_t x_last = left < (uint64_t)BT ? (uint32_t)left : (uint32_t)BT;   // last row of the slab, counted from the tile's first
+    keep = 0;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const uint32_t row = (uint32_t)(s_row + RP * i);
+      if (row < (uint32_t)QT) {
+        const bool in = row <= q_last && k_in;
+        reg[i] = *reinterpret_cast<const float4 *>(q_base + ((row < q_last ? row : q_last) * d + kc));
+        keep |= in ? 1u << i : 0u;
+      } else {
+        const uint32_t r = row - QT;
+        const bool in = t0 < b_end && r <= x_last && k_in;
+        reg[i] = *reinterpret_cast<const float4 *>(x_base + ((r < x_last ? r : x_last) * d + kc));
+        keep |= in ? 1u << i : 0u;
+      }
+    }
+  }
+  __device__ __forceinline__ void stage(const float4 (&reg)[NLD], uint32_t keep, int b) const {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const bool in = (keep >> i) & 1u;
+      const float4 v = make_float4(in ? reg[i].x : 0.f, in ? reg[i].y : 0.f, in ? reg[i].z : 0.f, in ? reg[i].w : 0.f);
+      *reinterpret_cast<float4 *>(stage_buf + ((size_t)b * ROWS + s_row + RP * i) * P + s_col) = v;
+    }
+  }
+};
+
 // ---------------------------------------------------------------------------
 // Larger tiles for the common case (d a multiple of 4, moderate k): a
 // workgroup of four wavefronts computes 64 WR queries x 64 WC base rows per
@@ -242,11 +303,10 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
                                                        uint32_t metric, uint64_t rows_per_slab, uint32_t kp, uint32_t cb,
                                                        uint32_t *__restrict__ bound /*[nq]*/,
                                                        uint32_t *__restrict__ cand_out /*[nq][slabs][kp]*/) {
-  constexpr int QT = 64 * WR, BT = 64 * WC, ROWS = QT + BT, P = KC + 4;
-  constexpr int C4 = KC / 4;            // float4 per staged row
-  constexpr int RP = 256 / C4;          // rows staged per pass of the workgroup
-  constexpr int NLD = ROWS / RP;        // passes
-  static_assert(WR * WC == 4 && ROWS % RP == 0 && QT % RP == 0, "tile shape");
+  constexpr int QT = 64 * WR, BT = 64 * WC;
+  using Stager = TileStager<QT, BT, KC, 256>;
+  constexpr int ROWS = Stager::ROWS, P = Stager::P, NLD = Stager::NLD;
+  static_assert(WR * WC == 4, "four wavefronts");
   extern __shared__ float smem_f[];
   float *stage_buf = smem_f;                                // [2][ROWS][P]
   float *thr = stage_buf + 2 * ROWS * P;                    // [QT]
@@ -266,29 +326,9 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
     cnt[r] = 0;
   }
 
-  const int s_row = tid / C4, s_col = (tid % C4) * 4;
+  const Stager stager(Q, X, stage_buf, q0, nq, d, b_end, tid);
   float4 reg[NLD];
-  auto fetch = [&](uint64_t t0, uint32_t k0) {
-    const uint32_t kk = k0 + s_col;
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int row = s_row + RP * i;   // a pass is all queries or all base rows (QT % RP == 0)
-      reg[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (row < QT) {
-        const uint32_t qi = q0 + row;
-        if (qi < nq && kk < d) reg[i] = *reinterpret_cast<const float4 *>(Q + (uint64_t)qi * d + kk);
-      } else {
-        const uint64_t bi = t0 + (row - QT);
-        if (bi < b_end && kk < d) reg[i] = *reinterpret_cast<const float4 *>(X + bi * d + kk);
-      }
-    }
-  };
-  auto stage = [&](int b) {
-#pragma unroll
-    for (int i = 0; i < NLD; ++i)
-      *reinterpret_cast<float4 *>(stage_buf + ((size_t)b * ROWS + s_row + RP * i) * P + s_col) = reg[i];
-  };
-
+  uint32_t keep = 0;
   // Cut row `row` back to its kp smallest entries (ids differ, so no ties).
   auto cut = [&](int row) {
     const uint32_t c = cnt[row] < cb ? cnt[row] : cb;
@@ -339,8 +379,8 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
   const float scale = metric == ANN_L2 ? -2.0f : -1.0f;
   int cur = 0;
   if (b_begin < b_end) {
-    fetch(b_begin, 0);
-    stage(0);
+    stager.fetch(reg, keep, b_begin, 0);
+    stager.stage(reg, keep, 0);
   }
   __syncthreads();
 
@@ -366,7 +406,7 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
       const bool last_chunk = c + 1 == n_chunks;
       const uint64_t nt0 = last_chunk ? t0 + BT : t0;
       const bool more = nt0 < b_end;
-      if (more) fetch(nt0, last_chunk ? 0 : (c + 1) * KC);
+      stager.fetch(reg, keep, nt0, last_chunk ? 0 : (c + 1) * KC);   // (no tile left: clamped loads that are never staged)
       const float *ap = stage_buf + ((size_t)cur * ROWS + wr * 64 + l32) * P + half * (KC / 2);
       const float *bp = stage_buf + ((size_t)cur * ROWS + QT + wc * 64 + l32) * P + half * (KC / 2);
 #pragma unroll
@@ -385,7 +425,7 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
           acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av1[e], bv1[e], acc[1][1], 0, 0, 0);
         }
       }
-      if (more) stage(cur ^ 1);
+      if (more) stager.stage(reg, keep, cur ^ 1);
       __syncthreads();
       cur ^= 1;
     }
@@ -484,10 +524,11 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
                                                      uint32_t metric, uint64_t rows_per_slab, uint32_t kp,
                                                      uint32_t *__restrict__ bound /*[nq]*/,
                                                      uint32_t *__restrict__ cand_out /*[nq][slabs][2][kp]*/) {
-  constexpr int WC = 2, QT = 128, BT = 128, ROWS = QT + BT, P = KC + 4, NT = 64 * kOwnWaves;
-  constexpr int C4 = KC / 4, RP = NT / C4, NLD = ROWS / RP;
+  constexpr int WC = 2, QT = 128, BT = 128;
+  using Stager = TileStager<QT, BT, KC, 64 * kOwnWaves>;
+  constexpr int ROWS = Stager::ROWS, P = Stager::P, NLD = Stager::NLD;
   constexpr int NR = kOwnWaves * kOwnRows;   // (row, wavefront) lists per workgroup
-  static_assert(ROWS % RP == 0 && QT % RP == 0 && kOwnWaves / WC * kOwnRows == QT, "tile shape");
+  static_assert(kOwnWaves / WC * kOwnRows == QT, "tile shape");
   extern __shared__ float smem_f[];
   float *stage_buf = smem_f;                                                  // [2][ROWS][P]
   float *u_all = stage_buf + 2 * ROWS * P;                                    // [NR]  acc must exceed this
@@ -516,49 +557,11 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
     cnt[lane] = 0;
   }
 
-  const int s_row = tid / C4, s_col = (tid % C4) * 4;
   // two sets of staging registers: a chunk is fetched two steps before it is
-  // multiplied (one step does not cover the latency of a row that comes from HBM)
+  // multiplied, so that a row that comes from HBM has two steps to arrive
+  const Stager stager(Q, X, stage_buf, q0, nq, d, b_end, tid);
   float4 reg_a[NLD], reg_b[NLD];
   uint32_t keep_a = 0, keep_b = 0;   // bit i: reg[i] lies inside the arrays
-  // Loads are unconditional (addresses clamped into the arrays) so that they
-  // are issued back to back; what lies outside is zeroed when it is staged.
-  // An address is a base common to the workgroup (the tile's first row) plus
-  // a 32-bit offset of the thread (row inside the tile, column).
-  const float *q_base = Q + (uint64_t)q0 * d;
-  const uint32_t q_last = nq - 1 - q0;   // last row of the batch, counted from the tile's first
-  auto fetch = [&](float4 (&reg)[NLD], uint32_t &keep, uint64_t t0, uint32_t k0) {
-    const uint32_t kk = k0 + s_col;
-    const bool k_in = kk < d;
-    const uint32_t kc = k_in ? kk : 0;
-    const uint64_t t0c = t0 < b_end ? t0 : b_end - 1;
-    const float *x_base = X + t0c * d;
-    const uint64_t left = b_end - 1 - t0c;
-    const uint32_t x_last = left < (uint64_t)BT ? (uint32_t)left : (uint32_t)BT;   // last row of the slab, counted from the tile's first
-    keep = 0;
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const uint32_t row = (uint32_t)(s_row + RP * i);   // a pass is all queries or all base rows (QT % RP == 0)
-      if (row < (uint32_t)QT) {
-        const bool in = row <= q_last && k_in;
-        reg[i] = *reinterpret_cast<const float4 *>(q_base + ((row < q_last ? row : q_last) * d + kc));
-        keep |= in ? 1u << i : 0u;
-      } else {
-        const uint32_t r = row - QT;
-        const bool in = t0 < b_end && r <= x_last && k_in;
-        reg[i] = *reinterpret_cast<const float4 *>(x_base + ((r < x_last ? r : x_last) * d + kc));
-        keep |= in ? 1u << i : 0u;
-      }
-    }
-  };
-  auto stage = [&](const float4 (&reg)[NLD], uint32_t keep, int b) {
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const bool in = (keep >> i) & 1u;
-      const float4 v = make_float4(in ? reg[i].x : 0.f, in ? reg[i].y : 0.f, in ? reg[i].z : 0.f, in ? reg[i].w : 0.f);
-      *reinterpret_cast<float4 *>(stage_buf + ((size_t)b * ROWS + s_row + RP * i) * P + s_col) = v;
-    }
-  };
   auto wave_sync = [&]() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -603,10 +606,10 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
     }
   };
   if (b_begin < b_end) {
-    fetch(reg_a, keep_a, f_t0, 0);
+    stager.fetch(reg_a, keep_a, f_t0, 0);
     advance();
-    stage(reg_a, keep_a, 0);
-    fetch(reg_a, keep_a, f_t0, f_c * KC);   // (past the end: clamped loads that are never staged)
+    stager.stage(reg_a, keep_a, 0);
+    stager.fetch(reg_a, keep_a, f_t0, f_c * KC);   // (past the end: clamped loads that are never staged)
     advance();
   }
   __syncthreads();
@@ -706,7 +709,7 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
   auto one_step = [&](const float4 (&r_stage)[NLD], uint32_t k_stage, float4 (&r_fetch)[NLD], uint32_t &k_fetch) -> bool {
     const bool last_chunk = c + 1 == n_chunks;
     const bool more = !last_chunk || t0 + BT < b_end;
-    fetch(r_fetch, k_fetch, f_t0, f_c * KC);   // (past the end: clamped loads that are never staged)
+    stager.fetch(r_fetch, k_fetch, f_t0, f_c * KC);   // (past the end: clamped loads that are never staged)
     advance();
     const float *ap = stage_buf + ((size_t)cur * ROWS + wr * kOwnRows + l32) * P + half * (KC / 2);
     const float *bp = stage_buf + ((size_t)cur * ROWS + QT + wc * 64 + l32) * P + half * (KC / 2);
@@ -723,7 +726,7 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
         acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0[e], bv1[e], acc[1], 0, 0, 0);
       }
     }
-    if (more) stage(r_stage, k_stage, cur ^ 1);
+    if (more) stager.stage(r_stage, k_stage, cur ^ 1);
     __syncthreads();
     cur ^= 1;
     if (last_chunk) {
