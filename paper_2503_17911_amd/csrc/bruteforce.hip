@@ -302,6 +302,8 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
                                                        uint64_t n, uint32_t d, const float *__restrict__ Q, uint32_t nq,
                                                        uint32_t metric, uint64_t rows_per_slab, uint32_t kp, uint32_t cb,
                                                        uint32_t *__restrict__ bound /*[nq]*/,
+                                                       uint32_t *__restrict__ part_best /*[nq][slabs]*/, uint32_t part_rank,
+                                                       uint32_t part_lists,
                                                        uint32_t *__restrict__ cand_out /*[nq][slabs][kp]*/) {
   constexpr int QT = 64 * WR, BT = 64 * WC;
   using Stager = TileStager<QT, BT, KC, 256>;
@@ -357,6 +359,8 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
       const uint32_t i = lane + u * kWave;
       if (i < c && rank[u] < kp) {
         list[rank[u]] = mine[u];
+        // this slab's part_rank-th best, for the bound over several slabs (see the tile loop)
+        if (rank[u] == part_rank - 1 && q0 + row < nq) part_best[(uint64_t)(q0 + row) * n_slabs + slab] = (uint32_t)(mine[u] >> 32);
         if (rank[u] == kp - 1) {
           thr[row] = unorder_f32((uint32_t)(mine[u] >> 32));
           // the kp-th best of one slab bounds the kp-th best overall: the slabs of a query share the smallest
@@ -384,7 +388,33 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
   }
   __syncthreads();
 
-  for (uint64_t t0 = b_begin; t0 < b_end; t0 += BT) {
+  uint32_t tile_no = 0;
+  for (uint64_t t0 = b_begin; t0 < b_end; t0 += BT, ++tile_no) {
+    // A tighter bound, every eighth tile: if part_lists slabs each hold
+    // part_rank entries at or below T, the query has part_lists * part_rank >=
+    // kp entries at or below T.  With every slab publishing its part_rank-th
+    // best, T is the part_lists-th smallest of the published values; it joins
+    // the shared bound.
+    if (tile_no % 8 == 7 && tid < QT && q0 + tid < nq) {
+      constexpr int kMaxLists = 8;
+      uint32_t low[kMaxLists];   // the smallest published values, ascending
+#pragma unroll
+      for (int j = 0; j < kMaxLists; ++j) low[j] = 0xFFFFFFFFu;
+      const uint32_t *pb = part_best + (uint64_t)(q0 + tid) * n_slabs;
+      for (uint32_t sl = 0; sl < n_slabs; ++sl) {
+        uint32_t v = pb[sl];
+#pragma unroll
+        for (int j = 0; j < kMaxLists; ++j) {
+          const uint32_t lo_ = v < low[j] ? v : low[j];
+          v = v < low[j] ? low[j] : v;
+          low[j] = lo_;
+        }
+      }
+      uint32_t t = 0xFFFFFFFFu;
+#pragma unroll
+      for (int j = 0; j < kMaxLists; ++j) t = (uint32_t)j == part_lists - 1 ? low[j] : t;
+      if (t < 0xFF800000u) atomicMin(&bound[q0 + tid], t);   // (unpublished slots hold +inf)
+    }
     floatx16 acc[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -855,9 +885,17 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
   // candidates, then one shared bound per query (the large-tile kernels)
   const size_t n_cand_words = (size_t)nq * slabs * lists * kp;
-  ANN_HIP(hipMalloc((void **)&cand, (n_cand_words + nq) * sizeof(uint32_t)));
+  // (then, for the 4-wavefront kernels, every slab's part_rank-th best per query)
+  const uint32_t part_lists = slabs < 8 ? slabs : 8;
+  const uint32_t part_rank = (kp + part_lists - 1) / part_lists;
+  const size_t n_part_words = shape == 1 || shape == 2 ? (size_t)nq * slabs : 0;
+  ANN_HIP(hipMalloc((void **)&cand, (n_cand_words + nq + n_part_words) * sizeof(uint32_t)));
   uint32_t *bound = cand + n_cand_words;
-  if (shape != 0) fill_u32_kernel<<<(nq + 255) / 256, 256, 0, st>>>(bound, nq, 0xFF800000u);   // +inf in score order
+  uint32_t *part_best = bound + nq;
+  if (shape != 0) {
+    const size_t n_fill = nq + n_part_words;
+    fill_u32_kernel<<<(uint32_t)((n_fill + 255) / 256), 256, 0, st>>>(bound, (uint32_t)n_fill, 0xFF800000u);   // +inf in score order
+  }
   if (metric == ANN_L2) {
     e = hipMalloc((void **)&xnorm, (size_t)n * sizeof(float));
     if (e != hipSuccess) {
@@ -871,9 +909,11 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
     bf_own_kernel<32><<<grid, 64 * kOwnWaves, smem, st>>>(x, metric == ANN_L2 ? xnorm : x, n, d, q, nq, metric, rows_per_slab, kp,
                                                           bound, cand);
   else if (shape == 1)
-    bf_block_kernel<2, 2, 32, 1><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, bound, cand);
+    bf_block_kernel<2, 2, 32, 1><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, bound, part_best,
+                                                          part_rank, part_lists, cand);
   else if (shape == 2)
-    bf_block_kernel<1, 4, 16, 3><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, bound, cand);
+    bf_block_kernel<1, 4, 16, 3><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, bound, part_best,
+                                                          part_rank, part_lists, cand);
   else if (vec4)
     bf_tile_kernel<true><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, cand);
   else
