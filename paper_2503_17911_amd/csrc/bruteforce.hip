@@ -219,6 +219,33 @@ __global__ __launch_bounds__(256) void bf_tile_kernel(const float *__restrict__ 
 }
 
 
+// The part_lists-th smallest of n_vals published values (+inf in score order:
+// nothing published): with every part (a slab's buffer, a wavefront's list)
+// publishing its part_rank-th best score, that many parts hold part_rank
+// entries each at or below it, so the query has part_lists * part_rank >= kp
+// entries at or below it - a bound on its kp-th best.
+__device__ __forceinline__ uint32_t bound_over_parts(const uint32_t *vals, uint32_t n_vals, uint32_t part_lists) {
+  constexpr int kMaxLists = 8;
+  uint32_t low[kMaxLists];   // the smallest published values, ascending
+#pragma unroll
+  for (int j = 0; j < kMaxLists; ++j) low[j] = 0xFFFFFFFFu;
+  for (uint32_t i = 0; i < n_vals; ++i) {
+    uint32_t v = vals[i];
+#pragma unroll
+    for (int j = 0; j < kMaxLists; ++j) {
+      const uint32_t lo_ = v < low[j] ? v : low[j];
+      v = v < low[j] ? low[j] : v;
+      low[j] = lo_;
+    }
+  }
+  uint32_t t = 0xFFFFFFFFu;
+#pragma unroll
+  for (int j = 0; j < kMaxLists; ++j) t = (uint32_t)j == part_lists - 1 ? low[j] : t;
+  return t;
+}
+// tiles 3, 7, 15, 31, ... of a slab: often while the thresholds still move fast, rarely later
+__device__ __forceinline__ bool bound_refresh_due(uint32_t tile_no) { return tile_no >= 3 && (tile_no & (tile_no + 1)) == 0; }
+
 // Global -> LDS staging of one K chunk of a tile (QT query rows, then BT base
 // rows) by NT threads.  Rows are staged K-contiguous with pitch KC + 4 floats:
 // LDS is written and read 16 bytes at a time without bank conflicts.  The loads
@@ -390,30 +417,10 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
 
   uint32_t tile_no = 0;
   for (uint64_t t0 = b_begin; t0 < b_end; t0 += BT, ++tile_no) {
-    // A tighter bound, every eighth tile: if part_lists slabs each hold
-    // part_rank entries at or below T, the query has part_lists * part_rank >=
-    // kp entries at or below T.  With every slab publishing its part_rank-th
-    // best, T is the part_lists-th smallest of the published values; it joins
-    // the shared bound.
-    if (tile_no % 8 == 7 && tid < QT && q0 + tid < nq) {
-      constexpr int kMaxLists = 8;
-      uint32_t low[kMaxLists];   // the smallest published values, ascending
-#pragma unroll
-      for (int j = 0; j < kMaxLists; ++j) low[j] = 0xFFFFFFFFu;
-      const uint32_t *pb = part_best + (uint64_t)(q0 + tid) * n_slabs;
-      for (uint32_t sl = 0; sl < n_slabs; ++sl) {
-        uint32_t v = pb[sl];
-#pragma unroll
-        for (int j = 0; j < kMaxLists; ++j) {
-          const uint32_t lo_ = v < low[j] ? v : low[j];
-          v = v < low[j] ? low[j] : v;
-          low[j] = lo_;
-        }
-      }
-      uint32_t t = 0xFFFFFFFFu;
-#pragma unroll
-      for (int j = 0; j < kMaxLists; ++j) t = (uint32_t)j == part_lists - 1 ? low[j] : t;
-      if (t < 0xFF800000u) atomicMin(&bound[q0 + tid], t);   // (unpublished slots hold +inf)
+    // a tighter bound from several slabs' part_rank-th best scores joins the shared bound
+    if (bound_refresh_due(tile_no) && tid < QT && q0 + tid < nq) {
+      const uint32_t t = bound_over_parts(part_best + (uint64_t)(q0 + tid) * n_slabs, n_slabs, part_lists);
+      if (t < 0xFF800000u) atomicMin(&bound[q0 + tid], t);
     }
     floatx16 acc[2][2];
 #pragma unroll
@@ -885,7 +892,8 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
   // candidates, then one shared bound per query (the large-tile kernels)
   const size_t n_cand_words = (size_t)nq * slabs * lists * kp;
-  // (then, for the 4-wavefront kernels, every slab's part_rank-th best per query)
+  // (then, for the 4-wavefront kernels, every slab's part_rank-th best per query: see bound_over_parts; in the
+  // 8-wavefront kernel the loads of that bound cost more than the few hits it would save)
   const uint32_t part_lists = slabs < 8 ? slabs : 8;
   const uint32_t part_rank = (kp + part_lists - 1) / part_lists;
   const size_t n_part_words = shape == 1 || shape == 2 ? (size_t)nq * slabs : 0;
