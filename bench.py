@@ -92,8 +92,8 @@ def main():
         print(kernel_source_hash())
         return
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (query sharding across GPUs needs no exchange; "
-                 "see DESIGN.md); run with --gpus 1")
+        sys.exit("bench.py: this build runs on one GPU only (queries are independent: more GPUs would each hold the "
+                 "index and take a share of the batch, with no exchange); run with --gpus 1")
 
     import numpy as np
     import torch
