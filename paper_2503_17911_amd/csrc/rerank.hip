@@ -49,7 +49,80 @@ __global__ __launch_bounds__(64) void rerank_kernel(const float *__restrict__ X,
   __syncthreads();
   const uint32_t *cand = cand_ids + (uint64_t)qi * cand_stride;
   uint32_t n_valid = 0;   // candidates that name a node: their entries are kept in order at the front of the list
-  for (uint32_t base = 0; base < n_cand; base += G) {
+  // the row sums of one round (G candidates side by side) go to the list; acc is this lane's share of candidate v
+  auto append = [&](uint32_t v, double acc) {
+    acc = group_sum_f64<LPR>(acc);
+    const bool have = chunk == 0 && v != kNone;
+    const uint64_t hm = __ballot(have);
+    if (have) {
+      float dist = (float)(metric == ANN_L2 ? acc : -acc);
+      uint32_t b = __float_as_uint(dist);
+      if ((b & 0x7FFFFFFFu) == 0) dist = 0.0f;
+      const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(hm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hm, 0u));
+      list[n_valid + below] = pack_vi(order_u32(dist), v);
+    }
+    n_valid += (uint32_t)__popcll(hm);
+  };
+  bool done = false;
+  if constexpr (VEC4) {
+    const uint32_t d4 = d / 4;
+    if (d4 <= 4 * (uint32_t)LPR) {
+      // Short rows (at most four 16-byte pieces per lane): three rounds at a
+      // time - their ids first, then all their rows, so that one memory latency
+      // covers the three rounds; the sums are formed in the order of the loop below.
+      constexpr int kRounds = 3;
+      const float4 *x4 = reinterpret_cast<const float4 *>(X);
+      for (uint32_t base = 0; base < n_cand; base += kRounds * G) {
+        uint32_t vv[kRounds];
+        float4 xr[kRounds][4];
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+          const uint32_t ci = base + r * G + grp;
+          uint32_t v = cand[ci < n_cand ? ci : n_cand - 1];
+          if (ci >= n_cand || v >= n) v = kNone;   // (padding is 0xFFFFFFFF >= n)
+          vv[r] = v;
+        }
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+          const float4 *row = x4 + (uint64_t)(vv[r] != kNone ? vv[r] : 0) * d4;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const uint32_t c = (uint32_t)(chunk + LPR * t);
+            xr[r][t] = row[c < d4 ? c : 0];
+          }
+        }
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+          if (base + r * G >= n_cand) break;
+          double acc = 0.0;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const uint32_t c = (uint32_t)(chunk + LPR * t);
+            if (c < d4 && vv[r] != kNone) {
+              const float4 xv = xr[r][t];
+              const float4 qv = *reinterpret_cast<const float4 *>(qs + 4 * c);
+              if (metric == ANN_L2) {
+                const double t0 = (double)qv.x - (double)xv.x, t1 = (double)qv.y - (double)xv.y;
+                const double t2 = (double)qv.z - (double)xv.z, t3 = (double)qv.w - (double)xv.w;
+                acc += t0 * t0;
+                acc += t1 * t1;
+                acc += t2 * t2;
+                acc += t3 * t3;
+              } else {
+                acc += (double)qv.x * (double)xv.x;
+                acc += (double)qv.y * (double)xv.y;
+                acc += (double)qv.z * (double)xv.z;
+                acc += (double)qv.w * (double)xv.w;
+              }
+            }
+          }
+          append(vv[r], acc);
+        }
+      }
+      done = true;
+    }
+  }
+  for (uint32_t base = 0; !done && base < n_cand; base += G) {
     const uint32_t ci = base + grp;
     uint32_t v = ci < n_cand ? cand[ci] : kNone;
     if (v != kNone && v >= n) v = kNone;
@@ -85,17 +158,7 @@ __global__ __launch_bounds__(64) void rerank_kernel(const float *__restrict__ X,
         }
       }
     }
-    acc = group_sum_f64<LPR>(acc);
-    const bool have = chunk == 0 && v != kNone;
-    const uint64_t hm = __ballot(have);
-    if (have) {
-      float dist = (float)(metric == ANN_L2 ? acc : -acc);
-      uint32_t b = __float_as_uint(dist);
-      if ((b & 0x7FFFFFFFu) == 0) dist = 0.0f;
-      const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(hm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hm, 0u));
-      list[n_valid + below] = pack_vi(order_u32(dist), v);
-    }
-    n_valid += (uint32_t)__popcll(hm);
+    append(v, acc);
   }
   __syncthreads();
   // only the entries that name a node are ranked (padding sorts last anyway)
