@@ -548,6 +548,7 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
 // the hit is tried again.  The lists of one query (its slabs, its two
 // wavefronts) publish their thresholds in global memory and use the smallest.
 constexpr int kOwnList = 32;     // entries per (row, wavefront) list
+constexpr int kOwnListRes = 24;  // the same when the query tile stays in LDS (d <= 128, k <= 10), which leaves less room
 constexpr int kOwnWaves = 8, kOwnRows = 32;   // wavefronts per workgroup, query rows per wavefront
 
 // number of set bits of mask below this lane's
@@ -555,23 +556,27 @@ __device__ __forceinline__ int bf_lanes_below(uint64_t mask) {
   return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-template <int KC>
+template <int KC, bool QRES, int LIST>
 __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X, const float *__restrict__ xnorm,
                                                      uint64_t n, uint32_t d, const float *__restrict__ Q, uint32_t nq,
                                                      uint32_t metric, uint64_t rows_per_slab, uint32_t kp,
                                                      uint32_t *__restrict__ bound /*[nq]*/,
                                                      uint32_t *__restrict__ cand_out /*[nq][slabs][2][kp]*/) {
   constexpr int WC = 2, QT = 128, BT = 128;
-  using Stager = TileStager<QT, BT, KC, 64 * kOwnWaves>;
+  constexpr int QS = QRES ? 0 : QT;   // query rows staged with every chunk (none when the query tile stays in LDS)
+  using Stager = TileStager<QS, BT, KC, 64 * kOwnWaves>;
   constexpr int ROWS = Stager::ROWS, P = Stager::P, NLD = Stager::NLD;
   constexpr int NR = kOwnWaves * kOwnRows;   // (row, wavefront) lists per workgroup
   static_assert(kOwnWaves / WC * kOwnRows == QT, "tile shape");
   extern __shared__ float smem_f[];
-  float *stage_buf = smem_f;                                                  // [2][ROWS][P]
+  // QRES: the 128 queries of the tile stay in LDS for the whole kernel, K padded to whole chunks, row pitch + 4
+  const uint32_t q_pitch = (d + KC - 1) / KC * KC + 4;
+  float *q_res = smem_f;                                                      // [QT][q_pitch] (QRES)
+  float *stage_buf = smem_f + (QRES ? QT * q_pitch : 0);                      // [2][ROWS][P]
   float *u_all = stage_buf + 2 * ROWS * P;                                    // [NR]  acc must exceed this
   uint32_t *thr_all = reinterpret_cast<uint32_t *>(u_all + NR);               // [NR]  ordered score an entry must be below
   uint32_t *cnt_all = thr_all + NR;                                           // [NR]
-  uint64_t *list_all = reinterpret_cast<uint64_t *>(cnt_all + NR);            // [NR][kOwnList]
+  uint64_t *list_all = reinterpret_cast<uint64_t *>(cnt_all + NR);            // [NR][LIST]
 
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int wr = wave / WC, wc = wave % WC, half = lane / 32, l32 = lane % 32;
@@ -586,7 +591,7 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
   float *u = u_all + wave * kOwnRows;
   uint32_t *thr = thr_all + wave * kOwnRows;
   uint32_t *cnt = cnt_all + wave * kOwnRows;
-  uint64_t *list = list_all + (size_t)wave * kOwnRows * kOwnList;
+  uint64_t *list = list_all + (size_t)wave * kOwnRows * LIST;
   if (lane < kOwnRows) {
     const bool live = q0 + wr * kOwnRows + lane < nq;
     u[lane] = live ? -INFINITY : INFINITY;   // rows past the batch never take anything
@@ -594,6 +599,15 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
     cnt[lane] = 0;
   }
 
+  if (QRES) {
+    const uint32_t p4 = (q_pitch - 4) / 4, d4 = d / 4;   // float4 per padded row, per row of Q
+    for (uint32_t e = tid; e < QT * p4; e += 64 * kOwnWaves) {
+      const uint32_t row = e / p4, c4 = e % p4;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (q0 + row < nq && c4 < d4) v = reinterpret_cast<const float4 *>(Q + (uint64_t)(q0 + row) * d)[c4];
+      *reinterpret_cast<float4 *>(q_res + row * q_pitch + 4 * c4) = v;
+    }
+  }
   // two sets of staging registers: a chunk is fetched two steps before it is
   // multiplied, so that a row that comes from HBM has two steps to arrive
   const Stager stager(Q, X, stage_buf, q0, nq, d, b_end, tid);
@@ -605,14 +619,14 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   };
 
-  // Cut list `row` (c entries, c <= kOwnList) back to its kp smallest; returns the new length.
+  // Cut list `row` (c entries, c <= LIST) back to its kp smallest; returns the new length.
   auto cut = [&](int row, uint32_t c) -> uint32_t {
-    uint64_t *l = list + (size_t)row * kOwnList;
-    const uint64_t mine = (uint32_t)lane < c ? l[lane < kOwnList ? lane : 0] : ~0ull;
+    uint64_t *l = list + (size_t)row * LIST;
+    const uint64_t mine = (uint32_t)lane < c ? l[lane < LIST ? lane : 0] : ~0ull;
     const uint32_t mhi = (uint32_t)(mine >> 32), mlo = (uint32_t)mine;
     uint32_t rank = 0;
 #pragma unroll
-    for (int j = 0; j < kOwnList; ++j) {
+    for (int j = 0; j < LIST; ++j) {
       const uint64_t o = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mhi, j) << 32) |
                          (uint32_t)__builtin_amdgcn_readlane((int)mlo, j);
       rank += o < mine ? 1u : 0u;   // ids differ, so no two entries are equal
@@ -721,8 +735,8 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
       while (__ballot(pending)) {
         if (pending) {
           const uint32_t pos = atomicAdd(&cnt[erow], 1u);
-          if (pos < (uint32_t)kOwnList) {
-            list[(size_t)erow * kOwnList + pos] = ent;
+          if (pos < (uint32_t)LIST) {
+            list[(size_t)erow * LIST + pos] = ent;
             pending = false;
           }
         }
@@ -732,7 +746,7 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
         while (todo) {
           const int row = __builtin_amdgcn_readlane(erow, __builtin_ctzll(todo));
           todo &= ~__ballot(pending && erow == row);
-          const uint32_t left = cut(row, kOwnList);   // the count ran past the list's end: the list is full
+          const uint32_t left = cut(row, LIST);   // the count ran past the list's end: the list is full
           if (lane == 0) cnt[row] = left;
         }
         wave_sync();
@@ -748,8 +762,9 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
     const bool more = !last_chunk || t0 + BT < b_end;
     stager.fetch(r_fetch, k_fetch, f_t0, f_c * KC);   // (past the end: clamped loads that are never staged)
     advance();
-    const float *ap = stage_buf + ((size_t)cur * ROWS + wr * kOwnRows + l32) * P + half * (KC / 2);
-    const float *bp = stage_buf + ((size_t)cur * ROWS + QT + wc * 64 + l32) * P + half * (KC / 2);
+    const float *ap = QRES ? q_res + (size_t)(wr * kOwnRows + l32) * q_pitch + c * KC + half * (KC / 2)
+                           : stage_buf + ((size_t)cur * ROWS + wr * kOwnRows + l32) * P + half * (KC / 2);
+    const float *bp = stage_buf + ((size_t)cur * ROWS + QS + wc * 64 + l32) * P + half * (KC / 2);
 #pragma unroll
     for (int j = 0; j < KC / 8; ++j) {
       const float4 a0 = *reinterpret_cast<const float4 *>(ap + 4 * j);
@@ -786,12 +801,12 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
   // every list down to kp, then to the exact stage
   wave_sync();
   for (int row = 0; row < kOwnRows; ++row) {
-    uint32_t c = cnt[row] < (uint32_t)kOwnList ? cnt[row] : (uint32_t)kOwnList;
+    uint32_t c = cnt[row] < (uint32_t)LIST ? cnt[row] : (uint32_t)LIST;
     if (c > kp) c = cut(row, c);
     const uint32_t qi = q0 + wr * kOwnRows + row;
     if (qi < nq && (uint32_t)lane < kp) {
       // an entry above what the query's lists have agreed on by now is not among its kp best
-      const uint64_t ent = list[(size_t)row * kOwnList + lane];
+      const uint64_t ent = list[(size_t)row * LIST + lane];
       const bool keep = (uint32_t)lane < c && (uint32_t)(ent >> 32) <= bound[qi];
       cand_out[(((uint64_t)qi * n_slabs + slab) * WC + wc) * kp + lane] = keep ? (uint32_t)ent : ANN_PAD_ID;
     }
@@ -874,9 +889,15 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
   uint32_t *cand = nullptr;
   size_t smem;
   const void *fn;
-  if (shape == 3) {
+  // (short rows and small k: the query tile stays in LDS and only base rows are staged)
+  const bool q_res = shape == 3 && d <= 128 && kp + 6 <= (uint32_t)kOwnListRes;
+  if (q_res) {
+    smem = (size_t)128 * ((d + 31) / 32 * 32 + 4) * sizeof(float) + (size_t)2 * 128 * (32 + 4) * sizeof(float) + 3 * 256 * 4 +
+           (size_t)256 * kOwnListRes * sizeof(uint64_t);
+    fn = reinterpret_cast<const void *>(bf_own_kernel<32, true, kOwnListRes>);
+  } else if (shape == 3) {
     smem = (size_t)2 * 256 * (32 + 4) * sizeof(float) + 3 * 256 * 4 + (size_t)256 * kOwnList * sizeof(uint64_t);
-    fn = reinterpret_cast<const void *>(bf_own_kernel<32>);
+    fn = reinterpret_cast<const void *>(bf_own_kernel<32, false, kOwnList>);
   } else if (shape == 1) {
     smem = (size_t)2 * 256 * (32 + 4) * sizeof(float) + 128 * 8 + (size_t)128 * cb * sizeof(uint64_t);
     fn = reinterpret_cast<const void *>(bf_block_kernel<2, 2, 32, 1>);
@@ -913,9 +934,12 @@ extern "C" ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d
     row_norm_kernel<<<2048, 256, 0, st>>>(x, n, d, xnorm);
   }
   const dim3 grid(q_tiles, slabs);
-  if (shape == 3)
-    bf_own_kernel<32><<<grid, 64 * kOwnWaves, smem, st>>>(x, metric == ANN_L2 ? xnorm : x, n, d, q, nq, metric, rows_per_slab, kp,
-                                                          bound, cand);
+  if (q_res)
+    bf_own_kernel<32, true, kOwnListRes><<<grid, 64 * kOwnWaves, smem, st>>>(x, metric == ANN_L2 ? xnorm : x, n, d, q, nq, metric,
+                                                                             rows_per_slab, kp, bound, cand);
+  else if (shape == 3)
+    bf_own_kernel<32, false, kOwnList><<<grid, 64 * kOwnWaves, smem, st>>>(x, metric == ANN_L2 ? xnorm : x, n, d, q, nq, metric,
+                                                                            rows_per_slab, kp, bound, cand);
   else if (shape == 1)
     bf_block_kernel<2, 2, 32, 1><<<grid, 256, smem, st>>>(x, xnorm, n, d, q, nq, metric, rows_per_slab, kp, cb, bound, part_best,
                                                           part_rank, part_lists, cand);
