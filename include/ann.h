@@ -9,7 +9,8 @@
  * Conventions that hold for every call
  *   - All array arguments are DEVICE pointers unless a comment says "host".
  *     The caller owns every input and output buffer; the library owns only the
- *     packed index it builds in ann_upload_index and a per-index workspace.
+ *     packed index it builds in ann_upload_index and the workspaces for folded
+ *     queries it keeps with that index (one per stream, see below).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue work on it and return without waiting, except where noted.
  *   - Ids are uint32_t < 2^31.  ANN_PAD_ID marks "no entry"; result lists
@@ -330,7 +331,9 @@ ann_status ann_rerank(ann_index *index, const float *q, uint32_t nq, const uint3
  * ground truth of the paper's recall, Section 6.1): a dense Q.X^T contraction
  * on the matrix cores selects k + margin candidates per query, which are then
  * re-evaluated directly in fp64 and sorted by (distance, id).
- *   x [n][d], q [nq][d] fp32; out_ids/out_dist [nq][k]; k <= 256.
+ *   x [n][d], q [nq][d] fp32; out_ids/out_dist [nq][k]; k <= 256, d <= 2048,
+ *   n < 2^31.  The fastest path needs d to be a multiple of 4, 16-byte aligned
+ *   x and q, and k <= 16; any d and k within the limits work.
  * Allocates temporaries and synchronises the stream before returning.
  */
 ann_status ann_bruteforce_topk(const float *x, uint64_t n, uint32_t d, const float *q, uint32_t nq, uint32_t k,
