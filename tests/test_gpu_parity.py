@@ -394,7 +394,8 @@ def test_rerank_and_rescore(H, metric):
 @pytest.mark.parametrize("n,d,nq,k,metric", [(4000, 64, 70, 10, "l2"), (3001, 128, 33, 10, "ip"),
                                               (2500, 100, 5, 100, "l2"), (130, 960, 40, 10, "l2"),
                                               (50, 16, 3, 64, "ip"), (3000, 30, 20, 10, "l2"),
-                                              (3000, 64, 20, 200, "l2"), (40000, 32, 300, 10, "ip")])
+                                              (3000, 64, 20, 200, "l2"), (40000, 32, 300, 10, "ip"), (1, 4, 1, 1, "l2"),
+                                              (5, 8, 200, 3, "l2"), (129, 132, 129, 16, "ip"), (257, 128, 1, 17, "l2")])
 def test_bruteforce_matches_fp64_exhaustive_search(H, n, d, nq, k, metric):
     w = inputs.Workload("bf", n, d, 9, 0.3, nq, seed=n + d, normalize=(metric == "ip"))
     X, Q = inputs.base_vectors(w), inputs.queries(w)
