@@ -547,6 +547,10 @@ __global__ __launch_bounds__(256) void bf_block_kernel(const float *__restrict__
 // its kp best (rank counting over lanes), which lowers the row's threshold, and
 // the hit is tried again.  The lists of one query (its slabs, its two
 // wavefronts) publish their thresholds in global memory and use the smallest.
+//
+// QRES: for rows of up to 128 dimensions the query tile is read into LDS once
+// and stays there (K padded to whole chunks, row pitch + 4); only base rows are
+// staged with every chunk.  LIST: entries per (row, wavefront) list.
 constexpr int kOwnList = 32;     // entries per (row, wavefront) list
 constexpr int kOwnListRes = 24;  // the same when the query tile stays in LDS (d <= 128, k <= 10), which leaves less room
 constexpr int kOwnWaves = 8, kOwnRows = 32;   // wavefronts per workgroup, query rows per wavefront
