@@ -49,7 +49,7 @@ def _load():
         lib.orc_key.argtypes = [_i32, _f32, _f32, _i32, _f32]
         lib.orc_key.restype = _f32
         lib.orc_search_batch.argtypes = [_i64, _i32, _i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _u32p, _u32,
-                                         _f32p, _i32, _u32p, _i32, _i32, _f32p, _f32, _i32, _i32, _u32p, _f32p, _i32p, _u32p]
+                                         _f32p, _i32, _u32p, _i32, _i32, _f32p, _f32, _i32, _i32, _u32p, _f32p, _i32p, _u32p, _u8p]
         lib.orc_rescore_batch.argtypes = [_i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _f32p, _i32, _u32p, _i32,
                                           _u32p, _f32p, _i32p]
         lib.orc_entry_scan.argtypes = [_i64, _i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _f32p, _i32, _i32, _i32, _u32p]
@@ -142,8 +142,9 @@ def key(metric, s, qlo, idot_value, norm_term) -> np.float32:
 
 
 def search_batch(level: SQLevel, d, adjacency, entry_point, Q, ef, metric=L2, entries=None, labels=None,
-                 alpha_s=float("inf"), m_s=0, expansions_per_step=1):
-    """Algorithm 1 per query.  Returns (ids, keys, idot, counts), pools padded to ef."""
+                 alpha_s=float("inf"), m_s=0, expansions_per_step=1, want_visited=False):
+    """Algorithm 1 per query.  Returns (ids, keys, idot, counts), pools padded to ef;
+    with want_visited also the final visited sets as a [nq][n] uint8 array."""
     adjacency, Q = _c(adjacency, np.uint32), _c(Q, np.float32)
     n, degree = adjacency.shape
     nq = Q.shape[0]
@@ -151,6 +152,7 @@ def search_batch(level: SQLevel, d, adjacency, entry_point, Q, ef, metric=L2, en
     keys = np.empty((nq, ef), np.float32)
     dots = np.empty((nq, ef), np.int32)
     counts = np.empty((nq, 4), np.uint32)
+    visited = np.empty((nq, n), np.uint8) if want_visited else None
     n_entry = 0
     if entries is not None:
         entries = _c(entries, np.uint32).reshape(nq, -1)
@@ -161,7 +163,9 @@ def search_batch(level: SQLevel, d, adjacency, entry_point, Q, ef, metric=L2, en
                              _p(level.delta, _f32p), _p(level.norm_term, _f32p), _p(adjacency, _u32p),
                              int(entry_point), _p(Q, _f32p), nq, _p(entries, _u32p), n_entry, ef, _p(labels, _f32p),
                              float(alpha_s), int(m_s), int(expansions_per_step), _p(ids, _u32p),
-                             _p(keys, _f32p), _p(dots, _i32p), _p(counts, _u32p))
+                             _p(keys, _f32p), _p(dots, _i32p), _p(counts, _u32p), _p(visited, _u8p))
+    if want_visited:
+        return ids, keys, dots, counts, visited
     return ids, keys, dots, counts
 
 

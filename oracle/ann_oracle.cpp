@@ -111,7 +111,7 @@ void orc_sq_train_truncated(const float *X, int64_t n, int32_t d, int32_t bits, 
 
 // c_ij = clamp(floor((x - lo_j) / delta_j + 0.5), 0, 2^b - 1).  Also emits the
 // norm term B_i = sum_j decode(c_ij)^2 (fp64 accumulation in index order,
-// rounded once), the "one additional FLOAT32 per database vector" of Sec. 5.2.
+// rounded once): the single extra fp32 that Section 5.2 stores with each base vector.
 void orc_sq_encode(const float *X, int64_t n, int32_t d, int32_t bits, const float *lo, const float *delta,
                    uint8_t *codes, float *norm_term) {
   const int rb = row_bytes(d, bits);
@@ -189,103 +189,141 @@ float orc_key(int32_t metric, float s, float qlo, int32_t idot, float norm_term)
   return key_from_idot(metric, s, qlo, idot, norm_term);
 }
 
+}  // extern "C" (the search helpers below are internal)
+
 // ---------------------------------------------------------------- search
 // Algorithm 1 for a batch of queries, one after the other.  The prefetch
 // parameters of the algorithm do not affect results and are absent.
+//
+// How this file states the algorithm.  A query's state is its pool C (a vector
+// kept in (key, id) order, each entry carrying an "expanded" mark) and its
+// visited set V (one byte per node).  A step is
+//   pick     the P closest pool entries that are not yet expanded and mark them
+//            (P = 1 is the paper's algorithm; stop when there is none);
+//   resolve  for every picked node, walk its adjacency row in stored order and
+//            decide from ids, labels and V alone which neighbours are new - the
+//            paper's deterministic access: no vector is touched before the whole
+//            row has been resolved; the new ones enter V at once;
+//   score    only now read the code rows of the new neighbours, one by one, and
+//            offer each to the pool (kept if the pool is not full or it beats
+//            the pool's last entry, which then falls out).
 //   labels: NULL -> every edge passes; otherwise [n][degree] edge labels, an
 //            edge is usable when label <= alpha_s (Section 4.3).
 //   m_s:    at most m_s neighbours are taken per expansion (<= 0: no cap).
-//   expansions_per_step: 1 is Algorithm 1.  P > 1 is the batched variant used
-//            by the GPU's fast mode (not in the paper): each step takes the P
-//            closest un-expanded pool entries, marks them expanded, collects
-//            their unvisited neighbours (entries in pool order, rows in stored
-//            order) and only then evaluates and inserts them.
+//   expansions_per_step: P above.  P > 1 is not in the paper: it is the
+//            multi-expansion mode of the GPU library, whose definition is the
+//            three phases above with P picks per step (picked nodes resolved in
+//            pool order, all of them before anything is scored).
 //   entries: NULL -> every query starts from `entry_point`; otherwise
 //            [nq][n_entry] per-query initial nodes I (duplicates skipped).
 //   out_ids/out_keys/out_idot: [nq][ef], final pool in (key, id) order, padded
 //            with id 0xFFFFFFFF, key +inf, idot 0.
 //   out_counts: [nq][4] = expansions, distance evaluations (= |V|), pool size, 0.
+//   out_visited: NULL, or [nq][n] bytes: 1 where the node's key was evaluated
+//            (the final V), for tests of properties that hold for any P.
+namespace {
+
+struct QueryState {
+  std::vector<Entry> pool;       // C, ascending (key, id)
+  std::vector<uint8_t> visited;  // V
+  uint32_t n_exp = 0, n_dist = 0;
+};
+
+// pick: ids of the (at most) P closest un-expanded pool entries, now marked.
+std::vector<uint32_t> pick_unexpanded(QueryState &st, int P) {
+  std::vector<uint32_t> picked;
+  for (Entry &e : st.pool) {
+    if ((int)picked.size() == P) break;
+    if (e.expanded) continue;
+    e.expanded = true;
+    picked.push_back(e.id);
+  }
+  return picked;
+}
+
+// resolve: the neighbours of u that become members of V with this expansion,
+// appended to `fresh` in stored order.  Ids, labels and V only.
+void resolve_row(QueryState &st, const uint32_t *row, const float *row_labels, int degree, float alpha_s, int m_s,
+                 std::vector<uint32_t> &fresh) {
+  int taken = 0;
+  for (int slot = 0; slot < degree && taken < m_s; ++slot) {
+    const uint32_t v = row[slot];
+    if (v == kPad) continue;                                    // unused slot
+    if (st.visited[v]) continue;                                // already in V
+    if (row_labels && !(row_labels[slot] <= alpha_s)) continue;  // edge pruned at this alpha_s
+    st.visited[v] = 1;
+    fresh.push_back(v);
+    ++taken;
+  }
+}
+
+// score: offer one evaluated node to the pool of capacity ef.
+void offer(QueryState &st, const Entry &e, int ef) {
+  ++st.n_dist;
+  if ((int)st.pool.size() >= ef && !entry_less(e, st.pool.back())) return;
+  st.pool.insert(std::upper_bound(st.pool.begin(), st.pool.end(), e, entry_less), e);
+  if ((int)st.pool.size() > ef) st.pool.pop_back();  // the farthest falls out for good (it stays in V)
+}
+
+}  // namespace
+
+extern "C" {
+
 void orc_search_batch(int64_t n, int32_t d, int32_t degree, int32_t metric, int32_t bits, const uint8_t *codes,
                       const float *lo, const float *delta, const float *norm_term, const uint32_t *adjacency,
                       uint32_t entry_point, const float *Q, int32_t nq, const uint32_t *entries, int32_t n_entry,
                       int32_t ef, const float *labels, float alpha_s, int32_t m_s, int32_t expansions_per_step,
-                      uint32_t *out_ids,
-                      float *out_keys, int32_t *out_idot, uint32_t *out_counts) {
+                      uint32_t *out_ids, float *out_keys, int32_t *out_idot, uint32_t *out_counts,
+                      uint8_t *out_visited) {
   const int rb = row_bytes(d, bits);
   if (m_s <= 0) m_s = degree;
-  std::vector<uint8_t> visited(n);
+  const int P = expansions_per_step > 1 ? expansions_per_step : 1;
   std::vector<int8_t> t(d);
-  std::vector<Entry> pool;
+  QueryState st;
   for (int32_t qi = 0; qi < nq; ++qi) {
-    const float *q = Q + (int64_t)qi * d;
     float s, qlo;
-    orc_query_prep(q, d, lo, delta, t.data(), &s, &qlo);
-    std::fill(visited.begin(), visited.end(), 0);
-    pool.clear();
-    uint32_t n_exp = 0, n_dist = 0;
-
-    auto evaluate_and_insert = [&](uint32_t v) {
-      int32_t idot = orc_idot(t.data(), codes + (int64_t)v * rb, d, bits);
-      float key = key_from_idot(metric, s, qlo, idot, norm_term ? norm_term[v] : 0.0f);
-      ++n_dist;
-      Entry e{key, v, idot, false};
-      if ((int)pool.size() >= ef && !entry_less(e, pool.back())) return;
-      auto pos = std::upper_bound(pool.begin(), pool.end(), e, entry_less);
-      pool.insert(pos, e);
-      if ((int)pool.size() > ef) pool.pop_back();  // drop the farthest
+    orc_query_prep(Q + (int64_t)qi * d, d, lo, delta, t.data(), &s, &qlo);
+    st.pool.clear();
+    st.visited.assign(n, 0);
+    st.n_exp = st.n_dist = 0;
+    auto scored = [&](uint32_t v) {
+      const int32_t idot = orc_idot(t.data(), codes + (int64_t)v * rb, d, bits);
+      return Entry{key_from_idot(metric, s, qlo, idot, norm_term ? norm_term[v] : 0.0f), v, idot, false};
     };
 
-    // initial nodes I go into the pool and into V
-    const uint32_t *I = entries ? entries + (int64_t)qi * n_entry : &entry_point;
-    const int nI = entries ? n_entry : 1;
-    for (int e = 0; e < nI; ++e) {
-      uint32_t v = I[e];
-      if (v == kPad || visited[v]) continue;
-      visited[v] = 1;
-      evaluate_and_insert(v);
-    }
+    // the initial nodes I are members of V from the start and are scored like
+    // any other node
+    std::vector<uint32_t> fresh;
+    if (entries)
+      resolve_row(st, entries + (int64_t)qi * n_entry, nullptr, n_entry, 0.0f, n_entry, fresh);
+    else
+      resolve_row(st, &entry_point, nullptr, 1, 0.0f, 1, fresh);
+    for (uint32_t v : fresh) offer(st, scored(v), ef);
 
-    const int P = expansions_per_step > 1 ? expansions_per_step : 1;
     for (;;) {
-      // the P closest un-expanded pool entries (P = 1: the closest)
-      std::vector<uint32_t> expand;
-      for (size_t p = 0; p < pool.size() && (int)expand.size() < P; ++p)
-        if (!pool[p].expanded) {
-          pool[p].expanded = true;
-          expand.push_back(pool[p].id);
-        }
-      if (expand.empty()) break;
-      n_exp += (uint32_t)expand.size();
-      // first pass over ids only: collect the unvisited neighbours N and mark them
-      std::vector<uint32_t> N;
-      for (uint32_t uid : expand) {
-        int taken = 0;
-        for (int slot = 0; slot < degree; ++slot) {
-          uint32_t v = adjacency[(int64_t)uid * degree + slot];
-          if (v == kPad || visited[v]) continue;
-          if (labels && !(labels[(int64_t)uid * degree + slot] <= alpha_s)) continue;
-          if (!(taken < m_s)) continue;
-          visited[v] = 1;
-          N.push_back(v);
-          ++taken;
-        }
-      }
-      // second pass: touch the vectors of N only
-      for (uint32_t v : N) evaluate_and_insert(v);
+      const std::vector<uint32_t> picked = pick_unexpanded(st, P);
+      if (picked.empty()) break;
+      st.n_exp += (uint32_t)picked.size();
+      fresh.clear();
+      for (uint32_t u : picked)
+        resolve_row(st, adjacency + (int64_t)u * degree, labels ? labels + (int64_t)u * degree : nullptr, degree,
+                    alpha_s, m_s, fresh);
+      for (uint32_t v : fresh) offer(st, scored(v), ef);
     }
 
     for (int p = 0; p < ef; ++p) {
-      bool have = p < (int)pool.size();
-      out_ids[(int64_t)qi * ef + p] = have ? pool[p].id : kPad;
-      out_keys[(int64_t)qi * ef + p] = have ? pool[p].key : INFINITY;
-      if (out_idot) out_idot[(int64_t)qi * ef + p] = have ? pool[p].idot : 0;
+      const bool have = p < (int)st.pool.size();
+      out_ids[(int64_t)qi * ef + p] = have ? st.pool[p].id : kPad;
+      out_keys[(int64_t)qi * ef + p] = have ? st.pool[p].key : INFINITY;
+      if (out_idot) out_idot[(int64_t)qi * ef + p] = have ? st.pool[p].idot : 0;
     }
     if (out_counts) {
-      out_counts[(int64_t)qi * 4 + 0] = n_exp;
-      out_counts[(int64_t)qi * 4 + 1] = n_dist;
-      out_counts[(int64_t)qi * 4 + 2] = (uint32_t)pool.size();
+      out_counts[(int64_t)qi * 4 + 0] = st.n_exp;
+      out_counts[(int64_t)qi * 4 + 1] = st.n_dist;
+      out_counts[(int64_t)qi * 4 + 2] = (uint32_t)st.pool.size();
       out_counts[(int64_t)qi * 4 + 3] = 0;
     }
+    if (out_visited) std::memcpy(out_visited + (int64_t)qi * n, st.visited.data(), (size_t)n);
   }
 }
 

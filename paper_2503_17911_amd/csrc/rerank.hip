@@ -1,6 +1,7 @@
-// Candidate re-evaluation: the exact fp32 rerank that ends Algorithm 1 (the
-// paper's line "re-rank C with tau_l and tau_h", here over a fixed-length
-// prefix of the pool) and the rescore with a finer code level.  One query per
+// Candidate re-evaluation: the exact fp32 rerank that ends Algorithm 1 (its
+// last step orders the pool by the high-precision distance; here that is done
+// over a fixed-length prefix of the pool) and the rescore with a finer code
+// level.  One query per
 // wavefront; candidates are ordered by ranking every (value, id) pair against
 // all others in LDS.
 #include "ann_internal.hpp"

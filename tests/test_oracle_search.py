@@ -31,6 +31,47 @@ def test_ring_hand_trace():
     assert cnt[0, 2] == len(g["final_pool"])
 
 
+def line_case(positions):
+    """Points (pos, 0) and a query at the origin: keys are ordered like pos^2."""
+    X = np.zeros((len(positions), 2), np.float32)
+    X[:, 0] = positions
+    return X, oracle.sq_fit(X, 8)
+
+
+def test_ring_hand_trace_two_expansions_per_step():
+    """P = 2 on the ring, traced by hand in the golden file: other counters and
+    another visited set than P = 1 (which the same file also states)."""
+    g = read_golden("ring12_trace_p2.txt")
+    n = int(g["n"][0])
+    X, lv = line_case(np.arange(n))
+    adj = np.stack([(np.arange(n) + 1) % n, (np.arange(n) - 1) % n], 1).astype(np.uint32)
+    q = np.array([[float(v) for v in g["query"]]], np.float32)
+    ef, entry = int(g["ef"][0]), int(g["entry"][0])
+    ids, keys, dots, cnt, vis = oracle.search_batch(lv, 2, adj, entry, q, ef, want_visited=True,
+                                                    expansions_per_step=int(g["expansions_per_step"][0]))
+    assert ids[0].tolist() == [int(v) for v in g["final_pool"]]
+    assert cnt[0].tolist() == [int(g["n_expansions"][0]), int(g["n_distance_evaluations"][0]), ef, 0]
+    assert np.nonzero(vis[0])[0].tolist() == [int(v) for v in g["visited"]]
+    ids1, _, _, cnt1 = oracle.search_batch(lv, 2, adj, entry, q, ef)
+    assert ids1[0].tolist() == [int(v) for v in g["final_pool"]]
+    assert cnt1[0, :2].tolist() == [int(g["p1_n_expansions"][0]), int(g["p1_n_distance_evaluations"][0])]
+
+
+def test_fork_hand_trace_where_two_expansions_change_the_result():
+    """A graph drawn so that P = 2 reaches a node that P = 1 never does (the
+    second-closest entry is expanded before the first one's neighbours can push
+    it out).  Both walks are written out by hand in the golden file."""
+    g = read_golden("fork_trace_p2.txt")
+    X, lv = line_case([float(v) for v in g["positions"]])
+    adj = np.array([PAD if v == "-" else int(v) for v in g["adjacency"]], np.uint32).reshape(len(X), 2)
+    q = np.zeros((1, 2), np.float32)
+    ef, entry = int(g["ef"][0]), int(g["entry"][0])
+    for P, tag in ((1, "p1"), (2, "p2"), (4, "p2")):       # more than 2 picks never exist here: P = 4 walks like P = 2
+        ids, _, _, cnt = oracle.search_batch(lv, 2, adj, entry, q, ef, expansions_per_step=P)
+        assert ids[0].tolist() == [int(v) for v in g[tag + "_final_pool"]], P
+        assert cnt[0, :2].tolist() == [int(g[tag + "_n_expansions"][0]), int(g[tag + "_n_distance_evaluations"][0])], P
+
+
 def test_label_filter_paper_example():
     """Section 4.3 worked example: 5 neighbours, m_s=3, alpha_s=1.2, 2nd label 1.4."""
     g = read_golden("label_filter_example.txt")
@@ -51,14 +92,15 @@ def test_label_filter_paper_example():
     assert cnt[0, 1] == 1 + len(g["visited"])
 
 
+@pytest.mark.parametrize("P", [1, 2, 4])
 @pytest.mark.parametrize("metric,bits", [(oracle.L2, 8), (oracle.IP, 8), (oracle.L2, 4)])
-def test_ef_at_least_n_is_bruteforce_under_tau_l(metric, bits):
+def test_ef_at_least_n_is_bruteforce_under_tau_l(metric, bits, P):
     """With ef >= N on a graph where every node is reachable the final pool is
-    every node, ordered by (key, id)."""
+    every node, ordered by (key, id) - however many entries a step expands."""
     w, X, Q, adj = small_case(300, 16, 6, 5, seed=11, bits=bits)
     assert inputs.count_reachable(adj, 0) == 300
     lv = oracle.sq_fit(X, bits)
-    ids, keys, dots, cnt = oracle.search_batch(lv, w.d, adj, 0, Q, 320, metric=metric)
+    ids, keys, dots, cnt = oracle.search_batch(lv, w.d, adj, 0, Q, 320, metric=metric, expansions_per_step=P)
     for qi in range(len(Q)):
         k = all_keys(lv, w.d, Q[qi], metric)
         order = np.lexsort((np.arange(300), k))
@@ -68,19 +110,52 @@ def test_ef_at_least_n_is_bruteforce_under_tau_l(metric, bits):
         assert cnt[qi].tolist() == [300, 300, 300, 0]
 
 
-def test_complete_graph_one_expansion_sees_everything():
+@pytest.mark.parametrize("P", [1, 2, 4])
+def test_complete_graph_one_expansion_sees_everything(P):
     n, ef = 40, 7
     w = inputs.Workload("cg", n, 8, 3, 0.3, 4, seed=3)
     X, Q = inputs.base_vectors(w), inputs.queries(w)
     adj = np.array([[j for j in range(n) if j != i] for i in range(n)], np.uint32)
     lv = oracle.sq_fit(X, 8)
-    ids, keys, dots, cnt = oracle.search_batch(lv, w.d, adj, 5, Q, ef)
+    ids, keys, dots, cnt = oracle.search_batch(lv, w.d, adj, 5, Q, ef, expansions_per_step=P)
     for qi in range(len(Q)):
         k = all_keys(lv, w.d, Q[qi], oracle.L2)
         order = np.lexsort((np.arange(n), k))[:ef]
         assert ids[qi].tolist() == order.tolist()
         assert cnt[qi, 1] == n                  # everything evaluated once
         assert cnt[qi, 0] in (ef, ef + 1)       # entry + survivors (entry may or may not survive)
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 4])
+@pytest.mark.parametrize("metric,bits,ef", [(oracle.L2, 8, 10), (oracle.IP, 8, 33), (oracle.L2, 4, 64)])
+def test_properties_that_hold_for_any_number_of_expansions_per_step(metric, bits, ef, P):
+    """Whatever P is: (1) the pool is the ef smallest (key, id) pairs over the
+    set V of evaluated nodes, keys recomputed here one by one (the pool's
+    maximum only falls, so nothing that was pushed out could come back);
+    (2) every node of the final pool was expanded, so all its neighbours are in
+    V; (3) V holds the initial node; (4) the counters say |V| and at least
+    |pool| expansions; (5) every member of V is a neighbour of a member of V
+    or the initial node (nothing is evaluated that the walk did not reach)."""
+    w, X, Q, adj = small_case(1500, 24, 10, 12, seed=5 + bits, bits=bits, normalize=(metric == oracle.IP))
+    lv = oracle.sq_fit(X, bits)
+    entry = 7
+    ids, keys, dots, cnt, vis = oracle.search_batch(lv, w.d, adj, entry, Q, ef, metric=metric, expansions_per_step=P,
+                                                    want_visited=True)
+    for qi in range(len(Q)):
+        k = all_keys(lv, w.d, Q[qi], metric)
+        V = np.nonzero(vis[qi])[0]
+        best = sorted((float(k[v]), int(v)) for v in V)[:ef]
+        assert ids[qi, :len(best)].tolist() == [v for _, v in best]
+        assert keys[qi, :len(best)].tolist() == [kv for kv, _ in best]
+        assert vis[qi, entry] == 1 and cnt[qi, 1] == len(V) and cnt[qi, 2] == len(best) <= cnt[qi, 0]
+        for v in ids[qi, :len(best)]:
+            row = adj[v][adj[v] != PAD]
+            assert vis[qi, row].all()
+        reached = np.zeros(w.n, bool)
+        reached[entry] = True
+        rows = adj[V]
+        reached[rows[rows != PAD]] = True
+        assert reached[V].all()
 
 
 @pytest.mark.parametrize("seed", range(6))
