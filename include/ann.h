@@ -28,9 +28,10 @@
  *     follow each other as stream order says.  An index keeps up to 8 such
  *     workspaces; a 9th stream takes over the least recently used one after a
  *     device-wide wait.  A workspace grows (hipMalloc, device-wide wait) when a
- *     batch is larger than any before it on that stream.  Calls for one index
- *     may come from several host threads as long as no two of them use the
- *     same stream at once.
+ *     batch is larger than any before it on that stream; ann_reserve_workspace
+ *     sizes it ahead of time, after which no call on that stream allocates for
+ *     batches up to the reserved size.  Calls for one index may come from
+ *     several host threads as long as no two of them use the same stream at once.
  */
 #ifndef ANN_H_
 #define ANN_H_
@@ -227,6 +228,17 @@ ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index 
 ann_status ann_free_index(ann_index *index); /* synchronises the device; NULL is a no-op */
 
 /*
+ * Size the folded-query workspaces of `stream` (every code level of the index)
+ * for batches of up to max_nq queries, so that the calls that fold queries
+ * (ann_search_batch, ann_entry_scan, ann_query_prep, ann_rescore) never
+ * allocate on that stream for nq <= max_nq: Algorithm 1's per-query state is
+ * then set up without touching the allocator.  May allocate and wait for the
+ * device; call it once after ann_upload_index, per stream that will be used.
+ * Errors: ANN_EINVAL (NULL index, max_nq == 0), ANN_ENOMEM, ANN_EDEVICE.
+ */
+ann_status ann_reserve_workspace(ann_index *index, uint32_t max_nq, void *stream);
+
+/*
  * Query folding for one code level (the query side of the low-precision
  * distance; paper Section 5.2 precomputes the query terms before the search):
  * a_j = delta_j * q_j, s = max|a| / 127, t_j = rint(a_j * 127 / max|a|) as
@@ -299,7 +311,7 @@ ann_status ann_schedule_queries(const uint32_t *keys, uint32_t nq, uint32_t key_
  * for ef, ANN_VISITED_CACHE together with m_s below the degree),
  * ANN_ECAPACITY (ef > ANN_MAX_EF, n_entry > ANN_MAX_ENTRIES), ANN_ENOMEM when
  * the per-index workspace has to grow for a larger nq (the only allocation on
- * this path), ANN_EDEVICE.
+ * this path; none after ann_reserve_workspace), ANN_EDEVICE.
  */
 ann_status ann_search_batch(ann_index *index, const float *q, uint32_t nq, const ann_search_params *params,
                             const uint32_t *entry_ids, uint32_t n_entry, uint32_t *out_ids, float *out_keys,

@@ -27,7 +27,8 @@ _STATUS_NAMES = ["ANN_OK", "ANN_EINVAL", "ANN_ENOMEM", "ANN_EDEVICE", "ANN_EUNSU
 
 EXPORTED_SYMBOLS = ["ann_sq_train", "ann_sq_train_truncated", "ann_sq_encode", "ann_upload_index", "ann_free_index", "ann_query_prep",
                     "ann_search_batch", "ann_rescore", "ann_rerank", "ann_bruteforce_topk", "ann_build_entry_table",
-                    "ann_entry_scan", "ann_build_prs", "ann_schedule_queries", "ann_last_error", "ann_version"]
+                    "ann_entry_scan", "ann_build_prs", "ann_schedule_queries", "ann_reserve_workspace",
+                    "ann_last_error", "ann_version"]
 
 
 class AnnError(RuntimeError):
@@ -72,6 +73,7 @@ def _load_library() -> ctypes.CDLL:
     lib.ann_free_index.argtypes = [vp]
     lib.ann_query_prep.argtypes = [vp, u32, vp, u32, vp, vp, vp, vp]
     lib.ann_search_batch.argtypes = [vp, vp, u32, ctypes.POINTER(SearchParams), vp, u32, vp, vp, vp, vp, vp]
+    lib.ann_reserve_workspace.argtypes = [vp, u32, vp]
     lib.ann_rescore.argtypes = [vp, u32, vp, u32, vp, u32, u32, vp, vp, vp, vp]
     lib.ann_rerank.argtypes = [vp, vp, u32, vp, u32, u32, u32, vp, vp, vp]
     lib.ann_bruteforce_topk.argtypes = [vp, u64, u32, vp, u32, u32, u32, vp, vp, vp]
@@ -158,6 +160,10 @@ def ann_query_prep(index, level, q, nq, t, s, qlo, stream=None):
     _check(_lib.ann_query_prep(index, level, _ptr(q), nq, _ptr(t), _ptr(s), _ptr(qlo), stream))
 
 
+def ann_reserve_workspace(index, max_nq, stream=None):
+    _check(_lib.ann_reserve_workspace(index, max_nq, stream))
+
+
 def ann_search_batch(index, q, nq, *, k, ef, out_ids, out_keys=None, out_idot=None, out_counts=None, mode=0,
                      expansions_per_step=0, visited_slots=0, alpha_s=0.0, m_s=0, layout=0, visited_kind=0, query_order=None,
                      reuse_folded_queries=False, ef_per_query=None, entry_ids=None,
@@ -165,8 +171,9 @@ def ann_search_batch(index, q, nq, *, k, ef, out_ids, out_keys=None, out_idot=No
     p = SearchParams(k=k, ef=ef, mode=mode, expansions_per_step=expansions_per_step, visited_slots=visited_slots,
                      alpha_s=alpha_s, m_s=m_s, layout=layout, visited_kind=visited_kind, query_order=_ptr(query_order),
                      reuse_folded_queries=int(bool(reuse_folded_queries)), ef_per_query=_ptr(ef_per_query))
-    _check(_lib.ann_search_batch(index, _ptr(q), nq, ctypes.byref(p), _ptr(entry_ids), n_entry, _ptr(out_ids),
-                                 _ptr(out_keys), _ptr(out_idot), _ptr(out_counts), stream))
+    fn = _lib.ann_search_batch
+    _check(fn(index, _ptr(q), nq, ctypes.byref(p), _ptr(entry_ids), n_entry, _ptr(out_ids),
+              _ptr(out_keys), _ptr(out_idot), _ptr(out_counts), stream))
 
 
 def ann_rescore(index, level, q, nq, cand_ids, n_cand, cand_stride, out_ids, out_keys=None, out_idot=None,

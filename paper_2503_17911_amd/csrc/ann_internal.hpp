@@ -87,14 +87,24 @@ inline uint32_t tq_stride_for(const LevelDev &L) {
   return chunks * (L.bits == 8 ? 16u : 32u);
 }
 
-// The workspace of (level, stream), holding at least nq queries; *out is
-// valid until the index is destroyed or the stream's set is recycled (which
-// happens only when more than kMaxStreamWorkspaces streams have used the index,
-// after a device-wide wait).
-ann_status workspace_for(ann_index *index, uint32_t level, uint32_t nq, hipStream_t stream, Workspace **out);
-// Folds a batch into the workspace of (level, stream) and returns that
-// workspace in *ws_out when ws_out is given.
+// A workspace together with the lock on the index's stream -> workspace
+// table.  The holder keeps it until everything that reads or writes the
+// workspace has been enqueued: a stream beyond kMaxStreamWorkspaces takes a
+// set over only under this lock and after a device-wide wait, so work that was
+// enqueued while a lease was held never sees its buffers change hands.
+struct WorkspaceLease {
+  std::unique_lock<std::mutex> lock;
+  Workspace *ws = nullptr;
+};
+
+// The workspace of (level, stream), holding at least nq queries.
+ann_status workspace_for(ann_index *index, uint32_t level, uint32_t nq, hipStream_t stream, WorkspaceLease &lease);
+// Folds a batch into the given buffers (no allocation, no table lookup).
+ann_status launch_query_prep_into(const ann_index *index, uint32_t level, const float *q, uint32_t nq,
+                                  const Workspace &w, int8_t *t_plain, float *s_out, float *qlo_out,
+                                  hipStream_t stream);
+// Folds a batch into the workspace of (level, stream), which `lease` then holds.
 ann_status launch_query_prep(ann_index *index, uint32_t level, const float *q, uint32_t nq, int8_t *t_plain,
-                             float *s_out, float *qlo_out, hipStream_t stream, const Workspace **ws_out = nullptr);
+                             float *s_out, float *qlo_out, hipStream_t stream, WorkspaceLease &lease);
 
 }  // namespace ann

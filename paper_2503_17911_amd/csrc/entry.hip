@@ -280,13 +280,13 @@ ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_
   if (index->n_pivots == 0) return fail(ANN_EINVAL, "ann_entry_scan: call ann_build_entry_table first");
   if (nq == 0 || n_entry == 0) return fail(ANN_EINVAL, "ann_entry_scan: nq and n_entry must be positive");
   if (n_entry > (uint32_t)kScanKeep) return fail(ANN_ECAPACITY, "ann_entry_scan: n_entry = %u exceeds %d", n_entry, kScanKeep);
-  const Workspace *wp = nullptr;
+  WorkspaceLease lease;
   const LevelDev &L = index->level[0];
   if (L.bits == 8 && n_entry == 1 && index->d <= (uint32_t)kFsMaxD) {
     // folding and scan in one launch, on the matrix cores
-    Workspace *fw = nullptr;
-    ann_status rc = workspace_for(index, 0, nq, st, &fw);
+    ann_status rc = workspace_for(index, 0, nq, st, lease);
     if (rc != ANN_OK) return rc;
+    Workspace *fw = lease.ws;
     const size_t smem = (size_t)kFsQueries * (index->d + 1) * sizeof(double) + 4 * kFsQueries * sizeof(uint64_t) +
                         3 * kFsQueries * 4 + (size_t)kFsQueries * (L.row_stride + 8);
     if (smem > 48 * 1024) {
@@ -302,9 +302,9 @@ ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_
     fw->folded_nq = nq;
     return ANN_OK;
   }
-  ann_status rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st, &wp);
+  ann_status rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st, lease);
   if (rc != ANN_OK) return rc;
-  const Workspace &w = *wp;
+  const Workspace &w = *lease.ws;
 #define ANN_ES(B, P)                                                                                                   \
   entry_scan_kernel<B, P><<<nq, 64, 0, st>>>(index->pivot_codes, index->pivot_norm, index->pivot_ids, index->n_pivots,   \
                                              L.row_stride, L.row_stride / 16, index->metric, w.tq, w.tq_stride, w.s,    \

@@ -142,8 +142,8 @@ inline int grid_for(uint64_t total, int block) {
 
 }  // namespace
 
-ann_status workspace_for(ann_index *ix, uint32_t level, uint32_t nq, hipStream_t st, Workspace **out) {
-  std::lock_guard<std::mutex> lock(ix->ws_mutex);
+ann_status workspace_for(ann_index *ix, uint32_t level, uint32_t nq, hipStream_t st, WorkspaceLease &lease) {
+  if (!lease.lock.owns_lock()) lease.lock = std::unique_lock<std::mutex>(ix->ws_mutex);
   StreamWorkspaces *sw = nullptr, *free_slot = nullptr, *oldest = nullptr;
   for (StreamWorkspaces &c : ix->stream_ws) {
     if (c.used && c.stream == st) {
@@ -168,10 +168,11 @@ ann_status workspace_for(ann_index *ix, uint32_t level, uint32_t nq, hipStream_t
   }
   sw->last_use = ++ix->ws_clock;
   Workspace &w = sw->ws[level];
-  *out = &w;
+  lease.ws = &w;
   if (nq <= w.nq_cap) return ANN_OK;
-  // growth is the only allocation on the search path; it waits for work that
-  // may still be using the old buffers
+  // growth is the only allocation on the search path (ann_reserve_workspace
+  // moves it out of the path); it waits for work that may still be using the
+  // old buffers
   ANN_HIP(hipDeviceSynchronize());
   free_workspace(w);
   uint32_t cap = nq < 1024 ? 1024 : nq;
@@ -359,6 +360,17 @@ ann_status ann_build_prs(ann_index *index, void *stream) {
                                                          slots, index->n, L.row_stride, index->prs_codes, index->prs_norm);
   ANN_HIP(hipGetLastError());
   ANN_HIP(hipStreamSynchronize(st));
+  return ANN_OK;
+}
+
+ann_status ann_reserve_workspace(ann_index *index, uint32_t max_nq, void *stream) {
+  if (!index) return fail(ANN_EINVAL, "ann_reserve_workspace: index is NULL");
+  if (max_nq == 0) return fail(ANN_EINVAL, "ann_reserve_workspace: max_nq == 0");
+  WorkspaceLease lease;
+  for (uint32_t l = 0; l < index->n_levels; ++l) {
+    ann_status rc = workspace_for(index, l, max_nq, (hipStream_t)stream, lease);
+    if (rc != ANN_OK) return rc;
+  }
   return ANN_OK;
 }
 

@@ -286,11 +286,11 @@ ann_status ann_rescore(ann_index *index, uint32_t level, const float *q, uint32_
   if (nq == 0 || n_cand == 0) return fail(ANN_EINVAL, "ann_rescore: nq and n_cand must be positive");
   if (cand_stride < n_cand) return fail(ANN_EINVAL, "ann_rescore: cand_stride = %u < n_cand = %u", cand_stride, n_cand);
   if (n_cand > 4096) return fail(ANN_ECAPACITY, "ann_rescore: n_cand = %u exceeds 4096", n_cand);
-  const Workspace *wp = nullptr;
-  ann_status rc = launch_query_prep(index, level, q, nq, nullptr, nullptr, nullptr, st, &wp);
+  WorkspaceLease lease;
+  ann_status rc = launch_query_prep(index, level, q, nq, nullptr, nullptr, nullptr, st, lease);
   if (rc != ANN_OK) return rc;
   const LevelDev &L = index->level[level];
-  const Workspace &w = *wp;
+  const Workspace &w = *lease.ws;
   const float *norm = index->metric == ANN_L2 ? L.norm_term : nullptr;
   const size_t smem = (size_t)n_cand * (sizeof(uint64_t) + sizeof(int32_t));
 #define ANN_RS(B, P)                                                                                              \

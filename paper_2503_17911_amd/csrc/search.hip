@@ -5,34 +5,42 @@
 
 using namespace ann;
 
-extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_t nq, const ann_search_params *params,
-                                       const uint32_t *entry_ids, uint32_t n_entry, uint32_t *out_ids, float *out_keys,
-                                       int32_t *out_idot, uint32_t *out_counts, void *stream) {
-  hipStream_t st = (hipStream_t)stream;
-  if (!index || !q || !params || !out_ids) return fail(ANN_EINVAL, "ann_search_batch: NULL argument");
-  if (nq == 0) return fail(ANN_EINVAL, "ann_search_batch: nq == 0");
-  if (params->k == 0) return fail(ANN_EINVAL, "ann_search_batch: k == 0");
-  if (params->ef < params->k) return fail(ANN_EINVAL, "ann_search_batch: ef = %u < k = %u", params->ef, params->k);
-  if (params->ef > ANN_MAX_EF) return fail(ANN_ECAPACITY, "ann_search_batch: ef = %u exceeds ANN_MAX_EF = %u", params->ef, ANN_MAX_EF);
-  if (params->layout > 1) return fail(ANN_EINVAL, "ann_search_batch: unknown layout %u", params->layout);
-  if (params->layout == 1 && !index->prs_codes) return fail(ANN_EINVAL, "ann_search_batch: layout 1 needs ann_build_prs first");
+namespace {
+
+// What the argument checks settle before anything is launched.
+struct SearchPlan {
+  uint32_t p = 1, vis_log2 = 0;
+  bool cache = false, wide = false;
+};
+
+ann_status check_search_args(const char *fn, const ann_index *index, const float *q, uint32_t nq,
+                             const ann_search_params *params, const uint32_t *entry_ids, uint32_t n_entry,
+                             const uint32_t *out_ids, SearchPlan &plan) {
+
+  if (!index || !q || !params || !out_ids) return fail(ANN_EINVAL, "%s: NULL argument", fn);
+  if (nq == 0) return fail(ANN_EINVAL, "%s: nq == 0", fn);
+  if (params->k == 0) return fail(ANN_EINVAL, "%s: k == 0", fn);
+  if (params->ef < params->k) return fail(ANN_EINVAL, "%s: ef = %u < k = %u", fn, params->ef, params->k);
+  if (params->ef > ANN_MAX_EF) return fail(ANN_ECAPACITY, "%s: ef = %u exceeds ANN_MAX_EF = %u", fn, params->ef, ANN_MAX_EF);
+  if (params->layout > 1) return fail(ANN_EINVAL, "%s: unknown layout %u", fn, params->layout);
+  if (params->layout == 1 && !index->prs_codes) return fail(ANN_EINVAL, "%s: layout 1 needs ann_build_prs first", fn);
   if (params->layout == 1 && (params->alpha_s > 0.0f || (params->m_s != 0 && params->m_s < index->degree)))
-    return fail(ANN_EUNSUPPORTED, "ann_search_batch: the edge filter is not available with the redundant layout");
-  if (!(params->alpha_s >= 0.0f)) return fail(ANN_EINVAL, "ann_search_batch: alpha_s must be >= 0");
-  if (params->alpha_s > 0.0f && !index->labels) return fail(ANN_EINVAL, "ann_search_batch: alpha_s given but the index was uploaded without edge labels");
-  if (params->mode > 1) return fail(ANN_EINVAL, "ann_search_batch: unknown mode %u", params->mode);
-  if (params->mode == 0 && params->expansions_per_step > 1) return fail(ANN_EINVAL, "ann_search_batch: expansions_per_step needs mode 1");
-  if (params->expansions_per_step > (uint32_t)kMaxExpansionsPerStep) return fail(ANN_ECAPACITY, "ann_search_batch: expansions_per_step = %u exceeds %d", params->expansions_per_step, kMaxExpansionsPerStep);
+    return fail(ANN_EUNSUPPORTED, "%s: the edge filter is not available with the redundant layout", fn);
+  if (!(params->alpha_s >= 0.0f)) return fail(ANN_EINVAL, "%s: alpha_s must be >= 0", fn);
+  if (params->alpha_s > 0.0f && !index->labels) return fail(ANN_EINVAL, "%s: alpha_s given but the index was uploaded without edge labels", fn);
+  if (params->mode > 1) return fail(ANN_EINVAL, "%s: unknown mode %u", fn, params->mode);
+  if (params->mode == 0 && params->expansions_per_step > 1) return fail(ANN_EINVAL, "%s: expansions_per_step needs mode 1", fn);
+  if (params->expansions_per_step > (uint32_t)kMaxExpansionsPerStep) return fail(ANN_ECAPACITY, "%s: expansions_per_step = %u exceeds %d", fn, params->expansions_per_step, kMaxExpansionsPerStep);
   const uint32_t p = params->mode == 0 ? 1u : (params->expansions_per_step ? params->expansions_per_step : (uint32_t)kMaxExpansionsPerStep);
-  if (entry_ids && n_entry == 0) return fail(ANN_EINVAL, "ann_search_batch: entry_ids given with n_entry == 0");
-  if (entry_ids && n_entry > ANN_MAX_ENTRIES) return fail(ANN_ECAPACITY, "ann_search_batch: n_entry = %u exceeds ANN_MAX_ENTRIES = %u", n_entry, ANN_MAX_ENTRIES);
+  if (entry_ids && n_entry == 0) return fail(ANN_EINVAL, "%s: entry_ids given with n_entry == 0", fn);
+  if (entry_ids && n_entry > ANN_MAX_ENTRIES) return fail(ANN_ECAPACITY, "%s: n_entry = %u exceeds ANN_MAX_ENTRIES = %u", fn, n_entry, ANN_MAX_ENTRIES);
 
   const uint32_t ef = params->ef;
   const bool capped = params->m_s != 0 && params->m_s < index->degree;
-  if (params->visited_kind > ANN_VISITED_CACHE_WIDE) return fail(ANN_EINVAL, "ann_search_batch: unknown visited_kind %u", params->visited_kind);
+  if (params->visited_kind > ANN_VISITED_CACHE_WIDE) return fail(ANN_EINVAL, "%s: unknown visited_kind %u", fn, params->visited_kind);
   const bool wide = params->visited_kind == ANN_VISITED_CACHE_WIDE;
   if ((params->visited_kind == ANN_VISITED_CACHE || wide) && capped)
-    return fail(ANN_EINVAL, "ann_search_batch: the cap m_s needs ANN_VISITED_TABLE (its choice of neighbours depends on the visited set)");
+    return fail(ANN_EINVAL, "%s: the cap m_s needs ANN_VISITED_TABLE (its choice of neighbours depends on the visited set)", fn);
   const bool cache = params->visited_kind == ANN_VISITED_CACHE || wide || (params->visited_kind == ANN_VISITED_AUTO && !capped);
   // the table must hold the pool and one step's candidates below 3/4 load
   // after a rebuild; the cache has no such minimum
@@ -51,28 +59,27 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
     if (vis_log2 < min_log2) vis_log2 = min_log2;
   } else {
     uint32_t v = params->visited_slots;
-    if (v & (v - 1)) return fail(ANN_EINVAL, "ann_search_batch: visited_slots = %u is not a power of two", v);
+    if (v & (v - 1)) return fail(ANN_EINVAL, "%s: visited_slots = %u is not a power of two", fn, v);
     vis_log2 = 0;
     while ((1u << vis_log2) < v) ++vis_log2;
-    if (vis_log2 < min_log2) return fail(ANN_EINVAL, "ann_search_batch: visited_slots = %u is below the minimum %u for ef = %u", v, 1u << min_log2, ef);
+    if (vis_log2 < min_log2) return fail(ANN_EINVAL, "%s: visited_slots = %u is below the minimum %u for ef = %u", fn, v, 1u << min_log2, ef);
   }
-  if (vis_log2 > 13) return fail(ANN_ECAPACITY, "ann_search_batch: the visited set would need more than 8192 slots");
+  if (vis_log2 > 13) return fail(ANN_ECAPACITY, "%s: the visited set would need more than 8192 slots", fn);
+  plan.p = p;
+  plan.vis_log2 = vis_log2;
+  plan.cache = cache;
+  plan.wide = wide;
+  return ANN_OK;
+}
 
-  const Workspace *wp = nullptr;
-  if (params->reuse_folded_queries) {
-    Workspace *mine = nullptr;
-    ann_status rc = workspace_for(index, 0, nq, st, &mine);
-    if (rc != ANN_OK) return rc;
-    if (mine->folded_q != q || mine->folded_nq != nq)
-      return fail(ANN_EINVAL, "ann_search_batch: reuse_folded_queries, but the last folding for this index on this stream was of another batch");
-    wp = mine;
-  } else {
-    ann_status rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st, &wp);
-    if (rc != ANN_OK) return rc;
-  }
-
+// Launch of the search kernel for a batch whose folded queries are in `w`.
+ann_status launch_search_with(const ann_index *index, uint32_t nq, const ann_search_params *params,
+                              const SearchPlan &plan, const uint32_t *entry_ids, uint32_t n_entry, uint32_t *out_ids,
+                              float *out_keys, int32_t *out_idot, uint32_t *out_counts, const Workspace &w,
+                              hipStream_t st) {
+  const uint32_t ef = params->ef, p = plan.p, vis_log2 = plan.vis_log2;
+  const bool cache = plan.cache, wide = plan.wide;
   const LevelDev &L = index->level[0];
-  const Workspace &w = *wp;
   SearchArgs a{};
   a.codes = L.codes;
   a.norm_term = index->metric == ANN_L2 ? L.norm_term : nullptr;
@@ -116,4 +123,29 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   const bool fast = packed && !a.filtered && !a.prs_codes && (!multi || (index->degree <= 32 && p == (uint32_t)kMaxExpansionsPerStep));
   return fast ? launch_search_fast(a, L.bits, L.search_lanes, m, multi, st)
               : launch_search_general(a, L.bits, L.search_lanes, m, multi, st);
+}
+
+}  // namespace
+
+
+
+extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_t nq, const ann_search_params *params,
+                                       const uint32_t *entry_ids, uint32_t n_entry, uint32_t *out_ids, float *out_keys,
+                                       int32_t *out_idot, uint32_t *out_counts, void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  SearchPlan plan;
+  ann_status rc = check_search_args("ann_search_batch", index, q, nq, params, entry_ids, n_entry, out_ids, plan);
+  if (rc != ANN_OK) return rc;
+  WorkspaceLease lease;  // held until the search kernel is enqueued
+  if (params->reuse_folded_queries) {
+    rc = workspace_for(index, 0, nq, st, lease);
+    if (rc != ANN_OK) return rc;
+    if (lease.ws->folded_q != q || lease.ws->folded_nq != nq)
+      return fail(ANN_EINVAL, "ann_search_batch: reuse_folded_queries, but the last folding for this index on this stream was of another batch");
+  } else {
+    rc = launch_query_prep(index, 0, q, nq, nullptr, nullptr, nullptr, st, lease);
+    if (rc != ANN_OK) return rc;
+  }
+  return launch_search_with(index, nq, params, plan, entry_ids, n_entry, out_ids, out_keys, out_idot, out_counts,
+                            *lease.ws, st);
 }

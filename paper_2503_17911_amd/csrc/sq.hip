@@ -214,23 +214,28 @@ __global__ __launch_bounds__(64) void query_prep_kernel(const float *__restrict_
   }
 }
 
-ann_status launch_query_prep(ann_index *ix, uint32_t level, const float *q, uint32_t nq, int8_t *t_plain, float *s_out,
-                             float *qlo_out, hipStream_t st, const Workspace **ws_out) {
-  Workspace *wp = nullptr;
-  ann_status rc = workspace_for(ix, level, nq, st, &wp);
-  if (rc != ANN_OK) return rc;
+ann_status launch_query_prep_into(const ann_index *ix, uint32_t level, const float *q, uint32_t nq, const Workspace &w,
+                                  int8_t *t_plain, float *s_out, float *qlo_out, hipStream_t st) {
   const LevelDev &L = ix->level[level];
-  Workspace &w = *wp;
+  const size_t smem = (size_t)ix->d * sizeof(double);
   if (L.bits == 8)
-    query_prep_kernel<8><<<nq, 64, (size_t)ix->d * sizeof(double), st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t, t_plain,
-                                            s_out, qlo_out);
+    query_prep_kernel<8><<<nq, 64, smem, st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t,
+                                               t_plain, s_out, qlo_out);
   else
-    query_prep_kernel<4><<<nq, 64, (size_t)ix->d * sizeof(double), st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t, t_plain,
-                                            s_out, qlo_out);
+    query_prep_kernel<4><<<nq, 64, smem, st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t,
+                                               t_plain, s_out, qlo_out);
   ANN_HIP(hipGetLastError());
-  w.folded_q = q;
-  w.folded_nq = nq;
-  if (ws_out) *ws_out = wp;
+  return ANN_OK;
+}
+
+ann_status launch_query_prep(ann_index *ix, uint32_t level, const float *q, uint32_t nq, int8_t *t_plain, float *s_out,
+                             float *qlo_out, hipStream_t st, WorkspaceLease &lease) {
+  ann_status rc = workspace_for(ix, level, nq, st, lease);
+  if (rc != ANN_OK) return rc;
+  rc = launch_query_prep_into(ix, level, q, nq, *lease.ws, t_plain, s_out, qlo_out, st);
+  if (rc != ANN_OK) return rc;
+  lease.ws->folded_q = q;
+  lease.ws->folded_nq = nq;
   return ANN_OK;
 }
 
@@ -333,7 +338,8 @@ ann_status ann_query_prep(ann_index *index, uint32_t level, const float *q, uint
   if (!index || !q) return fail(ANN_EINVAL, "ann_query_prep: NULL argument");
   if (level >= index->n_levels) return fail(ANN_EINVAL, "ann_query_prep: level %u not in the index", level);
   if (nq == 0) return fail(ANN_EINVAL, "ann_query_prep: nq == 0");
-  return launch_query_prep(index, level, q, nq, t, s, qlo, (hipStream_t)stream);
+  WorkspaceLease lease;
+  return launch_query_prep(index, level, q, nq, t, s, qlo, (hipStream_t)stream, lease);
 }
 
 }  // extern "C"

@@ -60,3 +60,31 @@ def small_case(n, d, R, nq, seed, metric="l2", bits=8, normalize=False, aniso=0.
         rng.shuffle(nb)
         adj[i, :len(nb)] = nb
     return w, X, Q, adj
+
+
+def n_workers():
+    import os
+    try:
+        avail = len(os.sched_getaffinity(0))
+    except AttributeError:
+        avail = os.cpu_count() or 1
+    return max(1, min(16, avail))
+
+
+def threaded(fn, n_items, concat=True):
+    """Run fn(slice) over disjoint query ranges on the host's cores (the oracle's
+    C calls release the interpreter lock) and stitch the tuples of arrays back."""
+    import threading
+    parts = [p for p in np.array_split(np.arange(n_items), n_workers()) if len(p)]
+    out = [None] * len(parts)
+
+    def work(i):
+        out[i] = fn(slice(int(parts[i][0]), int(parts[i][-1]) + 1))
+
+    ts = [threading.Thread(target=work, args=(i,)) for i in range(len(parts))]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    assert all(o is not None for o in out), "an oracle worker failed"
+    return tuple(np.concatenate([o[j] for o in out]) for j in range(len(out[0])))
