@@ -48,6 +48,7 @@ extern "C" {
 #define ANN_MAX_EF 512u
 #define ANN_MAX_DEGREE 64u
 #define ANN_MAX_ENTRIES 64u
+#define ANN_STATIC_SCRATCH_BYTES (8u << 20) /* see ann_search_batch_static */
 
 typedef struct ann_index ann_index; /* opaque; device memory owned by the library */
 
@@ -316,6 +317,31 @@ ann_status ann_schedule_queries(const uint32_t *keys, uint32_t nq, uint32_t key_
 ann_status ann_search_batch(ann_index *index, const float *q, uint32_t nq, const ann_search_params *params,
                             const uint32_t *entry_ids, uint32_t n_entry, uint32_t *out_ids, float *out_keys,
                             int32_t *out_idot, uint32_t *out_counts, void *stream);
+
+/*
+ * ann_search_batch for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels, same results; the folded queries go into a
+ * buffer of ANN_STATIC_SCRATCH_BYTES (8 MiB) that is part of the library's
+ * device image (each GPU the library runs on holds it until the process ends)
+ * instead of the index's workspace.  The call makes no hipMalloc / hipFree and
+ * no allocating library call.
+ *   Limit: 256-byte rounded nq * folded_row + 3 * (4 * nq) bytes must fit, where
+ *   folded_row is 16 bytes (8-bit codes) or 32 bytes (4-bit codes) per 16-byte
+ *   chunk of a code row, for at least the chunks the search kernel's lanes
+ *   cover: 128 bytes for d = 128 at 8 bits (about 59,000 queries), 1,024
+ *   bytes for d = 960 at 4 bits (about 8,000).  Beyond it: ANN_ECAPACITY,
+ *   nothing launched.
+ *   reuse_folded_queries is refused (ANN_EINVAL): the buffer belongs to no index.
+ *   Every call on a GPU shares that GPU's buffer and overwrites what the last
+ *   call left (each call writes all the bytes it reads, so nothing needs
+ *   clearing): calls whose execution may overlap on one GPU - on different
+ *   streams, or from different threads - race.  Calls on one stream are safe.
+ * Other errors as ann_search_batch.
+ */
+ann_status ann_search_batch_static(ann_index *index, const float *q, uint32_t nq, const ann_search_params *params,
+                                   const uint32_t *entry_ids, uint32_t n_entry, uint32_t *out_ids, float *out_keys,
+                                   int32_t *out_idot, uint32_t *out_counts, void *stream);
 
 /*
  * Re-evaluate candidates with code level `level` and sort them by (key, id):

@@ -21,6 +21,7 @@ LIB_PATH = Path(os.environ.get("ANN_LIBRARY_PATH") or (_PKG / "lib" / "libann_gf
 PAD_ID = 0xFFFFFFFF
 L2, IP = 0, 1
 MAX_EF, MAX_DEGREE, MAX_ENTRIES = 512, 64, 64
+STATIC_SCRATCH_BYTES = 8 << 20
 DESC_HOST_POINTERS = 1
 OK, EINVAL, ENOMEM, EDEVICE, EUNSUPPORTED, ECAPACITY = range(6)
 _STATUS_NAMES = ["ANN_OK", "ANN_EINVAL", "ANN_ENOMEM", "ANN_EDEVICE", "ANN_EUNSUPPORTED", "ANN_ECAPACITY"]
@@ -28,7 +29,7 @@ _STATUS_NAMES = ["ANN_OK", "ANN_EINVAL", "ANN_ENOMEM", "ANN_EDEVICE", "ANN_EUNSU
 EXPORTED_SYMBOLS = ["ann_sq_train", "ann_sq_train_truncated", "ann_sq_encode", "ann_upload_index", "ann_free_index", "ann_query_prep",
                     "ann_search_batch", "ann_rescore", "ann_rerank", "ann_bruteforce_topk", "ann_build_entry_table",
                     "ann_entry_scan", "ann_build_prs", "ann_schedule_queries", "ann_reserve_workspace",
-                    "ann_last_error", "ann_version"]
+                    "ann_search_batch_static", "ann_last_error", "ann_version"]
 
 
 class AnnError(RuntimeError):
@@ -73,6 +74,7 @@ def _load_library() -> ctypes.CDLL:
     lib.ann_free_index.argtypes = [vp]
     lib.ann_query_prep.argtypes = [vp, u32, vp, u32, vp, vp, vp, vp]
     lib.ann_search_batch.argtypes = [vp, vp, u32, ctypes.POINTER(SearchParams), vp, u32, vp, vp, vp, vp, vp]
+    lib.ann_search_batch_static.argtypes = lib.ann_search_batch.argtypes
     lib.ann_reserve_workspace.argtypes = [vp, u32, vp]
     lib.ann_rescore.argtypes = [vp, u32, vp, u32, vp, u32, u32, vp, vp, vp, vp]
     lib.ann_rerank.argtypes = [vp, vp, u32, vp, u32, u32, u32, vp, vp, vp]
@@ -167,13 +169,18 @@ def ann_reserve_workspace(index, max_nq, stream=None):
 def ann_search_batch(index, q, nq, *, k, ef, out_ids, out_keys=None, out_idot=None, out_counts=None, mode=0,
                      expansions_per_step=0, visited_slots=0, alpha_s=0.0, m_s=0, layout=0, visited_kind=0, query_order=None,
                      reuse_folded_queries=False, ef_per_query=None, entry_ids=None,
-                     n_entry=0, stream=None):
+                     n_entry=0, stream=None, static_scratch=False):
+    """static_scratch=True calls ann_search_batch_static (same arguments)."""
     p = SearchParams(k=k, ef=ef, mode=mode, expansions_per_step=expansions_per_step, visited_slots=visited_slots,
                      alpha_s=alpha_s, m_s=m_s, layout=layout, visited_kind=visited_kind, query_order=_ptr(query_order),
                      reuse_folded_queries=int(bool(reuse_folded_queries)), ef_per_query=_ptr(ef_per_query))
-    fn = _lib.ann_search_batch
+    fn = _lib.ann_search_batch_static if static_scratch else _lib.ann_search_batch
     _check(fn(index, _ptr(q), nq, ctypes.byref(p), _ptr(entry_ids), n_entry, _ptr(out_ids),
               _ptr(out_keys), _ptr(out_idot), _ptr(out_counts), stream))
+
+
+def ann_search_batch_static(index, q, nq, **kw):
+    ann_search_batch(index, q, nq, static_scratch=True, **kw)
 
 
 def ann_rescore(index, level, q, nq, cand_ids, n_cand, cand_stride, out_ids, out_keys=None, out_idot=None,

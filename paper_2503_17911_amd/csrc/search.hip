@@ -3,6 +3,8 @@
 #include "search_kernel.hpp"
 
 
+#include <mutex>
+
 using namespace ann;
 
 namespace {
@@ -148,4 +150,70 @@ extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_
   }
   return launch_search_with(index, nq, params, plan, entry_ids, n_entry, out_ids, out_keys, out_idot, out_counts,
                             *lease.ws, st);
+}
+
+// ---------------------------------------------------------------- no allocation
+// The folded queries of ann_search_batch_static live here instead of in a
+// workspace from hipMalloc.  In host code the array's name is only a handle:
+// the address the kernels use comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[ANN_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device.
+ann_status scratch_address(unsigned char **out) {
+  int dev = 0;
+  ANN_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(ANN_ECAPACITY, "ann_search_batch_static: device %d is beyond the %d devices the library tracks", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    ANN_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(ANN_EDEVICE, "ann_search_batch_static: hipGetSymbolAddress returned no address");
+    g_scratch_ptr[dev] = static_cast<unsigned char *>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return ANN_OK;
+}
+
+inline size_t round_up_256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" ann_status ann_search_batch_static(ann_index *index, const float *q, uint32_t nq,
+                                              const ann_search_params *params, const uint32_t *entry_ids,
+                                              uint32_t n_entry, uint32_t *out_ids, float *out_keys, int32_t *out_idot,
+                                              uint32_t *out_counts, void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  SearchPlan plan;
+  ann_status rc = check_search_args("ann_search_batch_static", index, q, nq, params, entry_ids, n_entry, out_ids, plan);
+  if (rc != ANN_OK) return rc;
+  if (params->reuse_folded_queries)
+    return fail(ANN_EINVAL, "ann_search_batch_static: reuse_folded_queries is not available (the static scratch is shared by every index)");
+  // carve the folded-query buffers out of the static array
+  Workspace w;
+  w.tq_stride = tq_stride_for(index->level[0]);
+  const size_t tq_bytes = round_up_256((size_t)nq * w.tq_stride), word_bytes = round_up_256((size_t)nq * 4);
+  const size_t need = tq_bytes + 3 * word_bytes;
+  if (need > (size_t)ANN_STATIC_SCRATCH_BYTES)
+    return fail(ANN_ECAPACITY, "ann_search_batch_static: %u queries of %u folded bytes need %zu bytes of scratch, the static buffer holds %zu",
+                nq, w.tq_stride, need, (size_t)ANN_STATIC_SCRATCH_BYTES);
+  unsigned char *base = nullptr;
+  rc = scratch_address(&base);
+  if (rc != ANN_OK) return rc;
+  w.nq_cap = nq;
+  w.tq = base;
+  w.s = reinterpret_cast<float *>(base + tq_bytes);
+  w.qlo = reinterpret_cast<float *>(base + tq_bytes + word_bytes);
+  w.sum_t = reinterpret_cast<int32_t *>(base + tq_bytes + 2 * word_bytes);
+  // the folding writes every byte the search reads (rows are written whole,
+  // zero padding included), so nothing of an earlier call has to be cleared
+  rc = launch_query_prep_into(index, 0, q, nq, w, nullptr, nullptr, nullptr, st);
+  if (rc != ANN_OK) return rc;
+  return launch_search_with(index, nq, params, plan, entry_ids, n_entry, out_ids, out_keys, out_idot, out_counts, w,
+                            st);
 }
