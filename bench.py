@@ -231,6 +231,7 @@ def main():
     efs = [args.ef] if args.ef else list(w.ef)
     modes = [args.mode] if args.mode >= 0 else [0, 1]
     sweep = []
+    sweep_counts = {}
     chosen = None
     for ef in efs:
         pool = torch.empty((nq, ef), dtype=torch.int32, device=dev)
@@ -249,6 +250,7 @@ def main():
             ev1.record()
             torch.cuda.synchronize()
             ms = ev0.elapsed_time(ev1)
+            sweep_counts[(ef, mode)] = c
             sweep.append(dict(ef=ef, mode=mode, recall=round(rec, 4), qps=round(nq / ms * 1e3),
                               n_exp=float(c[:, 0].mean()), n_dist=float(c[:, 1].mean()),
                               rebuilds=int(c[:, 3].sum())))
@@ -271,7 +273,11 @@ def main():
     # term for L2) actually needed, folded query in, pool out
     code_row = d if bits == 8 else d // 2
     per_eval = code_row + (4 if metric == ann.L2 else 0)
-    bytes_search = int((c[:, 0] * 4 * adj.shape[1] + c[:, 1] * per_eval).sum() + nq * (d + ef * 4))
+
+    def algorithmic_bytes(cnt, ef_):
+        return int((cnt[:, 0] * 4 * adj.shape[1] + cnt[:, 1] * per_eval).sum() + cnt.shape[0] * (d + ef_ * 4))
+
+    bytes_search = algorithmic_bytes(c, ef)
     bytes_rerank = nq * (min(n_rerank, ef) * (d * 4 + 4) + d * 4 + k * 8)
 
     # the configuration that is timed repeats some evaluations because its small
@@ -280,8 +286,7 @@ def main():
     run_step(ef, mode, pool, counts)
     torch.cuda.synchronize()
     ca = counts.cpu().numpy().astype(np.int64)
-    evals_timed, rebuilds_timed = float(ca[:, 1].mean()), float((ca[:, 3] & 0x7FFFFFFF).mean())
-    assert (ca[:, 3] < 2 ** 31).all(), "visited table failure flag set"
+    evals_timed, rebuilds_timed = float(ca[:, 1].mean()), float(ca[:, 3].mean())
     log(f"[bench] timed configuration: {evals_timed:.1f} evaluations/query ({float(c[:, 1].mean()):.1f} needed), "
         f"{rebuilds_timed:.2f} table rebuilds/query")
 
@@ -366,15 +371,115 @@ def main():
     log(f"[bench] steady state ({nq * rep} queries per batch): {big_ms:.3f} ms/batch, {steady_qps:,.0f} QPS, "
         f"{bytes_search * rep / (big_ms * 1e-3) / 1e9:.0f} GB/s algorithmic incl. fold and rerank time")
     q_second, ids_second = q_big[nq:2 * nq].clone(), ids_big[nq:2 * nq].clone()   # another batch and its results
+
+    # rotation: the timed step again, every step on another of the 8 distinct
+    # batches (the headline repeats the workload's own query set, whose lines
+    # may stay in the caches from one step to the next; this does not)
+    rot_bytes = []
+    rot_counts = torch.empty((nq, 4), dtype=torch.int32, device=dev)
+    for b in range(rep):
+        qb = q_big[b * nq:(b + 1) * nq]
+        search(qb, nq, ef, mode, pool, entries, rot_counts, complete_table=True)
+        torch.cuda.synchronize()
+        rot_bytes.append(algorithmic_bytes(rot_counts.cpu().numpy().astype(np.int64), ef))
+    n_rot = rep * max(2, args.steps // (2 * rep))
+    rb = [torch.cuda.Event(enable_timing=True) for _ in range(n_rot)]
+    rm = [torch.cuda.Event(enable_timing=True) for _ in range(n_rot)]
+    r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def rot_step(i, timed):
+        qb = q_big[(i % rep) * nq:(i % rep + 1) * nq]
+        if entries is not None:
+            ann.ann_entry_scan(index, qb, nq, args.n_entry, entries, st)
+        order = schedule(qb, nq, entries)
+        if timed:
+            rb[i].record()
+        ann.ann_search_batch(index, qb, nq, k=k, ef=ef, mode=mode, out_ids=pool,
+                             entry_ids=entries, n_entry=args.n_entry if entries is not None else 0, layout=args.layout,
+                             expansions_per_step=args.expansions if mode == 1 else 0,
+                             visited_slots=args.visited_slots, visited_kind=args.visited_kind,
+                             query_order=order, reuse_folded_queries=order is not None or entries is not None,
+                             stream=st)
+        if timed:
+            rm[i].record()
+        finish(pool, ef, nq, qb, ids_rot, dist_rot)
+
+    ids_rot = torch.empty((nq, k), dtype=torch.int32, device=dev)
+    dist_rot = torch.empty((nq, k), dtype=torch.float32, device=dev)
+    for i in range(rep):
+        rot_step(i, False)
+    torch.cuda.synchronize()
+    r0.record()
+    for i in range(n_rot):
+        rot_step(i, True)
+    r1.record()
+    torch.cuda.synchronize()
+    rot_ms = r0.elapsed_time(r1) / n_rot
+    rot_call_ms = float(np.mean([rb[i].elapsed_time(rm[i]) for i in range(n_rot)]))
+    rot_kernel_ms = rot_call_ms if (scheduling or entries is not None) else max(rot_call_ms - prep_ms, 1e-6)
+    rot_gbs = float(np.mean(rot_bytes)) / (rot_kernel_ms * 1e-3) / 1e9
+    rotating = {"what": f"the same step over a rotation of {rep} distinct {nq}-query batches of the same law "
+                        f"(the headline repeats the workload's own {nq} queries)",
+                "ms_per_step": round(rot_ms, 4), "value": round(nq / (rot_ms * 1e-3), 1),
+                "kernel_ms": round(rot_kernel_ms, 4), "algorithmic_GBps": round(rot_gbs, 1),
+                "frac": round(rot_gbs / HBM_PEAK_GBS, 4)}
+    log(f"[bench] rotation of {rep} distinct batches: {rot_ms:.3f} ms/step {nq / rot_ms * 1e3:,.0f} QPS, "
+        f"search kernel {rot_kernel_ms:.3f} ms = {rot_gbs:.0f} GB/s algorithmic")
     del q_big, pool_big, ids_big, dist_big
 
+    # Algorithm 1 as the paper defines it (one expansion per step) at the same ef:
+    # its own step time and roofline figures beside the headline's
+    exact = None
+    if mode == 1 and (ef, 0) in sweep_counts:
+        c0 = sweep_counts[(ef, 0)]
+        rec0 = next(r["recall"] for r in sweep if r["ef"] == ef and r["mode"] == 0)
+        n_x = max(10, args.steps // 4)
+        xb = [torch.cuda.Event(enable_timing=True) for _ in range(n_x)]
+        xm = [torch.cuda.Event(enable_timing=True) for _ in range(n_x)]
+        x0, x1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+        def exact_step(i):
+            if entries is not None:
+                ann.ann_entry_scan(index, qd, nq, args.n_entry, entries, st)
+            order = schedule(qd, nq, entries)
+            if i >= 0:
+                xb[i].record()
+            ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=0, out_ids=pool,
+                                 entry_ids=entries, n_entry=args.n_entry if entries is not None else 0, layout=args.layout,
+                                 visited_slots=args.visited_slots, visited_kind=args.visited_kind,
+                                 query_order=order, reuse_folded_queries=order is not None or entries is not None,
+                                 stream=st)
+            if i >= 0:
+                xm[i].record()
+            finish(pool, ef, nq, qd, ids_rot, dist_rot)
+
+        for _ in range(3):
+            exact_step(-1)
+        torch.cuda.synchronize()
+        x0.record()
+        for i in range(n_x):
+            exact_step(i)
+        x1.record()
+        torch.cuda.synchronize()
+        x_ms = x0.elapsed_time(x1) / n_x
+        x_call = float(np.mean([xb[i].elapsed_time(xm[i]) for i in range(n_x)]))
+        x_kernel = x_call if (scheduling or entries is not None) else max(x_call - prep_ms, 1e-6)
+        x_bytes = algorithmic_bytes(c0, ef)
+        x_gbs = x_bytes / (x_kernel * 1e-3) / 1e9
+        exact = {"what": "one expansion per step (results identical to the sequential algorithm), same ef, same step",
+                 "ef": ef, f"recall_at_{k}": rec0, "ms_per_step": round(x_ms, 4), "value": round(nq / (x_ms * 1e-3), 1),
+                 "kernel_ms": round(x_kernel, 4), "algorithmic_bytes_per_launch": x_bytes,
+                 "algorithmic_GBps": round(x_gbs, 1), "frac": round(x_gbs / HBM_PEAK_GBS, 4)}
+        log(f"[bench] exact mode ef={ef}: {x_ms:.3f} ms/step {nq / x_ms * 1e3:,.0f} QPS, search kernel {x_kernel:.3f} ms = "
+            f"{x_gbs:.0f} GB/s algorithmic ({x_gbs / HBM_PEAK_GBS:.3f} of peak)")
+
     # latency of one query alone on the device (batch of 1): folding, search and
-    # rerank launched back to back, host-synchronised; median over 200 queries
+    # rerank launched back to back, host-synchronised; median over 1,000 launches
     lat = []
     pool1 = torch.empty((1, ef), dtype=torch.int32, device=dev)
     ids1 = torch.empty((1, k), dtype=torch.int32, device=dev)
     dist1 = torch.empty((1, k), dtype=torch.float32, device=dev)
-    for i in range(220):
+    for i in range(1020):
         q1 = qd[i % nq:i % nq + 1]
         torch.cuda.synchronize()
         t1 = time.perf_counter()
@@ -527,13 +632,17 @@ def main():
         ann.ann_free_index(index2)
         del x2
 
+    mean_degree = float((adj != 0xFFFFFFFF).sum(1).mean())
+    shape_label = {1_000_000: "1M", 10_000_000: "10M", 5_000_000: "5M"}.get(n, str(n)) + f" x {d} " + \
+        "->".join(f"SQ{b}" for b in w.bits)
+    mfma_scan = scheduling and bits == 8 and d <= 256 and (entries is None or args.n_entry == 1)
     default_config = (args.workload == "c2" and not args.n and not args.nq and not args.visited_slots and not args.visited_kind
                       and not args.pivots and not args.layout and not args.expansions and args.coverage == 1.0
                       and args.schedule_pivots == 256
                       and ef == 128 and mode == 1)
     traffic = MEASURED_TRAFFIC.get(kernel_source_hash()) if default_config else None
     result = {
-        "metric": "queries/sec at recall@10>=0.95 (1M x 128 SQ8, ef sweep)",
+        "metric": f"queries/sec at recall@{k}>=0.95 ({shape_label}, ef sweep)",
         "value": round(qps, 1),
         "unit": "queries/s",
         "n_gpus": 1,
@@ -545,23 +654,31 @@ def main():
         "vs_baseline": None,
         "dtype": "int8 traversal (int32 accumulate) + f32 rerank",
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: N={n} d={d} SQ{bits} R={adj.shape[1]} {w.metric} k={k} nq={nq} "
-                               f"rerank top {min(n_rerank, ef)}",
-                   "query_order": (f"scheduled by the closest of {args.schedule_pivots} scanned pivots (inside the timed step)"
+        "config": {"workload": f"{w.name}: N={n} d={d} SQ{bits} R={adj.shape[1]} (mean out-degree {mean_degree:.1f}: the graph "
+                               f"fixture prunes without back-fill) {w.metric} k={k} nq={nq} "
+                               + (f"rescore pool with SQ{w.bits[1]}, " if len(w.bits) > 1 else "")
+                               + f"rerank top {min(n_rerank, ef)}",
+                   "query_order": ((f"scheduled by the closest of {args.schedule_pivots} scanned pivots (inside the timed step"
+                                    + ("; folding and pivot scan are one int8 MFMA kernel" if mfma_scan else "") + ")")
                                    if scheduling and not args.pivots else
                                    "scheduled by the entry scan's result" if scheduling else "natural"),
+                   "matrix_cores_in_timed_step": ("int8 MFMA in the pivot scan that orders the batch (a dense integer contraction, "
+                                                  "exact); none in the search, rescore or rerank kernels") if mfma_scan else "none",
                    "entry": "medoid" if not args.pivots else f"closest {args.n_entry} of {args.pivots} scanned pivots",
-                   "ef": ef, "mode": "exact" if mode == 0 else "multi-expansion", "recall_at_10": round(rec, 4),
+                   "ef": ef, "mode": "exact" if mode == 0 else "multi-expansion", f"recall_at_{k}": round(rec, 4),
                    "recall_target_met": bool(rec >= 0.95), "evaluations_per_query": round(float(c[:, 1].mean()), 1),
                    "evaluations_per_query_timed": round(evals_timed, 1),
                    "steady_state_8x_batch": {"queries_per_batch": nq * rep, "ms_per_batch": round(big_ms, 4),
                                              "value": round(steady_qps, 1),
                                              "algorithmic_GBps": round(bytes_search * rep / (big_ms * 1e-3) / 1e9, 1)},
                    "single_query_latency_us": {"median": round(lat_med, 1), "p99": round(lat_p99, 1),
-                                               "what": "batch of 1: fold + search + rerank, host-synchronised"},
+                                               "launches": len(lat),
+                                               "what": "batch of 1: fold + search (+ rescore) + rerank, host-synchronised, one launch sequence per query"},
                    "entry_stage_variant": variant,
                    "renumbered_nodes_variant": relabel,
                    "two_batches_in_flight": pipelined,
+                   "rotating_batches": rotating,
+                   "exact_mode": exact,
                    "sweep": sweep},
         "ground_truth": {"kernel": "ann_bruteforce_topk (fp32 MFMA 128x128 tiles, shared top-k bounds, exact re-evaluation)", "bound": "mfma",
                          "seconds": round(bf_s, 4), "achieved": round(2 * n * nq * d / bf_s / 1e12, 1),
@@ -570,6 +687,14 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "search_kernel (one expansion per step)" if mode == 0 else "search_kernel (multi-expansion)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "achieved_is": "algorithmic gathered bytes (adjacency rows + code rows + norm terms needed by the algorithm, "
+                                    "counted by a run with a complete visited table) / search kernel time from HIP events in this run; "
+                                    "not a measurement of HBM traffic",
+                     "traffic_is": "bytes at the L2-fabric boundary per launch from rocprofv3 FETCH_SIZE/WRITE_SIZE of an earlier run of "
+                                   "this command (profiles/), stored in bench.py and keyed to a hash of the kernel sources; null "
+                                   "when the sources or the configuration differ; part of it is served by the 256 MB Infinity "
+                                   "Cache (the workload's hot set is about that size), not HBM",
+                     "traffic_measured_in_run": False,
                      "algorithmic_bytes_per_launch": bytes_search, "kernel_ms": round(kernel_ms, 4),
                      "rerank_bytes_per_launch": bytes_rerank,
                      "rest_of_step_ms": round(ms_per_step - search_ms, 4),

@@ -161,12 +161,20 @@ def cache_dir() -> Path:
     return Path(os.environ.get("ANN_INPUT_CACHE", _HERE.parent / "input_cache"))
 
 
-def graph(w: Workload, X: np.ndarray | None = None, use_cache: bool = True) -> tuple[np.ndarray, int]:
-    """Graph + entry point of a workload, cached on disk by its parameters."""
+def _graph_path(w: Workload) -> Path:
     key = f"{w.n}_{w.d}_{w.n_clusters}_{w.sigma}_{w.aniso_sigma}_{w.noise_frac}_{int(w.normalize)}_{w.seed}_" \
           f"{w.degree}_{w.ef_c}_nobackfill_v2"
     tag = hashlib.sha1((key + hashlib.sha1(_SRC.read_bytes()).hexdigest()).encode()).hexdigest()[:16]
-    path = cache_dir() / f"graph_{w.name.replace('@', '_')}_{tag}.npz"
+    return cache_dir() / f"graph_{w.name.replace('@', '_')}_{tag}.npz"
+
+
+def graph_is_cached(w: Workload) -> bool:
+    return _graph_path(w).exists()
+
+
+def graph(w: Workload, X: np.ndarray | None = None, use_cache: bool = True) -> tuple[np.ndarray, int]:
+    """Graph + entry point of a workload, cached on disk by its parameters."""
+    path = _graph_path(w)
     if use_cache and path.exists():
         z = np.load(path)
         return z["adj"], int(z["entry"])
@@ -176,6 +184,8 @@ def graph(w: Workload, X: np.ndarray | None = None, use_cache: bool = True) -> t
     if use_cache and w.n >= 100_000:
         path.parent.mkdir(parents=True, exist_ok=True)
         tmp = path.with_suffix(".tmp.npz")
-        np.savez(tmp, adj=adj, entry=np.int64(entry))
+        # compression halves the file (the padding goes) but takes a minute per GB: ANN_INPUT_CACHE_COMPRESS=0 skips it
+        save = np.savez if os.environ.get("ANN_INPUT_CACHE_COMPRESS", "1") == "0" else np.savez_compressed
+        save(tmp, adj=adj, entry=np.int64(entry))
         os.replace(tmp, path)
     return adj, entry

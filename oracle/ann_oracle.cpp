@@ -77,15 +77,19 @@ extern "C" {
 // (2^b - 1) in fp32; an empty range gets delta = 1.
 void orc_sq_train(const float *X, int64_t n, int32_t d, int32_t bits, float *lo, float *delta) {
   const float levels = (float)((1 << bits) - 1);
-  for (int j = 0; j < d; ++j) {
-    float mn = X[j], mx = X[j];
-    for (int64_t i = 1; i < n; ++i) {
-      float v = X[i * (int64_t)d + j];
-      if (v < mn) mn = v;
-      if (v > mx) mx = v;
+  // running minimum and maximum of every dimension, rows taken one after the
+  // other (minimum and maximum do not depend on the order of the rows)
+  std::vector<float> mn(X, X + d), mx(X, X + d);
+  for (int64_t i = 1; i < n; ++i) {
+    const float *row = X + i * (int64_t)d;
+    for (int j = 0; j < d; ++j) {
+      if (row[j] < mn[j]) mn[j] = row[j];
+      if (row[j] > mx[j]) mx[j] = row[j];
     }
-    lo[j] = mn;
-    delta[j] = (mx > mn) ? (mx - mn) / levels : 1.0f;
+  }
+  for (int j = 0; j < d; ++j) {
+    lo[j] = mn[j];
+    delta[j] = (mx[j] > mn[j]) ? (mx[j] - mn[j]) / levels : 1.0f;
   }
 }
 
