@@ -528,7 +528,7 @@ def main():
                 torch.cuda.synchronize()
                 ms_v = v0.elapsed_time(v1) / n_v
                 variant = {"entry": "closest of 1024 scanned pivots", "ef": ef_v, "mode": "multi-expansion",
-                           "recall_at_10": round(rec_v, 4), "ms_per_step": round(ms_v, 4),
+                           f"recall_at_{k}": round(rec_v, 4), "ms_per_step": round(ms_v, 4),
                            "value": round(nq / (ms_v * 1e-3), 1)}
                 log(f"[bench] variant with entry-point stage: ef={ef_v} recall@{k}={rec_v:.4f} {ms_v:.3f} ms/step "
                     f"{nq / ms_v * 1e3:,.0f} QPS (scan + search + rerank)")
@@ -625,7 +625,7 @@ def main():
         back = perm[ids2.to(torch.int64) & 0xFFFFFFFF].cpu().numpy()            # old ids
         rec_r = recall_at_k(back, gt)
         relabel = {"what": "nodes renumbered by region (closest of 1024 pivots) before upload; same graph, same queries",
-                   "ef": ef, "mode": "exact" if mode == 0 else "multi-expansion", "recall_at_10": round(rec_r, 4),
+                   "ef": ef, "mode": "exact" if mode == 0 else "multi-expansion", f"recall_at_{k}": round(rec_r, 4),
                    "ms_per_step": round(ms_r, 4), "value": round(nq / (ms_r * 1e-3), 1)}
         log(f"[bench] variant with nodes renumbered by region: ef={ef} recall@{k}={rec_r:.4f} {ms_r:.3f} ms/step "
             f"{nq / ms_r * 1e3:,.0f} QPS")

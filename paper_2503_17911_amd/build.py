@@ -32,10 +32,14 @@ def _compile(src: str) -> Path:
     return obj
 
 
-def build(verbose: bool = True) -> Path:
+def build(verbose: bool = True, only=None) -> Path:
+    """Compile every source (or, for quick iterations, only those named in
+    `only`, reusing the other object files) and link the library."""
     LIBDIR.mkdir(exist_ok=True)
+    todo = [s for s in SOURCES if only is None or s in only or not (LIBDIR / (s + ".o")).exists()]
     with ThreadPoolExecutor(max_workers=min(len(SOURCES), 8)) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+        list(ex.map(_compile, todo))
+    objs = [LIBDIR / (s + ".o") for s in SOURCES]
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *map(str, objs), "-o", str(LIB)]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
@@ -46,4 +50,4 @@ def build(verbose: bool = True) -> Path:
 
 
 if __name__ == "__main__":
-    build()
+    build(only=sys.argv[1:] or None)

@@ -31,6 +31,12 @@
 // execution bit for bit.  With P > 1 expansions per step the P closest
 // un-expanded entries are expanded together (rows filtered in that order).
 #pragma once
+#ifndef ANN_U
+#define ANN_U 2
+#endif
+#ifndef ANN_WPE
+#define ANN_WPE 6
+#endif
 #include "ann_internal.hpp"
 #include "device_utils.hpp"
 
@@ -64,6 +70,17 @@ struct SearchArgs {
   uint32_t m_s;
   float alpha_s;
 };
+
+// A workgroup of these kernels is one wavefront, and a wavefront's LDS
+// instructions are carried out in the order they were issued: what one lane
+// wrote is there for any lane's later read.  So all that is needed between a
+// write and a dependent read by another lane is that the compiler keeps the
+// two in program order - no barrier instruction and no wait for global loads
+// that are still in flight (which a workgroup barrier implies).
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
 
 __device__ __forceinline__ uint64_t pack64(uint32_t hi, uint32_t lo) { return ((uint64_t)hi << 32) | lo; }
 
@@ -103,7 +120,7 @@ template <int BITS, int LPR, int M, int PMAX, bool FAST>
 struct SearchWave {
   static constexpr int G = kWave / LPR;      // code rows evaluated side by side
   static constexpr int CPL = 4;              // 16-byte chunks of a row per lane
-  static constexpr int U = PMAX > 1 ? 2 : 1;  // groups of G rows in flight
+  static constexpr int U = PMAX > 1 ? ANN_U : 1;  // groups of G rows in flight
   static constexpr int TQW = TqRegs<BITS>::kWords;
 
   // the i-th unvisited id of the current step
@@ -339,9 +356,9 @@ struct SearchWave {
   // pool maximum that has only decreased since: re-evaluating it yields the
   // same key and the same rejection.  Results do not change; work is repeated.
   __device__ __forceinline__ void rebuild_table() {
-    __syncthreads();
+    wave_sync();
     clear_table();
-    __syncthreads();
+    wave_sync();
     int kept = 0;
 #pragma unroll
     for (int r = 0; r < M; ++r)
@@ -351,7 +368,7 @@ struct SearchWave {
       }
     n_vis = (uint32_t)group_sum_i32<64>(kept);
     ++n_rebuild;
-    __syncthreads();
+    wave_sync();
   }
 
   __device__ __forceinline__ void refresh_worst() {
@@ -397,9 +414,9 @@ struct SearchWave {
       // pool entry i moves up by the number of candidates with rank <= i
 #pragma unroll
       for (int r = 0; r < M; ++r) cnt[r * kWave + lane] = 0;
-      __syncthreads();
+      wave_sync();
       if (mine) atomicAdd(&cnt[rank_p], 1);
-      __syncthreads();
+      wave_sync();
       int carry = 0;
 #pragma unroll
       for (int r = 0; r < M; ++r) {
@@ -418,14 +435,14 @@ struct SearchWave {
       // equal destinations.  One of them stays, the count starts over (rare).
       // (candidates ranked past the buffer are dropped anyway)
       const bool lands = mine && dest < 64 * M;
-      __syncthreads();
+      wave_sync();
       if (lands) cnt[dest] = lane;
-      __syncthreads();
+      wave_sync();
       const uint64_t lose = __ballot(lands && cnt[dest] != lane);
       if (lose == 0) break;
       km &= ~lose;
       mine = mine && ((lose >> lane) & 1ull) == 0;
-      __syncthreads();
+      wave_sync();
     }
     const int n_m = __popcll(km);
     // no two (key, id) pairs are equal: the destinations are a permutation
@@ -435,7 +452,7 @@ struct SearchWave {
       if (to < 64 * M) mbuf[to] = pack64(pk[r], pv[r]);
     }
     if (mine && dest < 64 * M) mbuf[dest] = c64;
-    __syncthreads();
+    wave_sync();
 #pragma unroll
     for (int r = 0; r < M; ++r) {
       const uint64_t v = mbuf[r * kWave + lane];
@@ -443,7 +460,7 @@ struct SearchWave {
       pk[r] = beyond ? kEmpty : (uint32_t)(v >> 32);
       pv[r] = beyond ? kEmpty : (uint32_t)v;
     }
-    __syncthreads();
+    wave_sync();
     (void)n_m;
     refresh_worst();
   }
@@ -466,7 +483,7 @@ struct SearchWave {
     const bool open = valid && !lookup(nb);
     const uint64_t om = __ballot(open);
     const bool take = open && (uint32_t)lanes_below(om) < m_s;
-    __syncthreads();
+    wave_sync();
     const bool fresh = take && test_and_set(nb);
     const uint64_t fm = __ballot(fresh);
     if (fresh) cand_at(n_cand + lanes_below(fm)) = nb;
@@ -488,12 +505,12 @@ struct SearchWave {
   static constexpr int kStage = stage_entries(M, PMAX, FAST);
   __device__ __forceinline__ void merge_staged(int &n_q) {
     if (n_q == 0) return;
-    __syncthreads();
+    wave_sync();
     constexpr int kBatches = kStage / kWave;
     uint64_t batch[kBatches];
 #pragma unroll
     for (int b = 0; b < kBatches; ++b) batch[b] = b * kWave + lane < n_q ? stage[b * kWave + lane] : 0;
-    __syncthreads();
+    wave_sync();
     // one copy of the merge code, however many batches: the batch is picked by selects
 #pragma nounroll
     for (int b = 0; b * kWave < n_q; ++b) {
@@ -511,7 +528,7 @@ struct SearchWave {
     if (n_cand == 0) return;
     n_vis += n_cand;
     n_dist += n_cand;
-    __syncthreads();
+    wave_sync();
     int n_q = 0;
     for (int base = 0; base < n_cand; base += G * U) {
       uint4 rows[U][CPL];
@@ -615,7 +632,7 @@ struct SearchWave {
 #pragma unroll
     for (int r = 0; r < M; ++r) mbuf[r * kWave + lane] = ~0ull;  // the empty pool, in order
     clear_table();
-    __syncthreads();
+    wave_sync();
 
     // initial nodes I: into the pool and into V
     {
@@ -766,11 +783,11 @@ struct SearchWave {
     }
     if (a.out_idot) {
       // same arithmetic as during traversal, over the final pool
-      __syncthreads();
+      wave_sync();
       uint32_t *st_id = reinterpret_cast<uint32_t *>(mbuf);
 #pragma unroll
       for (int r = 0; r < M; ++r) st_id[r * kWave + lane] = pk[r] != kEmpty ? (pv[r] >> 1) : kEmpty;
-      __syncthreads();
+      wave_sync();
       for (int base = 0; base < (int)a.ef; base += G) {
         const int ci = base + grp;
         const uint32_t v = ci < (int)a.ef ? st_id[ci] : kEmpty;
@@ -797,7 +814,7 @@ struct SearchWave {
 };
 
 template <int BITS, int LPR, int M, int PMAX, bool FAST>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? (FAST ? (PMAX > 1 ? (BITS == 8 ? 6 : 5) : 8) : 5) : (M == 4 ? 4 : 3)))) void search_kernel(SearchArgs args) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? (FAST ? (PMAX > 1 ? (BITS == 8 ? ANN_WPE : 5) : 8) : 5) : (M == 4 ? 4 : 3)))) void search_kernel(SearchArgs args) {
   extern __shared__ uint64_t smem[];
   if (blockIdx.x >= args.nq) return;
   const uint32_t qi = args.order ? args.order[blockIdx.x] : blockIdx.x;
