@@ -65,6 +65,19 @@ typedef enum { ANN_L2 = 0, ANN_IP = 1 } ann_metric;
 
 /* ann_index_desc.flags */
 #define ANN_DESC_HOST_POINTERS 1u /* every array in the descriptor is in HOST memory */
+/*
+ * For ANN_IP indexes whose base vectors have unit norm (an improvement of the
+ * low-precision distance in the sense of the paper's Appendix G): traversal,
+ * entry-scan and rescore keys take the Euclidean form of Section 5.2,
+ * ||x^||^2 - 2 q.x^ with x^ the decoded vector, instead of -(q.x^).  On exact
+ * unit vectors both orders are the same; on decoded vectors the Euclidean form
+ * is the squared distance to x^ (minus ||q||^2), in which the part of the
+ * quantization error that lies along q - x, short for near neighbours, counts,
+ * where -(q.x^) carries the error along q at full length.  Needs norm_term
+ * for every level.  ann_rerank and ann_bruteforce_topk are not affected:
+ * returned distances stay -<q, x>.
+ */
+#define ANN_DESC_UNIT_NORM_L2_KEYS 2u
 
 /*
  * One scalar-quantization level (paper Appendix G, SQ-b with b = bits).
@@ -363,6 +376,26 @@ ann_status ann_rescore(ann_index *index, uint32_t level, const float *q, uint32_
  */
 ann_status ann_rerank(ann_index *index, const float *q, uint32_t nq, const uint32_t *cand_ids, uint32_t n_cand,
                       uint32_t cand_stride, uint32_t k, uint32_t *out_ids, float *out_dist, void *stream);
+
+/*
+ * Rerank of a per-query prefix: a stand-in for the paper's selective re-rank
+ * (Section 5.3 keeps the exact-distance work to the candidates that can still
+ * enter the result; its rule is given only in a cited work).  The rule here:
+ * with the candidates in ascending order of their low-precision keys
+ * cand_keys [nq][cand_stride] (as ann_search_batch and ann_rescore return
+ * them), query i re-evaluates the candidates whose key is not above
+ *     key[k-1] + gamma * (key[k-1] - key[0])        (fp32: one subtraction, one fma),
+ * at least n_min and at most n_max of them (all n_max when key[k-1] is not
+ * finite, i.e. the list is shorter than k): a candidate far behind the k-th
+ * in the low-precision order, measured by the spread of the first k keys,
+ * is taken not to be among the true k nearest.  Then as ann_rerank.
+ *   out_n [nq] (NULL allowed): the number of candidates re-evaluated per query.
+ * k <= n_min <= n_max <= cand_stride, n_max <= 4096, gamma >= 0.
+ */
+ann_status ann_rerank_adaptive(ann_index *index, const float *q, uint32_t nq, const uint32_t *cand_ids,
+                               const float *cand_keys, uint32_t n_min, uint32_t n_max, uint32_t cand_stride,
+                               float gamma, uint32_t k, uint32_t *out_ids, float *out_dist, uint32_t *out_n,
+                               void *stream);
 
 /*
  * Exact k nearest neighbours NN_k of every query by exhaustive search (the

@@ -54,6 +54,8 @@ def _load():
                                           _u32p, _f32p, _i32p]
         lib.orc_entry_scan.argtypes = [_i64, _i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _f32p, _i32, _i32, _i32, _u32p]
         lib.orc_rerank_batch.argtypes = [_f32p, _i32, _i32, _f32p, _i32, _u32p, _i32, _i32, _u32p, _f32p]
+        lib.orc_rerank_length.argtypes = [_f32p, _i32, _i32, _i32, _i32, _i32, _f32, _u32p]
+        lib.orc_rerank_length.restype = None
         lib.orc_bruteforce_topk.argtypes = [_f32p, _i64, _i32, _i32, _f32p, _i32, _i32, _u32p, _f64p]
         for name in ("orc_sq_train", "orc_sq_train_truncated", "orc_sq_encode", "orc_sq_decode", "orc_query_prep", "orc_search_batch",
                      "orc_rescore_batch", "orc_rerank_batch", "orc_bruteforce_topk", "orc_entry_scan"):
@@ -200,6 +202,24 @@ def rerank_batch(X, Q, cand_ids, k, metric=L2):
     _load().orc_rerank_batch(_p(X, _f32p), X.shape[1], metric, _p(Q, _f32p), nq, _p(cand_ids, _u32p), n_cand, k,
                              _p(ids, _u32p), _p(dist, _f32p))
     return ids, dist
+
+
+def rerank_length(keys, n_min, n_max, k, gamma):
+    """Per-query length of the reranked prefix from the low-precision keys [nq][stride]."""
+    keys = _c(keys, np.float32)
+    nq, stride = keys.shape
+    out = np.empty(nq, np.uint32)
+    _load().orc_rerank_length(_p(keys, _f32p), nq, stride, n_min, n_max, k, float(gamma), _p(out, _u32p))
+    return out
+
+
+def rerank_adaptive(X, Q, cand_ids, cand_keys, n_min, n_max, k, gamma, metric=L2):
+    """rerank_batch over each query's own prefix (the rest of the row is treated as padding)."""
+    n_r = rerank_length(cand_keys, n_min, n_max, k, gamma)
+    cand = _c(cand_ids, np.uint32)[:, :n_max].copy()
+    cand[np.arange(n_max)[None, :] >= n_r[:, None]] = PAD
+    ids, dist = rerank_batch(X, Q, cand, k, metric=metric)
+    return ids, dist, n_r
 
 
 def bruteforce_topk(X, Q, k, metric=L2):

@@ -422,6 +422,28 @@ void orc_rerank_batch(const float *X, int32_t d, int32_t metric, const float *Q,
   }
 }
 
+// Length of the reranked prefix chosen per query from the low-precision keys
+// (stand-in for the selective re-rank of Section 5.3, whose own rule is in a
+// cited work): the candidates, in ascending key order, whose key is not above
+//     key[k-1] + gamma * (key[k-1] - key[0])      (fp32: one subtraction, one fma)
+// are re-evaluated, at least n_min and at most n_max of them; all n_max when
+// key[k-1] is not finite (fewer than k candidates).
+void orc_rerank_length(const float *keys, int32_t nq, int32_t stride, int32_t n_min, int32_t n_max, int32_t k,
+                       float gamma, uint32_t *out_n) {
+  for (int32_t qi = 0; qi < nq; ++qi) {
+    const float *kq = keys + (int64_t)qi * stride;
+    const float k0 = kq[0], kk = kq[k - 1 < n_max ? k - 1 : n_max - 1];
+    int32_t n = n_max;
+    if (std::isfinite(kk)) {
+      const float thr = std::fmaf(gamma, kk - k0, kk);
+      n = 0;
+      for (int i = 0; i < n_max; ++i) n += kq[i] <= thr ? 1 : 0;
+      if (n < n_min) n = n_min;
+    }
+    out_n[qi] = (uint32_t)n;
+  }
+}
+
 // ---------------------------------------------------------------- exact kNN
 // NN_k by exhaustive fp64 evaluation, order (distance, id).
 void orc_bruteforce_topk(const float *X, int64_t n, int32_t d, int32_t metric, const float *Q, int32_t nq, int32_t k,

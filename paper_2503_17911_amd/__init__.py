@@ -23,11 +23,12 @@ L2, IP = 0, 1
 MAX_EF, MAX_DEGREE, MAX_ENTRIES = 512, 64, 64
 STATIC_SCRATCH_BYTES = 8 << 20
 DESC_HOST_POINTERS = 1
+DESC_UNIT_NORM_L2_KEYS = 2
 OK, EINVAL, ENOMEM, EDEVICE, EUNSUPPORTED, ECAPACITY = range(6)
 _STATUS_NAMES = ["ANN_OK", "ANN_EINVAL", "ANN_ENOMEM", "ANN_EDEVICE", "ANN_EUNSUPPORTED", "ANN_ECAPACITY"]
 
 EXPORTED_SYMBOLS = ["ann_sq_train", "ann_sq_train_truncated", "ann_sq_encode", "ann_upload_index", "ann_free_index", "ann_query_prep",
-                    "ann_search_batch", "ann_rescore", "ann_rerank", "ann_bruteforce_topk", "ann_build_entry_table",
+                    "ann_search_batch", "ann_rescore", "ann_rerank", "ann_rerank_adaptive", "ann_bruteforce_topk", "ann_build_entry_table",
                     "ann_entry_scan", "ann_build_prs", "ann_schedule_queries", "ann_reserve_workspace",
                     "ann_search_batch_static", "ann_last_error", "ann_version"]
 
@@ -78,6 +79,7 @@ def _load_library() -> ctypes.CDLL:
     lib.ann_reserve_workspace.argtypes = [vp, u32, vp]
     lib.ann_rescore.argtypes = [vp, u32, vp, u32, vp, u32, u32, vp, vp, vp, vp]
     lib.ann_rerank.argtypes = [vp, vp, u32, vp, u32, u32, u32, vp, vp, vp]
+    lib.ann_rerank_adaptive.argtypes = [vp, vp, u32, vp, vp, u32, u32, u32, ctypes.c_float, u32, vp, vp, vp, vp]
     lib.ann_bruteforce_topk.argtypes = [vp, u64, u32, vp, u32, u32, u32, vp, vp, vp]
     lib.ann_build_prs.argtypes = [vp, vp]
     lib.ann_build_entry_table.argtypes = [vp, u32, vp]
@@ -132,7 +134,7 @@ def ann_sq_encode(x, n, d, bits, lo, delta, codes, norm_term, stream=None):
 
 
 def ann_upload_index(*, n, d, degree, metric, vectors, levels, adjacency, entry_point, csr_offsets=None,
-                     edge_labels=None, host_pointers=False, stream=None) -> int:
+                     edge_labels=None, host_pointers=False, unit_norm_l2_keys=False, stream=None) -> int:
     """levels: list of (bits, codes, lo, delta, norm_term).  Returns the opaque index handle."""
     desc = IndexDesc()
     desc.n, desc.d, desc.degree, desc.metric = n, d, degree, metric
@@ -148,7 +150,7 @@ def ann_upload_index(*, n, d, degree, metric, vectors, levels, adjacency, entry_
     desc.csr_offsets = _ptr(csr_offsets)
     desc.edge_labels = _ptr(edge_labels)
     desc.entry_point = entry_point
-    desc.flags = DESC_HOST_POINTERS if host_pointers else 0
+    desc.flags = (DESC_HOST_POINTERS if host_pointers else 0) | (DESC_UNIT_NORM_L2_KEYS if unit_norm_l2_keys else 0)
     handle = ctypes.c_void_p()
     _check(_lib.ann_upload_index(ctypes.byref(desc), stream, ctypes.byref(handle)))
     return handle.value
@@ -192,6 +194,12 @@ def ann_rescore(index, level, q, nq, cand_ids, n_cand, cand_stride, out_ids, out
 def ann_rerank(index, q, nq, cand_ids, n_cand, cand_stride, k, out_ids, out_dist, stream=None):
     _check(_lib.ann_rerank(index, _ptr(q), nq, _ptr(cand_ids), n_cand, cand_stride, k, _ptr(out_ids),
                            _ptr(out_dist), stream))
+
+
+def ann_rerank_adaptive(index, q, nq, cand_ids, cand_keys, n_min, n_max, cand_stride, gamma, k, out_ids, out_dist,
+                        out_n=None, stream=None):
+    _check(_lib.ann_rerank_adaptive(index, _ptr(q), nq, _ptr(cand_ids), _ptr(cand_keys), n_min, n_max, cand_stride,
+                                    gamma, k, _ptr(out_ids), _ptr(out_dist), _ptr(out_n), stream))
 
 
 def ann_build_prs(index, stream=None):

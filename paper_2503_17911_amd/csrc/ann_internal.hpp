@@ -52,6 +52,7 @@ struct StreamWorkspaces {
 struct ann_index {
   uint64_t n = 0;
   uint32_t d = 0, degree = 0, metric = 0, n_levels = 0, entry_point = 0;
+  uint32_t key_metric = 0;  // form of the low-precision keys: the metric, or ANN_L2 for unit-norm inner-product data
   float *vectors = nullptr;    // [n][d] or nullptr
   uint32_t *adjacency = nullptr;  // [n][degree]
   float *labels = nullptr;        // [n][degree] edge labels or nullptr

@@ -19,7 +19,8 @@ namespace ann {
 
 ann_status rerank_device(const float *X, uint64_t n, uint32_t d, uint32_t metric, const float *Q, uint32_t nq,
                          const uint32_t *cand, uint32_t n_cand, uint32_t stride, uint32_t k, uint32_t *out_ids,
-                         float *out_dist, hipStream_t st);
+                         float *out_dist, hipStream_t st, const float *cand_keys = nullptr, uint32_t n_min = 0,
+                         float gamma = 0.0f, uint32_t *out_n = nullptr);
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 

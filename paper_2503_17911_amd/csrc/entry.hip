@@ -262,10 +262,10 @@ ann_status ann_build_entry_table(ann_index *index, uint32_t n_pivots, void *stre
   const LevelDev &L = index->level[0];
   ANN_HIP(hipMalloc((void **)&index->pivot_codes, (size_t)n_pivots * L.row_stride));
   ANN_HIP(hipMalloc((void **)&index->pivot_ids, (size_t)n_pivots * sizeof(uint32_t)));
-  if (index->metric == ANN_L2) ANN_HIP(hipMalloc((void **)&index->pivot_norm, (size_t)n_pivots * sizeof(float)));
+  if (index->key_metric == ANN_L2) ANN_HIP(hipMalloc((void **)&index->pivot_norm, (size_t)n_pivots * sizeof(float)));
   const uint64_t total = (uint64_t)n_pivots * (L.row_stride / 16);
   const int grid = (int)((total + 255) / 256 > 65535 ? 65535 : (total + 255) / 256);
-  gather_pivots_kernel<<<grid, 256, 0, st>>>(L.codes, index->metric == ANN_L2 ? L.norm_term : nullptr, index->n, n_pivots,
+  gather_pivots_kernel<<<grid, 256, 0, st>>>(L.codes, index->key_metric == ANN_L2 ? L.norm_term : nullptr, index->n, n_pivots,
                                              L.row_stride, index->pivot_codes, index->pivot_norm, index->pivot_ids);
   ANN_HIP(hipGetLastError());
   ANN_HIP(hipStreamSynchronize(st));
@@ -296,7 +296,7 @@ ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_
     }
     fold_scan_kernel<<<(nq + kFsQueries - 1) / kFsQueries, kFsThreads, smem, st>>>(
         q, nq, index->d, L.lo, L.delta, fw->tq, fw->tq_stride, fw->s, fw->qlo, fw->sum_t, index->pivot_codes,
-        index->pivot_norm, index->pivot_ids, index->n_pivots, L.row_stride, index->metric, out_entry_ids);
+        index->pivot_norm, index->pivot_ids, index->n_pivots, L.row_stride, index->key_metric, out_entry_ids);
     ANN_HIP(hipGetLastError());
     fw->folded_q = q;
     fw->folded_nq = nq;
@@ -307,7 +307,7 @@ ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_
   const Workspace &w = *lease.ws;
 #define ANN_ES(B, P)                                                                                                   \
   entry_scan_kernel<B, P><<<nq, 64, 0, st>>>(index->pivot_codes, index->pivot_norm, index->pivot_ids, index->n_pivots,   \
-                                             L.row_stride, L.row_stride / 16, index->metric, w.tq, w.tq_stride, w.s,    \
+                                             L.row_stride, L.row_stride / 16, index->key_metric, w.tq, w.tq_stride, w.s,    \
                                              w.qlo, w.sum_t, nq, n_entry, out_entry_ids)
   if (L.bits == 8) {
     switch (L.search_lanes) {

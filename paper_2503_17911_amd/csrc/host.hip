@@ -205,6 +205,8 @@ ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index 
   if (desc->degree == 0) return fail(ANN_EINVAL, "degree must be positive");
   if (desc->degree > ANN_MAX_DEGREE) return fail(ANN_ECAPACITY, "degree = %u exceeds ANN_MAX_DEGREE = %u", desc->degree, ANN_MAX_DEGREE);
   if (desc->metric != ANN_L2 && desc->metric != ANN_IP) return fail(ANN_EINVAL, "unknown metric %u", desc->metric);
+  if ((desc->flags & ANN_DESC_UNIT_NORM_L2_KEYS) && desc->metric != ANN_IP)
+    return fail(ANN_EINVAL, "ANN_DESC_UNIT_NORM_L2_KEYS is for ANN_IP indexes");
   if (desc->n_levels < 1 || desc->n_levels > ANN_MAX_LEVELS) return fail(ANN_EINVAL, "n_levels must be 1..%d", ANN_MAX_LEVELS);
   if (!desc->adjacency) return fail(ANN_EINVAL, "adjacency is NULL");
   if (desc->entry_point >= desc->n) return fail(ANN_EINVAL, "entry_point %u is not a node", desc->entry_point);
@@ -213,7 +215,8 @@ ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index 
     if (L.bits != 8 && L.bits != 4) return fail(ANN_EINVAL, "level %u: bits must be 4 or 8, got %u", l, L.bits);
     if (L.bits == 4 && (desc->d & 1)) return fail(ANN_EINVAL, "level %u: 4-bit codes need an even d", l);
     if (!L.codes || !L.lo || !L.delta) return fail(ANN_EINVAL, "level %u: codes, lo and delta must be given", l);
-    if (desc->metric == ANN_L2 && !L.norm_term) return fail(ANN_EINVAL, "level %u: norm_term is required for ANN_L2", l);
+    if ((desc->metric == ANN_L2 || (desc->flags & ANN_DESC_UNIT_NORM_L2_KEYS)) && !L.norm_term)
+      return fail(ANN_EINVAL, "level %u: norm_term is required for ANN_L2 and for ANN_DESC_UNIT_NORM_L2_KEYS", l);
   }
   const bool host = (desc->flags & ANN_DESC_HOST_POINTERS) != 0;
   const uint64_t n = desc->n;
@@ -224,6 +227,7 @@ ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index 
   ix->d = desc->d;
   ix->degree = desc->degree;
   ix->metric = desc->metric;
+  ix->key_metric = (desc->flags & ANN_DESC_UNIT_NORM_L2_KEYS) ? (uint32_t)ANN_L2 : desc->metric;
   ix->n_levels = desc->n_levels;
   ix->entry_point = desc->entry_point;
   (void)hipGetDevice(&ix->device);
@@ -347,7 +351,7 @@ ann_status ann_build_prs(ann_index *index, void *stream) {
   const LevelDev &L = index->level[0];
   const uint64_t slots = index->n * index->degree;
   ANN_HIP(hipMalloc((void **)&index->prs_codes, (size_t)slots * L.row_stride));
-  if (index->metric == ANN_L2) {
+  if (index->key_metric == ANN_L2) {
     hipError_t e = hipMalloc((void **)&index->prs_norm, (size_t)slots * sizeof(float));
     if (e != hipSuccess) {
       (void)hipFree(index->prs_codes);

@@ -36,16 +36,34 @@ __device__ __forceinline__ void rank_all(const uint64_t *list, uint32_t n, int l
 template <int LPR, bool VEC4>
 __global__ __launch_bounds__(64) void rerank_kernel(const float *__restrict__ X, uint32_t d, uint32_t metric,
                                                     const float *__restrict__ Q, uint32_t nq, uint64_t n,
-                                                    const uint32_t *__restrict__ cand_ids, uint32_t n_cand,
+                                                    const uint32_t *__restrict__ cand_ids, uint32_t n_max,
                                                     uint32_t cand_stride, uint32_t k, uint32_t *__restrict__ out_ids,
-                                                    float *__restrict__ out_dist) {
+                                                    float *__restrict__ out_dist,
+                                                    const float *__restrict__ cand_keys, uint32_t n_min, float gamma,
+                                                    uint32_t *__restrict__ out_n) {
   extern __shared__ uint64_t smem64[];
   float *qs = reinterpret_cast<float *>(smem64);             // [d], 16-byte aligned
-  uint64_t *list = smem64 + ((d + 3) / 4) * 2;               // [n_cand]
+  uint64_t *list = smem64 + ((d + 3) / 4) * 2;               // [n_max]
   const uint32_t qi = blockIdx.x;
   if (qi >= nq) return;
   const int lane = threadIdx.x, chunk = lane % LPR, grp = lane / LPR;
   constexpr int G = kWave / LPR;
+  // Length of the prefix that is re-evaluated.  Fixed (n_max), or chosen per
+  // query from the low-precision keys: every candidate whose key is not above
+  // key[k-1] + gamma * (key[k-1] - key[0]), at least n_min, at most n_max.
+  uint32_t n_cand = n_max;
+  if (cand_keys) {
+    const float *keys = cand_keys + (uint64_t)qi * cand_stride;
+    const float k0 = keys[0], kk = keys[k - 1 < n_max ? k - 1 : n_max - 1];
+    if (isfinite(kk)) {
+      const float thr = __fmaf_rn(gamma, __fsub_rn(kk, k0), kk);
+      uint32_t cnt = 0;
+      for (uint32_t i = lane; i < n_max; i += kWave) cnt += keys[i] <= thr ? 1u : 0u;
+      n_cand = (uint32_t)group_sum_i32<64>((int)cnt);
+      n_cand = n_cand < n_min ? n_min : n_cand;
+    }
+    if (out_n && lane == 0) out_n[qi] = n_cand;
+  }
   for (uint32_t j = lane; j < d; j += kWave) qs[j] = Q[(uint64_t)qi * d + j];
   __syncthreads();
   const uint32_t *cand = cand_ids + (uint64_t)qi * cand_stride;
@@ -232,8 +250,9 @@ __global__ __launch_bounds__(64) void rescore_kernel(const uint8_t *__restrict__
 template <bool VEC4>
 static void launch_rerank(uint32_t lpr, const float *X, uint32_t d, uint32_t metric, const float *Q, uint32_t nq,
                           uint64_t n, const uint32_t *cand, uint32_t n_cand, uint32_t stride, uint32_t k,
-                          uint32_t *out_ids, float *out_dist, size_t smem, hipStream_t st) {
-#define ANN_RR(L) rerank_kernel<L, VEC4><<<nq, 64, smem, st>>>(X, d, metric, Q, nq, n, cand, n_cand, stride, k, out_ids, out_dist)
+                          uint32_t *out_ids, float *out_dist, size_t smem, hipStream_t st, const float *cand_keys,
+                          uint32_t n_min, float gamma, uint32_t *out_n) {
+#define ANN_RR(L) rerank_kernel<L, VEC4><<<nq, 64, smem, st>>>(X, d, metric, Q, nq, n, cand, n_cand, stride, k, out_ids, out_dist, cand_keys, n_min, gamma, out_n)
   switch (lpr) {
     case 8: ANN_RR(8); break;
     case 16: ANN_RR(16); break;
@@ -246,15 +265,16 @@ static void launch_rerank(uint32_t lpr, const float *X, uint32_t d, uint32_t met
 // Shared by ann_rerank and the final stage of ann_bruteforce_topk.
 ann_status rerank_device(const float *X, uint64_t n, uint32_t d, uint32_t metric, const float *Q, uint32_t nq,
                          const uint32_t *cand, uint32_t n_cand, uint32_t stride, uint32_t k, uint32_t *out_ids,
-                         float *out_dist, hipStream_t st) {
+                         float *out_dist, hipStream_t st, const float *cand_keys, uint32_t n_min, float gamma,
+                         uint32_t *out_n) {
   // four 16-byte pieces of a row per lane: 128 dimensions -> 8 lanes per row, 8 rows side by side
   uint32_t chunks = (d + 3) / 4, lpr = 8;
   while (lpr * 4 < chunks && lpr < 64) lpr <<= 1;
   const size_t smem = (size_t)n_cand * sizeof(uint64_t) + (size_t)((d + 3) / 4) * 16;
   if (d % 4 == 0)
-    launch_rerank<true>(lpr, X, d, metric, Q, nq, n, cand, n_cand, stride, k, out_ids, out_dist, smem, st);
+    launch_rerank<true>(lpr, X, d, metric, Q, nq, n, cand, n_cand, stride, k, out_ids, out_dist, smem, st, cand_keys, n_min, gamma, out_n);
   else
-    launch_rerank<false>(lpr, X, d, metric, Q, nq, n, cand, n_cand, stride, k, out_ids, out_dist, smem, st);
+    launch_rerank<false>(lpr, X, d, metric, Q, nq, n, cand, n_cand, stride, k, out_ids, out_dist, smem, st, cand_keys, n_min, gamma, out_n);
   ANN_HIP(hipGetLastError());
   return ANN_OK;
 }
@@ -274,7 +294,23 @@ ann_status ann_rerank(ann_index *index, const float *q, uint32_t nq, const uint3
   if (cand_stride < n_cand) return fail(ANN_EINVAL, "ann_rerank: cand_stride = %u < n_cand = %u", cand_stride, n_cand);
   if (n_cand > 4096) return fail(ANN_ECAPACITY, "ann_rerank: n_cand = %u exceeds 4096", n_cand);
   return rerank_device(index->vectors, index->n, index->d, index->metric, q, nq, cand_ids, n_cand, cand_stride, k,
-                       out_ids, out_dist, (hipStream_t)stream);
+                       out_ids, out_dist, (hipStream_t)stream, nullptr, 0, 0.0f, nullptr);
+}
+
+ann_status ann_rerank_adaptive(ann_index *index, const float *q, uint32_t nq, const uint32_t *cand_ids,
+                               const float *cand_keys, uint32_t n_min, uint32_t n_max, uint32_t cand_stride,
+                               float gamma, uint32_t k, uint32_t *out_ids, float *out_dist, uint32_t *out_n,
+                               void *stream) {
+  if (!index || !q || !cand_ids || !cand_keys || !out_ids || !out_dist)
+    return fail(ANN_EINVAL, "ann_rerank_adaptive: NULL argument");
+  if (!index->vectors) return fail(ANN_EINVAL, "ann_rerank_adaptive: the index was uploaded without fp32 vectors");
+  if (nq == 0 || n_max == 0 || k == 0) return fail(ANN_EINVAL, "ann_rerank_adaptive: nq, n_max and k must be positive");
+  if (k > n_min || n_min > n_max) return fail(ANN_EINVAL, "ann_rerank_adaptive: need k <= n_min <= n_max, got %u, %u, %u", k, n_min, n_max);
+  if (cand_stride < n_max) return fail(ANN_EINVAL, "ann_rerank_adaptive: cand_stride = %u < n_max = %u", cand_stride, n_max);
+  if (n_max > 4096) return fail(ANN_ECAPACITY, "ann_rerank_adaptive: n_max = %u exceeds 4096", n_max);
+  if (!(gamma >= 0.0f)) return fail(ANN_EINVAL, "ann_rerank_adaptive: gamma must be >= 0");
+  return rerank_device(index->vectors, index->n, index->d, index->metric, q, nq, cand_ids, n_max, cand_stride, k,
+                       out_ids, out_dist, (hipStream_t)stream, cand_keys, n_min, gamma, out_n);
 }
 
 ann_status ann_rescore(ann_index *index, uint32_t level, const float *q, uint32_t nq, const uint32_t *cand_ids,
@@ -291,10 +327,10 @@ ann_status ann_rescore(ann_index *index, uint32_t level, const float *q, uint32_
   if (rc != ANN_OK) return rc;
   const LevelDev &L = index->level[level];
   const Workspace &w = *lease.ws;
-  const float *norm = index->metric == ANN_L2 ? L.norm_term : nullptr;
+  const float *norm = index->key_metric == ANN_L2 ? L.norm_term : nullptr;
   const size_t smem = (size_t)n_cand * (sizeof(uint64_t) + sizeof(int32_t));
 #define ANN_RS(B, P)                                                                                              \
-  rescore_kernel<B, P><<<nq, 64, smem, st>>>(L.codes, L.row_stride, L.row_stride / 16, norm, index->metric,       \
+  rescore_kernel<B, P><<<nq, 64, smem, st>>>(L.codes, L.row_stride, L.row_stride / 16, norm, index->key_metric,   \
                                              index->n, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t, nq, cand_ids,     \
                                              n_cand, cand_stride, out_ids, out_keys, out_idot)
   if (L.bits == 8) {

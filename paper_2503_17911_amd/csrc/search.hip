@@ -84,7 +84,7 @@ ann_status launch_search_with(const ann_index *index, uint32_t nq, const ann_sea
   const LevelDev &L = index->level[0];
   SearchArgs a{};
   a.codes = L.codes;
-  a.norm_term = index->metric == ANN_L2 ? L.norm_term : nullptr;
+  a.norm_term = index->key_metric == ANN_L2 ? L.norm_term : nullptr;
   a.adjacency = index->adjacency;
   a.tq = w.tq;
   a.s = w.s;
@@ -94,7 +94,7 @@ ann_status launch_search_with(const ann_index *index, uint32_t nq, const ann_sea
   a.order = params->query_order;
   a.ef_per_query = params->ef_per_query;
   a.prs_codes = params->layout == 1 ? index->prs_codes : nullptr;
-  a.prs_norm = params->layout == 1 && index->metric == ANN_L2 ? index->prs_norm : nullptr;
+  a.prs_norm = params->layout == 1 && index->key_metric == ANN_L2 ? index->prs_norm : nullptr;
   a.labels = params->alpha_s > 0.0f ? index->labels : nullptr;
   a.alpha_s = params->alpha_s;
   a.m_s = params->m_s == 0 || params->m_s > index->degree ? index->degree : params->m_s;
@@ -107,7 +107,7 @@ ann_status launch_search_with(const ann_index *index, uint32_t nq, const ann_sea
   a.row_stride = L.row_stride;
   a.n_chunks = L.row_stride / 16;
   a.degree = index->degree;
-  a.metric = index->metric;
+  a.metric = index->key_metric;  // the form of the traversal key
   a.tq_stride = w.tq_stride;
   a.n_entry = entry_ids ? n_entry : 0;
   a.entry_point = index->entry_point;

@@ -51,7 +51,7 @@ def gpu_sq_fit(X, bits, coverage=1.0):
 class GpuIndex:
     """Device index built from numpy arrays (oracle-encoded or GPU-encoded levels)."""
 
-    def __init__(self, X, adj, entry, levels, metric, csr=None, host_pointers=False, labels=None):
+    def __init__(self, X, adj, entry, levels, metric, csr=None, host_pointers=False, labels=None, unit_norm_l2_keys=False):
         self.n, self.d = X.shape
         self.metric = metric
         keep = []
@@ -78,13 +78,15 @@ class GpuIndex:
             self.degree = degree
             self.handle = ann.ann_upload_index(n=self.n, d=self.d, degree=degree, metric=metric, vectors=xv,
                                                levels=lv, adjacency=cols_d, csr_offsets=offs_d, entry_point=entry,
-                                               edge_labels=lab, host_pointers=host_pointers, stream=stream_ptr())
+                                               edge_labels=lab, host_pointers=host_pointers, unit_norm_l2_keys=unit_norm_l2_keys,
+                                               stream=stream_ptr())
         else:
             self.degree = adj.shape[1]
             adj_d = conv_u32(adj)
             self.handle = ann.ann_upload_index(n=self.n, d=self.d, degree=self.degree, metric=metric, vectors=xv,
                                                levels=lv, adjacency=adj_d, entry_point=entry, edge_labels=lab,
-                                               host_pointers=host_pointers, stream=stream_ptr())
+                                               host_pointers=host_pointers, unit_norm_l2_keys=unit_norm_l2_keys,
+                                               stream=stream_ptr())
         torch.cuda.synchronize()
 
     def close(self):
@@ -161,6 +163,17 @@ class GpuIndex:
         ann.ann_rerank(self.handle, qd, nq, cd, n_cand, stride, k, ids, dist, stream_ptr())
         torch.cuda.synchronize()
         return as_u32(ids), dist.cpu().numpy()
+
+
+def rerank_adaptive(ix, Q, cand, keys, n_min, n_max, gamma, k):
+    nq, stride = cand.shape
+    qd, cd, kd = dev(Q), u32(cand), dev(np.ascontiguousarray(keys, np.float32))
+    ids = torch.empty((nq, k), dtype=torch.int32, device=DEV)
+    dist = torch.empty((nq, k), dtype=torch.float32, device=DEV)
+    n_r = torch.empty(nq, dtype=torch.int32, device=DEV)
+    ann.ann_rerank_adaptive(ix.handle, qd, nq, cd, kd, n_min, n_max, stride, gamma, k, ids, dist, n_r, stream_ptr())
+    torch.cuda.synchronize()
+    return as_u32(ids), dist.cpu().numpy(), as_u32(n_r)
 
 
 def gpu_bruteforce(X, Q, k, metric):

@@ -391,6 +391,71 @@ def test_rerank_and_rescore(H, metric):
     ix.close()
 
 
+@pytest.mark.parametrize("bits,d,R,P", [(8, 96, 32, 1), (4, 768, 48, 4), (4, 100, 16, 4), (8, 128, 32, 4)])
+def test_unit_norm_index_with_euclidean_form_keys(H, bits, d, R, P):
+    """ANN_DESC_UNIT_NORM_L2_KEYS: an inner-product index whose traversal, entry
+    scan and rescore keys take the Euclidean form; the oracle's counterpart is
+    its search with the L2 key on the same codes, while the rerank stays -<q, x>."""
+    n, nq, ef, k = 2500, 24, 96, 10
+    w, X, Q, adj = small_case(n, d, R, nq, seed=d + bits, metric="ip", bits=bits, normalize=True)
+    lv, l8 = oracle.sq_fit(X, bits), oracle.sq_fit(X, 8)
+    ix = H.GpuIndex(X, adj, 0, [lv, l8], oracle.IP, unit_norm_l2_keys=True)
+    for kw in (dict(), dict(visited_slots=0)):
+        gpu = ix.search(Q, ef, mode=int(P > 1), expansions_per_step=P if P > 1 else 0, **kw)
+        orc = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=oracle.L2, expansions_per_step=P)
+        assert_search_equal(gpu, orc, check_counts=not kw)
+    plain = H.GpuIndex(X, adj, 0, [lv, l8], oracle.IP)
+    assert_search_equal(plain.search(Q, ef), oracle.search_batch(lv, d, adj, 0, Q, ef, metric=oracle.IP))
+    plain.close()
+    for n_piv, n_ent in ((200, 1), (64, 3)):
+        want = oracle.entry_scan(lv, d, Q, n_piv, n_ent, metric=oracle.L2)
+        assert (ix.entry_scan(Q, n_piv, n_ent) == want).all()
+    oid, okeys, odots = oracle.rescore_batch(l8, d, Q, orc[0], metric=oracle.L2)
+    gid, gkeys, gdots = ix.rescore(Q, gpu[0], level=1)
+    assert (gid == oid).all() and (gdots == odots).all() and (gkeys.view(np.uint32) == okeys.view(np.uint32)).all()
+    rid, rdist = ix.rerank(Q, gid, 2 * k, k)
+    roid, rodist = oracle.rerank_batch(X, Q, oid[:, :2 * k], k, metric=oracle.IP)
+    H.check_rerank(rid, rdist, roid, rodist)
+    assert (rdist <= 0).all()                    # still the negated inner product
+    ix.close()
+    import paper_2503_17911_amd as ann
+    with pytest.raises(ann.AnnError):            # the flag is for inner-product indexes
+        H.GpuIndex(X, adj, 0, [lv], oracle.L2, unit_norm_l2_keys=True)
+
+
+@pytest.mark.parametrize("metric,bits,d", [("l2", 4, 960), ("ip", 8, 96), ("l2", 8, 30)])
+def test_adaptive_rerank_length(H, metric, bits, d):
+    """ann_rerank_adaptive: the per-query prefix length equals the oracle's rule
+    exactly (the threshold is one fp32 subtraction and one fma on both sides),
+    and the rerank of that prefix equals the oracle's."""
+    n, nq, ef, k = 3000, 40, 128, 10
+    w, X, Q, adj = small_case(n, d, 16, nq, seed=d + 1, metric=metric, bits=bits, normalize=(metric == "ip"))
+    m = metric_id(metric)
+    lv = oracle.sq_fit(X, bits)
+    ix = H.GpuIndex(X, adj, 0, [lv], m)
+    ids, keys, _, _ = ix.search(Q, ef, want_idot=False)
+    oi, ok, _, _ = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m)
+    assert (ids == oi).all() and (keys.view(np.uint32) == ok.view(np.uint32)).all()
+    seen = set()
+    for n_min, n_max, gamma in ((k, ef, 0.0), (2 * k, ef, 0.5), (k, ef, 2.0), (k, 40, 1.0), (k, ef, 1e30), (ef, ef, 0.3)):
+        rid, rdist, n_r = H.rerank_adaptive(ix, Q, ids, keys, n_min, n_max, gamma, k)
+        oid, odist, on = oracle.rerank_adaptive(X, Q, oi, ok, n_min, n_max, k, gamma, metric=m)
+        assert (n_r == on).all(), (n_min, n_max, gamma)
+        H.check_rerank(rid, rdist, oid, odist)
+        seen.update(on.tolist())
+    assert len(seen) > 5                          # the rule did choose different lengths
+    # a pool shorter than k: every candidate is taken
+    short = ids.copy()
+    short[:, 4:] = PAD
+    skeys = keys.copy()
+    skeys[:, 4:] = np.inf
+    rid, rdist, n_r = H.rerank_adaptive(ix, Q, short, skeys, k, ef, 0.5, k)
+    oid, odist, on = oracle.rerank_adaptive(X, Q, short, skeys, k, ef, k, 0.5, metric=m)
+    assert (n_r == on).all() and (n_r == ef).all()
+    H.check_rerank(rid, rdist, oid, odist)
+    ix.close()
+
+
 @pytest.mark.parametrize("n,d,nq,k,metric", [(4000, 64, 70, 10, "l2"), (3001, 128, 33, 10, "ip"),
                                               (2500, 100, 5, 100, "l2"), (130, 960, 40, 10, "l2"),
                                               (50, 16, 3, 64, "ip"), (3000, 30, 20, 10, "l2"),

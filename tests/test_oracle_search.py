@@ -280,3 +280,54 @@ def test_entry_scan_is_bruteforce_over_the_pivot_sample():
                 order = sorted((float(k[v]), v) for v in piv)[:E]
                 want = [v for _, v in order] + [PAD] * (E - len(order))
                 assert got[qi].tolist() == want
+
+
+def test_rerank_length_rule_hand_cases():
+    """The per-query rerank length: candidates whose key is within gamma times the
+    spread of the first k keys above the k-th key, clamped to [n_min, n_max]."""
+    inf = np.inf
+    keys = np.array([[1, 2, 3, 4, 5, 6, 7, 8],            # k = 3: key0 = 1, key_k = 3
+                     [1, 2, 3, 3, 3, 9, 9, 9],            # ties with the k-th key count
+                     [5, 5, 5, 5, 5, 5, 5, 6],            # no spread: only ties with the k-th key
+                     [1, 2, inf, inf, inf, inf, inf, inf],  # fewer than k candidates
+                     [-8, -6, -4, -3.5, -3, 0, 1, 2]], np.float32)
+    assert oracle.rerank_length(keys, 3, 8, 3, 0.0).tolist() == [3, 5, 7, 8, 3]
+    assert oracle.rerank_length(keys, 3, 8, 3, 0.5).tolist() == [4, 5, 7, 8, 5]      # thresholds 4, 4, 5, -, -2
+    assert oracle.rerank_length(keys, 3, 8, 3, 1e9).tolist() == [8, 8, 7, 8, 8]      # zero spread stays zero
+    assert oracle.rerank_length(keys, 6, 8, 3, 0.0).tolist() == [6, 6, 7, 8, 6]      # at least n_min
+    assert oracle.rerank_length(keys, 3, 4, 3, 1e9).tolist() == [4, 4, 4, 4, 4]      # at most n_max
+
+
+def test_adaptive_rerank_is_exact_knn_of_the_chosen_prefix():
+    w, X, Q, adj = small_case(400, 24, 6, 9, seed=61)
+    lv = oracle.sq_fit(X, 4)
+    ids, keys, _, _ = oracle.search_batch(lv, w.d, adj, 0, Q, 64)
+    rid, rdist, n_r = oracle.rerank_adaptive(X, Q, ids, keys, 6, 64, 5, 1.5)
+    assert (n_r >= 6).all() and (n_r <= 64).all() and len(set(n_r.tolist())) > 1
+    X64, Q64 = X.astype(np.float64), Q.astype(np.float64)
+    for qi in range(len(Q)):
+        cand = ids[qi, :n_r[qi]]
+        cand = cand[cand != PAD]
+        dist = ((Q64[qi] - X64[cand]) ** 2).sum(1)
+        order = np.lexsort((cand, dist.astype(np.float32)))[:5]
+        assert rid[qi].tolist() == cand[order].tolist()
+    full, _, n_all = oracle.rerank_adaptive(X, Q, ids, keys, 6, 64, 5, 1e30)
+    want, _ = oracle.rerank_batch(X, Q, ids, 5)
+    assert (n_all == 64).all() and (full == want).all()
+
+
+def test_euclidean_form_keys_rank_unit_vectors_better_than_inner_product_keys():
+    """On unit-norm data the inner-product order and the Euclidean order are the
+    same for exact vectors.  With 4-bit codes the Euclidean form of the key
+    (stored norm of the decoded vector minus twice the inner product, Section
+    5.2) is closer to that order than the bare inner product with the decoded
+    vector: measured here with ef >= n, where the pool is every node in key order."""
+    w, X, Q, adj = small_case(600, 96, 8, 20, seed=71, metric="ip", normalize=True)
+    lv = oracle.sq_fit(X, 4)
+    gt, _ = oracle.bruteforce_topk(X, Q, 10, metric=oracle.IP)
+    gt_l2, _ = oracle.bruteforce_topk(X, Q, 10, metric=oracle.L2)
+    assert (gt == gt_l2).all()                                  # same neighbours under either metric
+    ip_ids, *_ = oracle.search_batch(lv, w.d, adj, 0, Q, 600, metric=oracle.IP)
+    l2_ids, *_ = oracle.search_batch(lv, w.d, adj, 0, Q, 600, metric=oracle.L2)
+    r_ip, r_l2 = oracle.recall(ip_ids, gt), oracle.recall(l2_ids, gt)
+    assert r_l2 > r_ip + 0.02, (r_ip, r_l2)
