@@ -82,6 +82,12 @@ def main():
                          "pivots (0 = natural order; with --pivots the entry scan's result is the key)")
     ap.add_argument("--coverage", type=float, default=1.0,
                     help="codebook range: 1 = per-dimension min/max, below 1 = truncated (symmetric order statistics)")
+    ap.add_argument("--unit-norm-l2-keys", action="store_true",
+                    help="inner-product workloads with unit-norm vectors: low-precision keys in the Euclidean form")
+    ap.add_argument("--rerank-gamma", type=float, default=-1.0,
+                    help=">= 0: per-query rerank length from the key gap (ann_rerank_adaptive) instead of the fixed prefix")
+    ap.add_argument("--rerank-max", type=int, default=0, help="longest reranked prefix with --rerank-gamma (0 = ef)")
+    ap.add_argument("--rerank-mult", type=int, default=0, help="fixed rerank prefix in units of k (0 = the workload's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bruteforce", action="store_true",
                     help="time the exact brute-force search alone (the ground-truth stage) on the workload's vectors "
@@ -110,7 +116,8 @@ def main():
         w = w.scaled(w.n, nq=args.nq, n_clusters=w.n_clusters)
     metric = ann.L2 if w.metric == "l2" else ann.IP
     bits = w.bits[0]
-    k, n_rerank = w.k, w.rerank_mult * w.k
+    k, n_rerank = w.k, (args.rerank_mult or w.rerank_mult) * w.k
+    adaptive = args.rerank_gamma >= 0.0
     if args.bruteforce:
         bruteforce_only(w, metric)
         return
@@ -150,7 +157,7 @@ def main():
     adj_d = torch.from_numpy(adj.view(np.int32)).to(dev)
     index = ann.ann_upload_index(n=n, d=d, degree=adj.shape[1], metric=metric, vectors=xd,
                                  levels=levels, adjacency=adj_d, entry_point=entry,
-                                 stream=st)
+                                 unit_norm_l2_keys=args.unit_norm_l2_keys, stream=st)
     del codes, adj_d, levels
     torch.cuda.synchronize()
 
@@ -195,11 +202,23 @@ def main():
         ann.ann_schedule_queries(keys, nq_, n, order, st)
         return order
 
+    key_bufs = {}
+
+    def keys_of(t):
+        """The key buffer that goes with an id buffer (only kept when the rerank length depends on the keys)."""
+        if not adaptive:
+            return None
+        if t.data_ptr() not in key_bufs:
+            key_bufs[t.data_ptr()] = torch.empty(t.shape, dtype=torch.float32, device=dev)
+        return key_bufs[t.data_ptr()]
+
+    n_reranked = {}
+
     def search(q_, nq_, ef, mode, pool, entries_, counts=None, complete_table=False):
         if entries_ is not None:
             ann.ann_entry_scan(index, q_, nq_, args.n_entry, entries_, st)
         order = schedule(q_, nq_, entries_)
-        ann.ann_search_batch(index, q_, nq_, k=k, ef=ef, mode=mode, out_ids=pool, out_counts=counts,
+        ann.ann_search_batch(index, q_, nq_, k=k, ef=ef, mode=mode, out_ids=pool, out_keys=keys_of(pool), out_counts=counts,
                              entry_ids=entries_, n_entry=args.n_entry if entries_ is not None else 0,
                              layout=args.layout, expansions_per_step=args.expansions if mode == 1 else 0,
                              visited_slots=8192 if complete_table else args.visited_slots,
@@ -222,8 +241,15 @@ def main():
             key = (nq_, ef)
             if key not in rescored:
                 rescored[key] = torch.empty((nq_, ef), dtype=torch.int32, device=dev)
-            ann.ann_rescore(index, 1, q_, nq_, pool, ef, ef, rescored[key], None, None, st)
+            ann.ann_rescore(index, 1, q_, nq_, pool, ef, ef, rescored[key], keys_of(rescored[key]), None, st)
             src = rescored[key]
+        if adaptive:
+            if nq_ not in n_reranked:
+                n_reranked[nq_] = torch.empty(nq_, dtype=torch.int32, device=dev)
+            ann.ann_rerank_adaptive(index, q_, nq_, src, keys_of(src), min(n_rerank, ef), min(args.rerank_max or ef, ef), ef,
+                                    args.rerank_gamma, k, out_ids if ids_ is None else ids_,
+                                    out_dist if dist_ is None else dist_, n_reranked[nq_], st)
+            return
         ann.ann_rerank(index, q_, nq_, src, min(n_rerank, ef), ef, k, out_ids if ids_ is None else ids_,
                        out_dist if dist_ is None else dist_, st)
 
@@ -304,7 +330,7 @@ def main():
             ann.ann_entry_scan(index, qd, nq, args.n_entry, entries, st)
         order = schedule(qd, nq, entries)
         e_begin[i].record()
-        ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=mode, out_ids=pool,
+        ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=mode, out_ids=pool, out_keys=keys_of(pool),
                              entry_ids=entries, n_entry=args.n_entry if entries is not None else 0, layout=args.layout,
                              expansions_per_step=args.expansions if mode == 1 else 0,
                              visited_slots=args.visited_slots, visited_kind=args.visited_kind,
@@ -394,7 +420,7 @@ def main():
         order = schedule(qb, nq, entries)
         if timed:
             rb[i].record()
-        ann.ann_search_batch(index, qb, nq, k=k, ef=ef, mode=mode, out_ids=pool,
+        ann.ann_search_batch(index, qb, nq, k=k, ef=ef, mode=mode, out_ids=pool, out_keys=keys_of(pool),
                              entry_ids=entries, n_entry=args.n_entry if entries is not None else 0, layout=args.layout,
                              expansions_per_step=args.expansions if mode == 1 else 0,
                              visited_slots=args.visited_slots, visited_kind=args.visited_kind,
@@ -444,7 +470,7 @@ def main():
             order = schedule(qd, nq, entries)
             if i >= 0:
                 xb[i].record()
-            ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=0, out_ids=pool,
+            ann.ann_search_batch(index, qd, nq, k=k, ef=ef, mode=0, out_ids=pool, out_keys=keys_of(pool),
                                  entry_ids=entries, n_entry=args.n_entry if entries is not None else 0, layout=args.layout,
                                  visited_slots=args.visited_slots, visited_kind=args.visited_kind,
                                  query_order=order, reuse_folded_queries=order is not None or entries is not None,
@@ -483,7 +509,7 @@ def main():
         q1 = qd[i % nq:i % nq + 1]
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        ann.ann_search_batch(index, q1, 1, k=k, ef=ef, mode=mode, out_ids=pool1, layout=args.layout,
+        ann.ann_search_batch(index, q1, 1, k=k, ef=ef, mode=mode, out_ids=pool1, out_keys=keys_of(pool1), layout=args.layout,
                              expansions_per_step=args.expansions if mode == 1 else 0,
                              visited_slots=args.visited_slots, visited_kind=args.visited_kind, stream=st)
         finish(pool1, ef, 1, q1, ids1, dist1)
@@ -509,7 +535,7 @@ def main():
             if scheduling:          # the entry scan's result is the scheduling key: no second scan
                 ann.ann_schedule_queries(ent, nq, n, v_order, st)
                 order_v = v_order
-            ann.ann_search_batch(index, qd, nq, k=k, ef=ef_v, mode=1, out_ids=pool_v, entry_ids=ent, n_entry=1,
+            ann.ann_search_batch(index, qd, nq, k=k, ef=ef_v, mode=1, out_ids=pool_v, out_keys=keys_of(pool_v), entry_ids=ent, n_entry=1,
                                  query_order=order_v, reuse_folded_queries=True, stream=st)
             finish(pool_v, ef_v)
 
@@ -538,7 +564,7 @@ def main():
     # (the index keeps one query workspace per stream): the next batch fills the
     # chip while the previous one drains
     pipelined = None
-    if entries is None and len(w.bits) == 1 and not args.layout:
+    if entries is None and len(w.bits) == 1 and not args.layout and not adaptive:
         ann.ann_build_entry_table(index, args.schedule_pivots or 256, st)
         lanes = []
         for q_lane, ids_lane in ((qd, ref_ids), (q_second, ids_second)):    # two different batches
@@ -577,7 +603,7 @@ def main():
     # make; ids are mapped back before recall is taken).  Region = the closest of
     # 1024 pivots, found with the library's own pivot scan over the base vectors.
     relabel = None
-    if entries is None and len(w.bits) == 1 and not args.layout and args.coverage == 1.0:
+    if entries is None and len(w.bits) == 1 and not args.layout and args.coverage == 1.0 and not adaptive and not args.unit_norm_l2_keys:
         ann.ann_build_entry_table(index, 1024, st)
         region = torch.empty(n, dtype=torch.int32, device=dev)
         ann.ann_entry_scan(index, xd, n, 1, region, st)
@@ -636,7 +662,7 @@ def main():
     shape_label = {1_000_000: "1M", 10_000_000: "10M", 5_000_000: "5M"}.get(n, str(n)) + f" x {d} " + \
         "->".join(f"SQ{b}" for b in w.bits)
     mfma_scan = scheduling and bits == 8 and d <= 256 and (entries is None or args.n_entry == 1)
-    default_config = (args.workload == "c2" and not args.n and not args.nq and not args.visited_slots and not args.visited_kind
+    default_config = (not adaptive and not args.unit_norm_l2_keys and not args.rerank_mult and args.workload == "c2" and not args.n and not args.nq and not args.visited_slots and not args.visited_kind
                       and not args.pivots and not args.layout and not args.expansions and args.coverage == 1.0
                       and args.schedule_pivots == 256
                       and ef == 128 and mode == 1)
@@ -664,6 +690,10 @@ def main():
                                    "scheduled by the entry scan's result" if scheduling else "natural"),
                    "matrix_cores_in_timed_step": ("int8 MFMA in the pivot scan that orders the batch (a dense integer contraction, "
                                                   "exact); none in the search, rescore or rerank kernels") if mfma_scan else "none",
+                   "codebook": "per-dimension min/max" if args.coverage >= 1.0 else f"truncated range, coverage {args.coverage}",
+                   "key_form": "Euclidean form on unit-norm inner-product data" if args.unit_norm_l2_keys else "the metric's own",
+                   "rerank": (f"per-query prefix from the key gap: gamma {args.rerank_gamma}, {min(n_rerank, ef)}..{min(args.rerank_max or ef, ef)} "
+                              f"candidates, mean {float(n_reranked[nq].float().mean()):.1f}" if adaptive else f"fixed prefix of {min(n_rerank, ef)}"),
                    "entry": "medoid" if not args.pivots else f"closest {args.n_entry} of {args.pivots} scanned pivots",
                    "ef": ef, "mode": "exact" if mode == 0 else "multi-expansion", f"recall_at_{k}": round(rec, 4),
                    "recall_target_met": bool(rec >= 0.95), "evaluations_per_query": round(float(c[:, 1].mean()), 1),
@@ -703,7 +733,8 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, args.coverage)
+        result["cpu_baseline"] = cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, args.coverage,
+                                              key_metric=ann.L2 if args.unit_norm_l2_keys else metric)
 
     ann.ann_free_index(index)
     print(json.dumps(result), flush=True)
@@ -735,7 +766,43 @@ def bruteforce_only(w, metric):
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, coverage=1.0):
+def oracle_fit_threaded(oracle, X, bits, coverage, threads):
+    """The oracle's codebook training and encoding, split over the host's cores:
+    training by blocks of columns (each dimension is trained on its own),
+    encoding by blocks of rows.  Same functions, same results as one call."""
+    import numpy as np
+    n, d = X.shape
+    lo, delta = np.empty(d, np.float32), np.empty(d, np.float32)
+    col_blocks = [b for b in np.array_split(np.arange(d), threads) if len(b)]
+
+    def train(b):
+        Xb = np.ascontiguousarray(X[:, b[0]:b[-1] + 1])
+        lo[b[0]:b[-1] + 1], delta[b[0]:b[-1] + 1] = (oracle.sq_train(Xb, bits) if coverage >= 1.0
+                                                     else oracle.sq_train_truncated(Xb, bits, coverage))
+        log(f"[bench] oracle codebook: columns {b[0]}..{b[-1]} done")
+
+    ts = [threading.Thread(target=train, args=(b,)) for b in col_blocks]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    rb = d if bits == 8 else (d + 1) // 2
+    codes, norm = np.empty((n, rb), np.uint8), np.empty(n, np.float32)
+    row_blocks = [b for b in np.array_split(np.arange(n), threads) if len(b)]
+
+    def encode(b):
+        L = oracle.sq_encode(X[b[0]:b[-1] + 1], bits, lo, delta)
+        codes[b[0]:b[-1] + 1], norm[b[0]:b[-1] + 1] = L.codes, L.norm_term
+
+    ts = [threading.Thread(target=encode, args=(b,)) for b in row_blocks]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    return oracle.SQLevel(bits, lo, delta, codes, norm)
+
+
+def cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, coverage=1.0, key_metric=None):
     """The CPU oracle as it stands (plain C++, -O2, no SIMD intrinsics), timed
     on this host: same workload, same ef, search + rerank, on a bounded sample
     of the queries split over the host's cores (queries are independent)."""
@@ -747,13 +814,14 @@ def cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, coverage=1.0):
     except AttributeError:
         cores = os.cpu_count() or 1
     threads = max(1, min(16, cores))
+    key_metric = metric if key_metric is None else key_metric
     t0 = time.time()
-    level = oracle.sq_fit(X, w.bits[0], coverage=coverage)
+    level = oracle_fit_threaded(oracle, X, w.bits[0], coverage, threads)
     log(f"[bench] oracle encode {time.time() - t0:.1f}s")
     # size the sample from a short probe so that the timed part is ~15 s of CPU work
     probe = Q[:32]
     t0 = time.perf_counter()
-    oracle.search_batch(level, w.d, adj, entry, probe, ef, metric=metric)
+    oracle.search_batch(level, w.d, adj, entry, probe, ef, metric=key_metric)
     per_q = (time.perf_counter() - t0) / len(probe)
     want = 15.0 / max(per_q, 1e-6)                      # queries worth ~15 s of CPU work
     sample = int(min(len(Q), max(threads * 8, want)))
@@ -765,7 +833,7 @@ def cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, coverage=1.0):
         if len(idx) == 0:
             return
         for _ in range(passes):
-            ids, _, _, _ = oracle.search_batch(level, w.d, adj, entry, Qs[idx], ef, metric=metric)
+            ids, _, _, _ = oracle.search_batch(level, w.d, adj, entry, Qs[idx], ef, metric=key_metric)
             oracle.rerank_batch(X, Qs[idx], ids[:, :min(n_rerank, ef)], k, metric=metric)
 
     ts = [threading.Thread(target=work, args=(p,)) for p in parts]
