@@ -272,6 +272,16 @@ ann_status ann_query_prep(ann_index *index, uint32_t level, const float *q, uint
  * Errors: ANN_EINVAL, ANN_ENOMEM.
  */
 ann_status ann_build_prs(ann_index *index, void *stream);
+/*
+ * The same with a redundancy ratio below 1 (the paper's delta, Section 3.3):
+ * only the first ceil(ratio * degree) slots of every adjacency row get their
+ * neighbours' code rows stored with the node; an expansion reads those in one
+ * sweep and gathers the unvisited neighbours of the remaining slots from the
+ * code table.  Results are the same for every ratio; memory is n *
+ * ceil(ratio * degree) * row_stride bytes.  ratio in (0, 1]; a call with
+ * another ratio replaces the earlier copy (device-wide wait).  Synchronous.
+ */
+ann_status ann_build_prs_ratio(ann_index *index, float ratio, void *stream);
 
 /*
  * Entry-point stage: per-query initial nodes I for Algorithm 1 (which takes

@@ -56,8 +56,9 @@ struct ann_index {
   float *vectors = nullptr;    // [n][d] or nullptr
   uint32_t *adjacency = nullptr;  // [n][degree]
   float *labels = nullptr;        // [n][degree] edge labels or nullptr
-  uint8_t *prs_codes = nullptr;    // redundant layout: [n][degree][row_stride] level-0 code rows of each node's neighbours
-  float *prs_norm = nullptr;       // [n][degree] their norm terms (L2)
+  uint8_t *prs_codes = nullptr;    // redundant layout: [n][prs_slots][row_stride] level-0 code rows of each node's first neighbours
+  float *prs_norm = nullptr;       // [n][prs_slots] their norm terms (L2)
+  uint32_t prs_slots = 0;          // slots per node stored that way (redundancy ratio = prs_slots / degree)
   uint8_t *pivot_codes = nullptr;  // entry-point stage: [n_pivots][row_stride] level-0 codes of the sampled nodes
   float *pivot_norm = nullptr;     // [n_pivots] their norm terms (L2)
   uint32_t *pivot_ids = nullptr;   // [n_pivots] their node ids

@@ -68,21 +68,23 @@ __global__ void check_rows_distinct_kernel(const uint32_t *__restrict__ adj, uin
   }
 }
 
-// Redundant layout: slot (i, t) receives a copy of the code row (and norm term)
-// of neighbour adjacency[i][t]; padding slots are zero.
+// Redundant layout: entry (i, t), t < stored, receives a copy of the code row
+// (and norm term) of neighbour adjacency[i][t]; padding slots are zero.
 __global__ void build_prs_kernel(const uint32_t *__restrict__ adj, const uint8_t *__restrict__ codes,
-                                 const float *__restrict__ norm, uint64_t slots, uint64_t n, uint32_t row_stride,
-                                 uint8_t *__restrict__ out_codes, float *__restrict__ out_norm) {
+                                 const float *__restrict__ norm, uint64_t n, uint32_t degree, uint32_t stored,
+                                 uint32_t row_stride, uint8_t *__restrict__ out_codes, float *__restrict__ out_norm) {
   const uint32_t cpr = row_stride / 16;
-  const uint64_t total = slots * cpr;
+  const uint64_t total = n * stored * cpr;
   for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < total; e += (uint64_t)gridDim.x * blockDim.x) {
-    const uint64_t slot = e / cpr;
-    const uint32_t c = (uint32_t)(e - slot * cpr);
-    const uint32_t v = adj[slot];
+    const uint64_t entry = e / cpr;
+    const uint32_t c = (uint32_t)(e - entry * cpr);
+    const uint64_t node = entry / stored;
+    const uint32_t t = (uint32_t)(entry - node * stored);
+    const uint32_t v = adj[node * degree + t];
     const bool real = v != ANN_PAD_ID && v < n;
     reinterpret_cast<uint4 *>(out_codes)[e] =
         real ? reinterpret_cast<const uint4 *>(codes + (uint64_t)v * row_stride)[c] : make_uint4(0, 0, 0, 0);
-    if (c == 0 && out_norm) out_norm[slot] = real ? norm[v] : 0.0f;
+    if (c == 0 && out_norm) out_norm[entry] = real ? norm[v] : 0.0f;
   }
 }
 
@@ -344,27 +346,46 @@ ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index 
   return ANN_OK;
 }
 
-ann_status ann_build_prs(ann_index *index, void *stream) {
+ann_status ann_build_prs_ratio(ann_index *index, float ratio, void *stream) {
   hipStream_t st = (hipStream_t)stream;
-  if (!index) return fail(ANN_EINVAL, "ann_build_prs: index is NULL");
-  if (index->prs_codes) return ANN_OK;
+  if (!index) return fail(ANN_EINVAL, "ann_build_prs_ratio: index is NULL");
+  if (!(ratio > 0.0f && ratio <= 1.0f)) return fail(ANN_EINVAL, "ann_build_prs_ratio: the ratio must be in (0, 1]");
+  uint32_t stored = (uint32_t)((double)ratio * index->degree + 0.999999);
+  if (stored < 1) stored = 1;
+  if (stored > index->degree) stored = index->degree;
+  if (index->prs_codes && index->prs_slots == stored) return ANN_OK;
+  if (index->prs_codes) {
+    ANN_HIP(hipDeviceSynchronize());  // a search may still be reading the old copy
+    (void)hipFree(index->prs_codes);
+    (void)hipFree(index->prs_norm);
+    index->prs_codes = nullptr;
+    index->prs_norm = nullptr;
+    index->prs_slots = 0;
+  }
   const LevelDev &L = index->level[0];
-  const uint64_t slots = index->n * index->degree;
-  ANN_HIP(hipMalloc((void **)&index->prs_codes, (size_t)slots * L.row_stride));
+  const uint64_t entries = index->n * stored;
+  ANN_HIP(hipMalloc((void **)&index->prs_codes, (size_t)entries * L.row_stride));
   if (index->key_metric == ANN_L2) {
-    hipError_t e = hipMalloc((void **)&index->prs_norm, (size_t)slots * sizeof(float));
+    hipError_t e = hipMalloc((void **)&index->prs_norm, (size_t)entries * sizeof(float));
     if (e != hipSuccess) {
       (void)hipFree(index->prs_codes);
       index->prs_codes = nullptr;
       return hip_fail(e, "hipMalloc");
     }
   }
-  const uint64_t total = slots * (L.row_stride / 16);
+  const uint64_t total = entries * (L.row_stride / 16);
   build_prs_kernel<<<grid_for(total, 256), 256, 0, st>>>(index->adjacency, L.codes, index->prs_norm ? L.norm_term : nullptr,
-                                                         slots, index->n, L.row_stride, index->prs_codes, index->prs_norm);
+                                                         index->n, index->degree, stored, L.row_stride, index->prs_codes,
+                                                         index->prs_norm);
   ANN_HIP(hipGetLastError());
   ANN_HIP(hipStreamSynchronize(st));
+  index->prs_slots = stored;
   return ANN_OK;
+}
+
+ann_status ann_build_prs(ann_index *index, void *stream) {
+  if (!index) return fail(ANN_EINVAL, "ann_build_prs: index is NULL");
+  return ann_build_prs_ratio(index, 1.0f, stream);
 }
 
 ann_status ann_reserve_workspace(ann_index *index, uint32_t max_nq, void *stream) {

@@ -95,6 +95,7 @@ ann_status launch_search_with(const ann_index *index, uint32_t nq, const ann_sea
   a.ef_per_query = params->ef_per_query;
   a.prs_codes = params->layout == 1 ? index->prs_codes : nullptr;
   a.prs_norm = params->layout == 1 && index->key_metric == ANN_L2 ? index->prs_norm : nullptr;
+  a.prs_slots = index->prs_slots;
   a.labels = params->alpha_s > 0.0f ? index->labels : nullptr;
   a.alpha_s = params->alpha_s;
   a.m_s = params->m_s == 0 || params->m_s > index->degree ? index->degree : params->m_s;

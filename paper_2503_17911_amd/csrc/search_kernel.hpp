@@ -68,6 +68,7 @@ struct SearchArgs {
   uint32_t vis_cache;  // visited set is the two-way cache
   uint32_t vis_packed;  // the cache keeps 16-bit tags, two ways to a word (needs (n - 1 >> vis_log2) + 1 < 0xFFFF)
   uint32_t m_s;
+  uint32_t prs_slots;  // slots of every adjacency row whose code rows are in prs_codes (the first prs_slots)
   float alpha_s;
 };
 
@@ -565,19 +566,22 @@ struct SearchWave {
   }
 
   // Expansion with redundantly stored neighbour vectors (the paper's PRS
-  // layout, Section 3.3, with ratio 1): the code rows and norm terms of u's
-  // neighbours lie next to each other in slot order, so they are requested
-  // together with the id row - one memory round trip per expansion instead of
-  // two, sequential instead of scattered reads, and no compaction.  Rows of
-  // visited neighbours are fetched as well; only unvisited ones are counted and
-  // can enter the pool.
-  __device__ __forceinline__ void expand_prs(uint32_t uid, int &n_q) {
-    const uint64_t rowbase = (uint64_t)uid * a.degree;
-    const uint32_t nb = lane < (int)a.degree ? a.adjacency[rowbase + lane] : kEmpty;
+  // layout, Section 3.3): the code rows and norm terms of u's first prs_slots
+  // neighbours (redundancy ratio = prs_slots / degree) lie next to each other
+  // in slot order, so they are requested together with the id row - one memory
+  // round trip instead of two, sequential instead of scattered reads, and no
+  // compaction.  Rows of visited neighbours among them are fetched as well;
+  // only unvisited ones are counted and can enter the pool.  The unvisited
+  // neighbours in the remaining slots go to the list cand[n_cand ..] and are
+  // gathered from the code table the usual way by the caller.
+  __device__ __forceinline__ void expand_prs(uint32_t uid, int &n_q, int &n_cand) {
+    const int S = (int)a.prs_slots;
+    const uint32_t nb = lane < (int)a.degree ? a.adjacency[(uint64_t)uid * a.degree + lane] : kEmpty;
+    const uint64_t rowbase = (uint64_t)uid * (uint32_t)S;
     uint64_t fm = 0;
-    for (int sg = 0; sg < (int)a.degree; sg += G) {
+    for (int sg = 0; sg < S; sg += G) {
       const int slot = sg + grp;
-      const uint64_t at = rowbase + (uint32_t)(slot < (int)a.degree ? slot : (int)a.degree - 1);
+      const uint64_t at = rowbase + (uint32_t)(slot < S ? slot : S - 1);
       const uint8_t *rp = a.prs_codes + at * a.row_stride;
       uint4 rows[CPL];
 #pragma unroll
@@ -591,15 +595,20 @@ struct SearchWave {
         }
         const bool fresh = nb != kEmpty && nb < a.n && test_and_set(nb);
         fm = __ballot(fresh);
-        const int n_new = __popcll(fm);
+        const uint64_t stored = S >= 64 ? ~0ull : ((1ull << S) - 1ull);
+        const int n_new = __popcll(fm & stored);
         n_vis += n_new;
         n_dist += n_new;
+        // the rest of the row: unvisited neighbours whose rows are not stored with u
+        const uint64_t rest = fm & ~stored;
+        if ((rest >> lane) & 1ull) cand_at(n_cand + lanes_below(rest)) = nb;
+        n_cand += __popcll(rest);
       }
       const int dot = group_sum_i32<LPR>(row_dot(rows)) + bias;
       const uint32_t vid = (uint32_t)__shfl((int)nb, slot & 63);
       const float key = key_from_idot(a.metric, s, qlo, dot, nrm);
       const uint64_t c64 = pack64(order_u32(key), vid << 1);
-      const bool q = sub == 0 && slot < (int)a.degree && ((fm >> (slot & 63)) & 1ull) && c64 < worst;
+      const bool q = sub == 0 && slot < S && ((fm >> (slot & 63)) & 1ull) && c64 < worst;
       const uint64_t bm = __ballot(q);
       if (n_q + G > kStage) merge_staged(n_q);
       if (q) stage[n_q + lanes_below(bm)] = c64;
@@ -691,11 +700,12 @@ struct SearchWave {
       if (PMAX > 1 && !use_cache() && n_vis + (uint32_t)(got * kWave) > vis_limit) rebuild_table();
 
       if (use_prs()) {
-        int n_q = 0;
+        int n_q = 0, n_rest = 0;
 #pragma unroll
         for (int e = 0; e < PMAX; ++e)
-          if (e < got) expand_prs(uid[e], n_q);
+          if (e < got) expand_prs(uid[e], n_q, n_rest);
         merge_staged(n_q);
+        evaluate_and_merge(n_rest);  // neighbours beyond the stored slots (none at ratio 1)
         continue;
       }
       int n_cand = 0;

@@ -131,8 +131,11 @@ class GpuIndex:
         torch.cuda.synchronize()
         return (as_u32(ids), keys.cpu().numpy(), dots.cpu().numpy() if want_idot else None, as_u32(counts))
 
-    def build_prs(self):
-        ann.ann_build_prs(self.handle, stream_ptr())
+    def build_prs(self, ratio=None):
+        if ratio is None:
+            ann.ann_build_prs(self.handle, stream_ptr())
+        else:
+            ann.ann_build_prs_ratio(self.handle, ratio, stream_ptr())
         torch.cuda.synchronize()
 
     def entry_scan(self, Q, n_pivots, n_entry):

@@ -178,13 +178,14 @@ def test_redundant_layout_gives_identical_results(H, n, d, R, nq, metric, bits, 
     m = metric_id(metric)
     lv = oracle.sq_fit(X, bits)
     ix = H.GpuIndex(X, adj, 0, [lv], m)
-    ix.build_prs()
-    for ef in efs:
-        orc = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m)
-        assert_search_equal(ix.search(Q, ef, layout=1), orc)
-        assert_search_equal(ix.search(Q, ef, layout=1, visited_slots=0), orc, check_counts=False)
-        orc4 = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=3)
-        assert_search_equal(ix.search(Q, ef, layout=1, mode=1, expansions_per_step=3), orc4)
+    for ratio in (None, 0.5, 0.2, 1.0):           # None: ann_build_prs (ratio 1); each call replaces the copy before it
+        ix.build_prs(ratio)
+        for ef in efs:
+            orc = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m)
+            assert_search_equal(ix.search(Q, ef, layout=1), orc)
+            assert_search_equal(ix.search(Q, ef, layout=1, visited_slots=0), orc, check_counts=False)
+            orc4 = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=3)
+            assert_search_equal(ix.search(Q, ef, layout=1, mode=1, expansions_per_step=3), orc4)
     ix.close()
 
 
