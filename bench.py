@@ -77,6 +77,7 @@ def main():
                     help="entry-point stage: scan this many sampled base vectors per query (0 = start at the medoid)")
     ap.add_argument("--n-entry", type=int, default=1, help="initial nodes per query taken from the pivot scan")
     ap.add_argument("--layout", type=int, default=0, help="1: redundant neighbour-code layout (PRS)")
+    ap.add_argument("--prs-ratio", type=float, default=1.0, help="redundancy ratio of the PRS layout (share of a row's slots stored with the node)")
     ap.add_argument("--schedule-pivots", type=int, default=256,
                     help="order each batch so that similar queries share a die's L2: keys from a scan of this many "
                          "pivots (0 = natural order; with --pivots the entry scan's result is the key)")
@@ -175,7 +176,7 @@ def main():
     out_dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
 
     if args.layout == 1:
-        ann.ann_build_prs(index, st)
+        ann.ann_build_prs_ratio(index, args.prs_ratio, st)
     entries = None
     if args.pivots:
         ann.ann_build_entry_table(index, args.pivots, st)
@@ -694,6 +695,7 @@ def main():
                    "key_form": "Euclidean form on unit-norm inner-product data" if args.unit_norm_l2_keys else "the metric's own",
                    "rerank": (f"per-query prefix from the key gap: gamma {args.rerank_gamma}, {min(n_rerank, ef)}..{min(args.rerank_max or ef, ef)} "
                               f"candidates, mean {float(n_reranked[nq].float().mean()):.1f}" if adaptive else f"fixed prefix of {min(n_rerank, ef)}"),
+                   "layout": "gathered code rows" if not args.layout else f"PRS, redundancy ratio {args.prs_ratio}",
                    "entry": "medoid" if not args.pivots else f"closest {args.n_entry} of {args.pivots} scanned pivots",
                    "ef": ef, "mode": "exact" if mode == 0 else "multi-expansion", f"recall_at_{k}": round(rec, 4),
                    "recall_target_met": bool(rec >= 0.95), "evaluations_per_query": round(float(c[:, 1].mean()), 1),

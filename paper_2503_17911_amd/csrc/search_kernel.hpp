@@ -100,6 +100,12 @@ __host__ __device__ constexpr int merge_buf_entries(int m) { return 64 * m; }
 __host__ __device__ constexpr int stage_entries(int m, int pmax, bool fast) {
   return fast && 32 * pmax > 64 * m ? 32 * pmax : 64 * m;
 }
+// During a merge the area holds 64 m integer counters (32 m entries) and,
+// behind them, the list of the batch's candidates (64 and 4 of padding).
+__host__ __device__ constexpr int merge_list_at(int m) { return 32 * m; }
+__host__ __device__ constexpr int stage_area_entries(int m, int pmax, bool fast) {
+  return stage_entries(m, pmax, fast) > merge_list_at(m) + 68 ? stage_entries(m, pmax, fast) : merge_list_at(m) + 68;
+}
 
 // Ids of one step's unvisited neighbours: up to pmax rows of `degree` ids.
 __host__ __device__ inline uint32_t cand_entries(uint32_t degree, int pmax) {
@@ -109,7 +115,7 @@ __host__ __device__ inline uint32_t cand_entries(uint32_t degree, int pmax) {
 // LDS bytes for one query: merge buffer, staging, visited set, candidate ids, folded query.
 __host__ __device__ inline size_t search_smem_bytes(int m, int pmax, bool fast, uint32_t vis_log2, uint32_t degree,
                                                     uint32_t tq_stride) {
-  return (size_t)(merge_buf_entries(m) + stage_entries(m, pmax, fast)) * 8 + ((size_t)1 << vis_log2) * 4 +
+  return (size_t)(merge_buf_entries(m) + stage_area_entries(m, pmax, fast)) * 8 + ((size_t)1 << vis_log2) * 4 +
          (fast ? 0 : (size_t)cand_entries(degree, pmax) * 4) + tq_stride;
 }
 
@@ -163,7 +169,7 @@ struct SearchWave {
     const uint32_t cap = 1u << a.vis_log2;
     mbuf = smem;
     stage = mbuf + merge_buf_entries(M);
-    vis = reinterpret_cast<uint32_t *>(stage + stage_entries(M, PMAX, FAST));
+    vis = reinterpret_cast<uint32_t *>(stage + stage_area_entries(M, PMAX, FAST));
     cand = FAST ? reinterpret_cast<uint32_t *>(stage) : vis + cap;
     tql = reinterpret_cast<const int *>(vis + cap + (FAST ? 0 : cand_entries(a.degree, PMAX)));
     vis_mask = cap - 1;
@@ -409,12 +415,18 @@ struct SearchWave {
     if (km == 0) return;
     const int rank_p = (int)(pos >> 3);
     int *cnt = reinterpret_cast<int *>(stage);
+    uint64_t *lst = stage + merge_list_at(M);
     int shift[M];
     int dest;
     for (;;) {
       // pool entry i moves up by the number of candidates with rank <= i
 #pragma unroll
       for (int r = 0; r < M; ++r) cnt[r * kWave + lane] = 0;
+      // the batch's candidates side by side, padded to a multiple of four with
+      // values above every candidate
+      const int n_l = __popcll(km);
+      if (mine) lst[lanes_below(km)] = c64;
+      if (lane < 4) lst[n_l + lane] = ~0ull;
       wave_sync();
       if (mine) atomicAdd(&cnt[rank_p], 1);
       wave_sync();
@@ -424,12 +436,12 @@ struct SearchWave {
         shift[r] = wave_inclusive_scan_i32(cnt[r * kWave + lane]) + carry;
         carry = __builtin_amdgcn_readlane(shift[r], kWave - 1);
       }
-      // candidates below this lane's candidate
+      // candidates below this lane's candidate: every lane walks the list
+      // (all lanes read the same entry: one LDS access each, four in flight)
       int below_c = 0;
-      for (uint64_t m = km; m; m &= m - 1) {
-        const int l = __builtin_ctzll(m);
-        const uint64_t s64 = pack64(__builtin_amdgcn_readlane(ck, l), __builtin_amdgcn_readlane(cv, l));
-        below_c += s64 < c64 ? 1 : 0;
+      for (int i = 0; i < n_l; i += 4) {
+        const uint64_t e0 = lst[i], e1 = lst[i + 1], e2 = lst[i + 2], e3 = lst[i + 3];
+        below_c += (e0 < c64 ? 1 : 0) + (e1 < c64 ? 1 : 0) + (e2 < c64 ? 1 : 0) + (e3 < c64 ? 1 : 0);
       }
       dest = rank_p + below_c;
       // The same forgotten node twice among the candidates: equal values get
