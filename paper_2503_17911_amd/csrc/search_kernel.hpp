@@ -400,12 +400,27 @@ struct SearchWave {
     bool mine = have && c64 < worst;
     if (__ballot(mine) == 0) return;
     // number of pool entries below the candidate: lower bound over slots
-    // 0 .. 64 M - 2 (a candidate that beats the last entry ranks below 64 M)
+    // 0 .. 64 M - 2 (a candidate that beats the last entry ranks below 64 M).
+    // Two levels of the bisection per round: the probe of the first level and
+    // both possible probes of the second are read together, so a round costs
+    // one LDS latency instead of two.
     uint32_t pos = 0;  // byte offset into mbuf
+    {
+      const char *mb = reinterpret_cast<const char *>(mbuf);
+      int step = 32 * M;
 #pragma unroll
-    for (int step = 32 * M; step >= 1; step >>= 1) {
-      const uint64_t e = *reinterpret_cast<const uint64_t *>(reinterpret_cast<const char *>(mbuf) + pos + (step - 1) * 8);
-      pos += e < c64 ? (uint32_t)step * 8u : 0u;
+      for (; step >= 2; step >>= 2) {
+        const uint64_t ea = *reinterpret_cast<const uint64_t *>(mb + pos + (step - 1) * 8);
+        const uint64_t eb = *reinterpret_cast<const uint64_t *>(mb + pos + (step / 2 - 1) * 8);
+        const uint64_t ec = *reinterpret_cast<const uint64_t *>(mb + pos + (step + step / 2 - 1) * 8);
+        const bool up = ea < c64;
+        const uint64_t second = up ? ec : eb;
+        pos += (up ? (uint32_t)step * 8u : 0u) + (second < c64 ? (uint32_t)(step / 2) * 8u : 0u);
+      }
+      if (step == 1) {
+        const uint64_t e = *reinterpret_cast<const uint64_t *>(mb + pos);
+        pos += e < c64 ? 8u : 0u;
+      }
     }
     // A node the visited set has forgotten can come back.  If it is in the
     // pool, the entry found is that node (ids are unique in the pool): dropped.
@@ -676,7 +691,29 @@ struct SearchWave {
       uint32_t uid[PMAX];
       uint32_t next_id = kEmpty;
       int got = 0;
-      {
+      if constexpr (PMAX > 1) {
+        // every lane ranks its own entries among the un-expanded ones (pool
+        // order: register by register); the first p mark themselves and leave
+        // their ids in LDS, where all lanes read them back
+        uint32_t *picked = reinterpret_cast<uint32_t *>(stage);
+        int before = 0;
+#pragma unroll
+        for (int r = 0; r < M; ++r) {
+          const bool open = (pv[r] & 1u) == 0;
+          const uint64_t um = __ballot(open);
+          const int rank = before + lanes_below(um);
+          if (open && rank < p) {
+            picked[rank] = pv[r] >> 1;
+            pv[r] |= 1u;
+          }
+          before += __popcll(um);
+        }
+        got = before < p ? before : p;
+        wave_sync();
+#pragma unroll
+        for (int e = 0; e < PMAX; ++e) uid[e] = e < got ? picked[e] : kEmpty;
+        wave_sync();
+      } else {
         uint64_t um[M], mark[M];
 #pragma unroll
         for (int r = 0; r < M; ++r) {
@@ -699,11 +736,9 @@ struct SearchWave {
           }
           got += found ? 1 : 0;
         }
-        if (PMAX == 1) {
 #pragma unroll
-          for (int r = M - 1; r >= 0; --r)
-            if (um[r] != 0) next_id = (uint32_t)__builtin_amdgcn_readlane(pv[r], __builtin_ctzll(um[r])) >> 1;
-        }
+        for (int r = M - 1; r >= 0; --r)
+          if (um[r] != 0) next_id = (uint32_t)__builtin_amdgcn_readlane(pv[r], __builtin_ctzll(um[r])) >> 1;
 #pragma unroll
         for (int r = 0; r < M; ++r) pv[r] |= (uint32_t)((mark[r] >> lane) & 1ull);
       }
