@@ -49,10 +49,17 @@ def _load():
         lib.orc_key.argtypes = [_i32, _f32, _f32, _i32, _f32]
         lib.orc_key.restype = _f32
         lib.orc_search_batch.argtypes = [_i64, _i32, _i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _u32p, _u32,
-                                         _f32p, _i32, _u32p, _i32, _i32, _f32p, _f32, _i32, _i32, _u32p, _f32p, _i32p, _u32p, _u8p]
+                                         _f32p, _i32, _u32p, _i32, _i32, _f32p, _f32, _i32, _i32, _u32p, _f32p, _i32p, _u32p, _u8p, _i32]
         lib.orc_rescore_batch.argtypes = [_i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _f32p, _i32, _u32p, _i32,
-                                          _u32p, _f32p, _i32p]
-        lib.orc_entry_scan.argtypes = [_i64, _i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _f32p, _i32, _i32, _i32, _u32p]
+                                          _u32p, _f32p, _i32p, _i32]
+        lib.orc_entry_scan.argtypes = [_i64, _i32, _i32, _i32, _u8p, _f32p, _f32p, _f32p, _f32p, _i32, _i32, _i32, _u32p,
+                                       _i32]
+        lib.orc_query_prep15.argtypes = [_f32p, _i32, _f32p, _f32p, _P(ctypes.c_int16), _f32p, _f32p]
+        lib.orc_query_prep15.restype = None
+        lib.orc_idot15.argtypes = [_P(ctypes.c_int16), _u8p, _i32, _i32]
+        lib.orc_idot15.restype = ctypes.c_int64
+        lib.orc_key15.argtypes = [_i32, _f32, _f32, ctypes.c_int64, _f32]
+        lib.orc_key15.restype = _f32
         lib.orc_rerank_batch.argtypes = [_f32p, _i32, _i32, _f32p, _i32, _u32p, _i32, _i32, _u32p, _f32p]
         lib.orc_rerank_length.argtypes = [_f32p, _i32, _i32, _i32, _i32, _i32, _f32, _u32p]
         lib.orc_rerank_length.restype = None
@@ -134,6 +141,26 @@ def query_prep(q, lo, delta):
     return t, np.float32(s.value), np.float32(qlo.value)
 
 
+def query_prep15(q, lo, delta):
+    """The query folded to 15 bits: (t int16 [d], s, qlo)."""
+    q, lo, delta = _c(q, np.float32), _c(lo, np.float32), _c(delta, np.float32)
+    d = q.shape[0]
+    t = np.empty(d, np.int16)
+    s, qlo = _f32(), _f32()
+    _load().orc_query_prep15(_p(q, _f32p), d, _p(lo, _f32p), _p(delta, _f32p), _p(t, _P(ctypes.c_int16)),
+                             ctypes.byref(s), ctypes.byref(qlo))
+    return t, np.float32(s.value), np.float32(qlo.value)
+
+
+def idot15(t, code_row, d, bits) -> int:
+    t, code_row = _c(t, np.int16), _c(code_row, np.uint8)
+    return int(_load().orc_idot15(_p(t, _P(ctypes.c_int16)), _p(code_row, _u8p), d, bits))
+
+
+def key15(metric, s, qlo, idot_value, norm_term) -> np.float32:
+    return np.float32(_load().orc_key15(metric, float(s), float(qlo), int(idot_value), float(norm_term)))
+
+
 def idot(t, code_row, d, bits) -> int:
     t, code_row = _c(t, np.int8), _c(code_row, np.uint8)
     return int(_load().orc_idot(_p(t, _i8p), _p(code_row, _u8p), d, bits))
@@ -144,7 +171,7 @@ def key(metric, s, qlo, idot_value, norm_term) -> np.float32:
 
 
 def search_batch(level: SQLevel, d, adjacency, entry_point, Q, ef, metric=L2, entries=None, labels=None,
-                 alpha_s=float("inf"), m_s=0, expansions_per_step=1, want_visited=False):
+                 alpha_s=float("inf"), m_s=0, expansions_per_step=1, want_visited=False, query_bits=8):
     """Algorithm 1 per query.  Returns (ids, keys, idot, counts), pools padded to ef;
     with want_visited also the final visited sets as a [nq][n] uint8 array."""
     adjacency, Q = _c(adjacency, np.uint32), _c(Q, np.float32)
@@ -165,24 +192,24 @@ def search_batch(level: SQLevel, d, adjacency, entry_point, Q, ef, metric=L2, en
                              _p(level.delta, _f32p), _p(level.norm_term, _f32p), _p(adjacency, _u32p),
                              int(entry_point), _p(Q, _f32p), nq, _p(entries, _u32p), n_entry, ef, _p(labels, _f32p),
                              float(alpha_s), int(m_s), int(expansions_per_step), _p(ids, _u32p),
-                             _p(keys, _f32p), _p(dots, _i32p), _p(counts, _u32p), _p(visited, _u8p))
+                             _p(keys, _f32p), _p(dots, _i32p), _p(counts, _u32p), _p(visited, _u8p), int(query_bits))
     if want_visited:
         return ids, keys, dots, counts, visited
     return ids, keys, dots, counts
 
 
-def entry_scan(level: SQLevel, d, Q, n_pivots, n_entry, metric=L2):
+def entry_scan(level: SQLevel, d, Q, n_pivots, n_entry, metric=L2, query_bits=8):
     """Per-query initial nodes: the n_entry closest (tau_l) of n_pivots evenly spaced base nodes."""
     Q = _c(Q, np.float32)
     nq = Q.shape[0]
     out = np.empty((nq, n_entry), np.uint32)
     _load().orc_entry_scan(level.codes.shape[0], d, metric, level.bits, _p(level.codes, _u8p), _p(level.lo, _f32p),
                            _p(level.delta, _f32p), _p(level.norm_term, _f32p), _p(Q, _f32p), nq, n_pivots, n_entry,
-                           _p(out, _u32p))
+                           _p(out, _u32p), int(query_bits))
     return out
 
 
-def rescore_batch(level: SQLevel, d, Q, cand_ids, metric=L2):
+def rescore_batch(level: SQLevel, d, Q, cand_ids, metric=L2, query_bits=8):
     Q, cand_ids = _c(Q, np.float32), _c(cand_ids, np.uint32)
     nq, n_cand = cand_ids.shape
     ids = np.empty((nq, n_cand), np.uint32)
@@ -190,7 +217,7 @@ def rescore_batch(level: SQLevel, d, Q, cand_ids, metric=L2):
     dots = np.empty((nq, n_cand), np.int32)
     _load().orc_rescore_batch(d, metric, level.bits, _p(level.codes, _u8p), _p(level.lo, _f32p),
                               _p(level.delta, _f32p), _p(level.norm_term, _f32p), _p(Q, _f32p), nq,
-                              _p(cand_ids, _u32p), n_cand, _p(ids, _u32p), _p(keys, _f32p), _p(dots, _i32p))
+                              _p(cand_ids, _u32p), n_cand, _p(ids, _u32p), _p(keys, _f32p), _p(dots, _i32p), int(query_bits))
     return ids, keys, dots
 
 

@@ -58,10 +58,24 @@ inline float key_from_idot(int metric, float s, float qlo, int32_t idot, float n
   return key;
 }
 
+// The same with a 64-bit integer dot product (the 15-bit query): one conversion
+// to fp32, then the same operations.
+inline float key_from_idot64(int metric, float s, float qlo, int64_t idot, float norm_term) {
+  float key;
+  if (metric == 0) {
+    float h = norm_term - 2.0f * qlo;
+    key = std::fmaf(-2.0f * s, (float)idot, h);
+  } else {
+    key = -std::fmaf(s, (float)idot, qlo);
+  }
+  if (key == 0.0f) key = 0.0f;
+  return key;
+}
+
 struct Entry {
   float key;
   uint32_t id;
-  int32_t idot;
+  int64_t idot;
   bool expanded;
 };
 inline bool entry_less(const Entry &a, const Entry &b) {
@@ -193,6 +207,47 @@ float orc_key(int32_t metric, float s, float qlo, int32_t idot, float norm_term)
   return key_from_idot(metric, s, qlo, idot, norm_term);
 }
 
+// The query folded to 15 bits instead of 8 (a finer low-precision distance in
+// the sense of Appendix G): the same a_j = delta_j * q_j, scaled to
+// [-16256, 16256] (= 127 * 128, so that the value splits into two signed
+// bytes), s = max|a| / 16256.  The integer dot product is taken in 64 bits
+// and converted to fp32 with one rounding; the key has the same form.
+void orc_query_prep15(const float *q, int32_t d, const float *lo, const float *delta, int16_t *t, float *s_out,
+                      float *qlo_out) {
+  std::vector<float> a(d);
+  float amax = 0.0f;
+  for (int j = 0; j < d; ++j) {
+    a[j] = delta[j] * q[j];
+    float m = std::fabs(a[j]);
+    if (m > amax) amax = m;
+  }
+  float s = 1.0f, r = 0.0f;
+  if (amax > 0.0f) {
+    s = amax / 16256.0f;
+    r = 16256.0f / amax;
+  }
+  double acc = 0.0;
+  for (int j = 0; j < d; ++j) {
+    int ti = (int)std::nearbyintf(a[j] * r);
+    if (ti > 16256) ti = 16256;
+    if (ti < -16256) ti = -16256;
+    t[j] = (int16_t)ti;
+    acc += (double)q[j] * (double)lo[j];
+  }
+  *s_out = s;
+  *qlo_out = (float)acc;
+}
+
+int64_t orc_idot15(const int16_t *t, const uint8_t *code_row, int32_t d, int32_t bits) {
+  int64_t acc = 0;
+  for (int j = 0; j < d; ++j) acc += (int64_t)t[j] * (int64_t)code_at(code_row, j, bits);
+  return acc;
+}
+
+float orc_key15(int32_t metric, float s, float qlo, int64_t idot, float norm_term) {
+  return key_from_idot64(metric, s, qlo, idot, norm_term);
+}
+
 }  // extern "C" (the search helpers below are internal)
 
 // ---------------------------------------------------------------- search
@@ -225,7 +280,36 @@ float orc_key(int32_t metric, float s, float qlo, int32_t idot, float norm_term)
 //   out_counts: [nq][4] = expansions, distance evaluations (= |V|), pool size, 0.
 //   out_visited: NULL, or [nq][n] bytes: 1 where the node's key was evaluated
 //            (the final V), for tests of properties that hold for any P.
+//   query_bits: 8 (int8 folded query) or 15 (orc_query_prep15); with 15 the
+//            integer dot products do not fit out_idot, which is then zero.
 namespace {
+
+// A query folded at either width (8: Section 5.2 with an int8 query; 15: the
+// finer variant above), ready to score code rows.
+struct Folded {
+  int query_bits = 8;
+  std::vector<int8_t> t8;
+  std::vector<int16_t> t15;
+  float s = 1.0f, qlo = 0.0f;
+  void fold(const float *q, int32_t d, const float *lo, const float *delta, int32_t bits_q) {
+    query_bits = bits_q == 15 ? 15 : 8;
+    if (query_bits == 15) {
+      t15.resize(d);
+      orc_query_prep15(q, d, lo, delta, t15.data(), &s, &qlo);
+    } else {
+      t8.resize(d);
+      orc_query_prep(q, d, lo, delta, t8.data(), &s, &qlo);
+    }
+  }
+  Entry score(int32_t metric, int32_t bits, int32_t d, const uint8_t *row, float norm, uint32_t v) const {
+    if (query_bits == 15) {
+      const int64_t idot = orc_idot15(t15.data(), row, d, bits);
+      return Entry{key_from_idot64(metric, s, qlo, idot, norm), v, idot, false};
+    }
+    const int32_t idot = orc_idot(t8.data(), row, d, bits);
+    return Entry{key_from_idot(metric, s, qlo, idot, norm), v, idot, false};
+  }
+};
 
 struct QueryState {
   std::vector<Entry> pool;       // C, ascending (key, id)
@@ -278,21 +362,19 @@ void orc_search_batch(int64_t n, int32_t d, int32_t degree, int32_t metric, int3
                       uint32_t entry_point, const float *Q, int32_t nq, const uint32_t *entries, int32_t n_entry,
                       int32_t ef, const float *labels, float alpha_s, int32_t m_s, int32_t expansions_per_step,
                       uint32_t *out_ids, float *out_keys, int32_t *out_idot, uint32_t *out_counts,
-                      uint8_t *out_visited) {
+                      uint8_t *out_visited, int32_t query_bits) {
   const int rb = row_bytes(d, bits);
   if (m_s <= 0) m_s = degree;
   const int P = expansions_per_step > 1 ? expansions_per_step : 1;
-  std::vector<int8_t> t(d);
+  Folded fq;
   QueryState st;
   for (int32_t qi = 0; qi < nq; ++qi) {
-    float s, qlo;
-    orc_query_prep(Q + (int64_t)qi * d, d, lo, delta, t.data(), &s, &qlo);
+    fq.fold(Q + (int64_t)qi * d, d, lo, delta, query_bits);
     st.pool.clear();
     st.visited.assign(n, 0);
     st.n_exp = st.n_dist = 0;
     auto scored = [&](uint32_t v) {
-      const int32_t idot = orc_idot(t.data(), codes + (int64_t)v * rb, d, bits);
-      return Entry{key_from_idot(metric, s, qlo, idot, norm_term ? norm_term[v] : 0.0f), v, idot, false};
+      return fq.score(metric, bits, d, codes + (int64_t)v * rb, norm_term ? norm_term[v] : 0.0f, v);
     };
 
     // the initial nodes I are members of V from the start and are scored like
@@ -319,7 +401,7 @@ void orc_search_batch(int64_t n, int32_t d, int32_t degree, int32_t metric, int3
       const bool have = p < (int)st.pool.size();
       out_ids[(int64_t)qi * ef + p] = have ? st.pool[p].id : kPad;
       out_keys[(int64_t)qi * ef + p] = have ? st.pool[p].key : INFINITY;
-      if (out_idot) out_idot[(int64_t)qi * ef + p] = have ? st.pool[p].idot : 0;
+      if (out_idot) out_idot[(int64_t)qi * ef + p] = have && query_bits != 15 ? (int32_t)st.pool[p].idot : 0;
     }
     if (out_counts) {
       out_counts[(int64_t)qi * 4 + 0] = st.n_exp;
@@ -336,26 +418,24 @@ void orc_search_batch(int64_t n, int32_t d, int32_t degree, int32_t metric, int3
 //   ids: [nq][n_cand] (padding allowed); outputs same shape, (key, id) order.
 void orc_rescore_batch(int32_t d, int32_t metric, int32_t bits, const uint8_t *codes, const float *lo,
                        const float *delta, const float *norm_term, const float *Q, int32_t nq, const uint32_t *ids,
-                       int32_t n_cand, uint32_t *out_ids, float *out_keys, int32_t *out_idot) {
+                       int32_t n_cand, uint32_t *out_ids, float *out_keys, int32_t *out_idot, int32_t query_bits) {
   const int rb = row_bytes(d, bits);
-  std::vector<int8_t> t(d);
+  Folded fq;
   std::vector<Entry> lst;
   for (int32_t qi = 0; qi < nq; ++qi) {
-    float s, qlo;
-    orc_query_prep(Q + (int64_t)qi * d, d, lo, delta, t.data(), &s, &qlo);
+    fq.fold(Q + (int64_t)qi * d, d, lo, delta, query_bits);
     lst.clear();
     for (int c = 0; c < n_cand; ++c) {
       uint32_t v = ids[(int64_t)qi * n_cand + c];
       if (v == kPad) continue;
-      int32_t idot = orc_idot(t.data(), codes + (int64_t)v * rb, d, bits);
-      lst.push_back({key_from_idot(metric, s, qlo, idot, norm_term ? norm_term[v] : 0.0f), v, idot, false});
+      lst.push_back(fq.score(metric, bits, d, codes + (int64_t)v * rb, norm_term ? norm_term[v] : 0.0f, v));
     }
     std::sort(lst.begin(), lst.end(), entry_less);
     for (int c = 0; c < n_cand; ++c) {
       bool have = c < (int)lst.size();
       out_ids[(int64_t)qi * n_cand + c] = have ? lst[c].id : kPad;
       out_keys[(int64_t)qi * n_cand + c] = have ? lst[c].key : INFINITY;
-      if (out_idot) out_idot[(int64_t)qi * n_cand + c] = have ? lst[c].idot : 0;
+      if (out_idot) out_idot[(int64_t)qi * n_cand + c] = have && query_bits != 15 ? (int32_t)lst[c].idot : 0;
     }
   }
 }
@@ -365,18 +445,16 @@ void orc_rescore_batch(int32_t d, int32_t metric, int32_t bits, const uint8_t *c
 // nodes floor(i * n / n_pivots), the n_entry with the smallest (tau_l key, id).
 void orc_entry_scan(int64_t n, int32_t d, int32_t metric, int32_t bits, const uint8_t *codes, const float *lo,
                     const float *delta, const float *norm_term, const float *Q, int32_t nq, int32_t n_pivots,
-                    int32_t n_entry, uint32_t *out_ids) {
+                    int32_t n_entry, uint32_t *out_ids, int32_t query_bits) {
   const int rb = row_bytes(d, bits);
-  std::vector<int8_t> t(d);
+  Folded fq;
   std::vector<Entry> all;
   for (int32_t qi = 0; qi < nq; ++qi) {
-    float s, qlo;
-    orc_query_prep(Q + (int64_t)qi * d, d, lo, delta, t.data(), &s, &qlo);
+    fq.fold(Q + (int64_t)qi * d, d, lo, delta, query_bits);
     all.clear();
     for (int64_t i = 0; i < n_pivots; ++i) {
       const int64_t v = i * n / n_pivots;
-      const int32_t idot = orc_idot(t.data(), codes + v * rb, d, bits);
-      all.push_back({key_from_idot(metric, s, qlo, idot, norm_term ? norm_term[v] : 0.0f), (uint32_t)v, idot, false});
+      all.push_back(fq.score(metric, bits, d, codes + v * rb, norm_term ? norm_term[v] : 0.0f, (uint32_t)v));
     }
     std::sort(all.begin(), all.end(), entry_less);
     for (int e = 0; e < n_entry; ++e) out_ids[(int64_t)qi * n_entry + e] = e < (int)all.size() ? all[e].id : kPad;

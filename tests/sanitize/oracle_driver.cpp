@@ -18,11 +18,11 @@ void orc_sq_decode(const uint8_t *, int64_t, int32_t, int32_t, const float *, co
 void orc_search_batch(int64_t, int32_t, int32_t, int32_t, int32_t, const uint8_t *, const float *, const float *,
                       const float *, const uint32_t *, uint32_t, const float *, int32_t, const uint32_t *, int32_t,
                       int32_t, const float *, float, int32_t, int32_t, uint32_t *, float *, int32_t *, uint32_t *,
-                      uint8_t *);
+                      uint8_t *, int32_t);
 void orc_rescore_batch(int32_t, int32_t, int32_t, const uint8_t *, const float *, const float *, const float *,
-                       const float *, int32_t, const uint32_t *, int32_t, uint32_t *, float *, int32_t *);
+                       const float *, int32_t, const uint32_t *, int32_t, uint32_t *, float *, int32_t *, int32_t);
 void orc_entry_scan(int64_t, int32_t, int32_t, int32_t, const uint8_t *, const float *, const float *, const float *,
-                    const float *, int32_t, int32_t, int32_t, uint32_t *);
+                    const float *, int32_t, int32_t, int32_t, uint32_t *, int32_t);
 void orc_rerank_batch(const float *, int32_t, int32_t, const float *, int32_t, const uint32_t *, int32_t, int32_t,
                       uint32_t *, float *);
 void orc_rerank_length(const float *, int32_t, int32_t, int32_t, int32_t, int32_t, float, uint32_t *);
@@ -59,13 +59,13 @@ int main() {
       std::vector<uint8_t> vis(nq * n);
       std::vector<double> gd(nq * k);
       orc_entry_scan(n, d, metric, bits, codes.data(), lo.data(), delta.data(), norm.data(), Q.data(), nq, 50, 3,
-                     ent.data());
+                     ent.data(), bits == 8 ? 15 : 8);
       for (int P : {1, 4}) {
         orc_search_batch(n, d, R, metric, bits, codes.data(), lo.data(), delta.data(), norm.data(), adj.data(), entry,
                          Q.data(), nq, P == 1 ? nullptr : ent.data(), P == 1 ? 0 : 3, ef, P == 1 ? labels.data() : nullptr,
-                         1.2f, P == 1 ? 5 : 0, P, ids.data(), keys.data(), dots.data(), cnt.data(), vis.data());
+                         1.2f, P == 1 ? 5 : 0, P, ids.data(), keys.data(), dots.data(), cnt.data(), vis.data(), P == 1 ? 8 : 15);
         orc_rescore_batch(d, metric, bits, codes.data(), lo.data(), delta.data(), norm.data(), Q.data(), nq, ids.data(),
-                          ef, rid.data(), rkeys.data(), dots.data());
+                          ef, rid.data(), rkeys.data(), dots.data(), P == 1 ? 15 : 8);
         orc_rerank_length(rkeys.data(), nq, ef, 2 * k, ef, k, 0.5f, n_r.data());
         orc_rerank_batch(X.data(), d, metric, Q.data(), nq, rid.data(), ef, k, top.data(), dist.data());
       }

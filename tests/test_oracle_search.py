@@ -331,3 +331,25 @@ def test_euclidean_form_keys_rank_unit_vectors_better_than_inner_product_keys():
     l2_ids, *_ = oracle.search_batch(lv, w.d, adj, 0, Q, 600, metric=oracle.L2)
     r_ip, r_l2 = oracle.recall(ip_ids, gt), oracle.recall(l2_ids, gt)
     assert r_l2 > r_ip + 0.02, (r_ip, r_l2)
+
+
+@pytest.mark.parametrize("metric,bits", [(oracle.L2, 8), (oracle.IP, 4)])
+def test_ef_at_least_n_with_the_15_bit_query(metric, bits):
+    """The search with the 15-bit folded query: with ef >= N the pool is every
+    node in the order of the 15-bit keys, recomputed here one by one."""
+    w, X, Q, adj = small_case(300, 16, 6, 5, seed=11, bits=bits)
+    lv = oracle.sq_fit(X, bits)
+    ids, keys, dots, cnt = oracle.search_batch(lv, w.d, adj, 0, Q, 320, metric=metric, query_bits=15)
+    for qi in range(len(Q)):
+        t, s, qlo = oracle.query_prep15(Q[qi], lv.lo, lv.delta)
+        k = np.array([oracle.key15(metric, s, qlo, oracle.idot15(t, lv.codes[v], w.d, bits), lv.norm_term[v])
+                      for v in range(300)], np.float32)
+        order = np.lexsort((np.arange(300), k))
+        assert ids[qi, :300].tolist() == order.tolist()
+        assert (keys[qi, :300] == k[order]).all() and (dots[qi] == 0).all()
+    want = oracle.entry_scan(lv, w.d, Q, 50, 3, metric=metric, query_bits=15)
+    piv = [i * 300 // 50 for i in range(50)]
+    for qi in range(len(Q)):
+        t, s, qlo = oracle.query_prep15(Q[qi], lv.lo, lv.delta)
+        sc = sorted((float(oracle.key15(metric, s, qlo, oracle.idot15(t, lv.codes[v], w.d, bits), lv.norm_term[v])), v) for v in piv)
+        assert want[qi].tolist() == [v for _, v in sc[:3]]

@@ -183,3 +183,81 @@ def test_truncated_sq_hand_case_and_invariants():
     c[:, 0::2] = lv_t.codes & 0x0F
     c[:, 1::2] = lv_t.codes >> 4
     assert (c[Y < lv_t.lo] == 0).all() and (c[Y > hi] == 15).all()
+
+
+def test_query_prep15_invariants_and_rounding():
+    """The 15-bit folded query: same coefficients on a grid 128 times finer."""
+    rng = np.random.default_rng(12)
+    d = 96
+    lo = rng.normal(size=d).astype(np.float32)
+    delta = rng.uniform(0.001, 0.05, size=d).astype(np.float32)
+    for trial in range(20):
+        q = rng.normal(size=d).astype(np.float32)
+        t, s, qlo = oracle.query_prep15(q, lo, delta)
+        t8, s8, qlo8 = oracle.query_prep(q, lo, delta)
+        a = delta.astype(np.float64) * q.astype(np.float64)
+        assert np.abs(t.astype(int)).max() == 16256 == 127 * 128
+        assert s == pytest.approx(np.abs(a).max() / 16256, rel=1e-6) and s == pytest.approx(s8 / 128, rel=1e-6)
+        assert (np.abs(s.astype(np.float64) * t - a) <= 0.5 * s * (1 + 1e-5)).all()
+        assert qlo == qlo8
+        # two signed bytes hold the value: t = 128 * hi + lo with lo in [-64, 63]
+        low = ((t.astype(int) + 64) % 128) - 64
+        high = (t.astype(int) - low) // 128
+        assert (np.abs(high) <= 127).all() and (low >= -64).all() and (low <= 63).all()
+    q = np.array([16256, 0.5, 1.5, 2.5, -0.5, -2.5], np.float32)     # delta = 1: a * r = a exactly; ties to even
+    t, s, _ = oracle.query_prep15(q, np.zeros(6, np.float32), np.ones(6, np.float32))
+    assert s == 1.0 and t.tolist() == [16256, 0, 2, 2, 0, -2]
+    t, s, qlo = oracle.query_prep15(np.zeros(d, np.float32), lo, delta)
+    assert (t == 0).all() and s == 1.0 and qlo == 0.0
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_idot15_matches_int64_and_exceeds_int32_without_harm(bits):
+    rng = np.random.default_rng(13)
+    d = 130
+    for _ in range(20):
+        t = rng.integers(-16256, 16257, size=d).astype(np.int16)
+        c = rng.integers(0, 1 << bits, size=d)
+        row = c.astype(np.uint8) if bits == 8 else (c[0::2] | (c[1::2] << 4)).astype(np.uint8)
+        assert oracle.idot15(t, row, d, bits) == int(np.dot(t.astype(np.int64), c.astype(np.int64)))
+    d = 768                                   # 16256 * 255 * 768 = 3.18e9 does not fit 32 bits
+    t = np.full(d, 16256, np.int16)
+    row = np.full(oracle.row_bytes(d, 8), 0xFF, np.uint8)
+    assert oracle.idot15(t, row, d, 8) == 16256 * 255 * d > 2 ** 31
+
+
+@pytest.mark.parametrize("bits,metric", [(8, oracle.L2), (4, oracle.L2), (8, oracle.IP), (4, oracle.IP)])
+def test_key15_is_closer_to_the_decoded_distance_than_the_int8_key(bits, metric):
+    """Same identity as for the int8 query, with the perturbation of b.q bounded
+    by (s15 / 2) * sum_j c_j: 128 times tighter, and the measured error is smaller."""
+    w = inputs.Workload("k15", 400, 32, 4, 0.3, 8, seed=5, aniso_sigma=0.5)
+    X, Q = inputs.base_vectors(w), inputs.queries(w)
+    lv = oracle.sq_fit(X, bits)
+    dec = oracle.sq_decode(lv, w.d).astype(np.float64)
+    c = (dec - lv.lo.astype(np.float64)) / lv.delta.astype(np.float64)
+    err8 = err15 = 0.0
+    for q in Q:
+        t, s, qlo = oracle.query_prep15(q, lv.lo, lv.delta)
+        t8, s8, _ = oracle.query_prep(q, lv.lo, lv.delta)
+        q64 = q.astype(np.float64)
+        for v in range(0, w.n, 7):
+            key = float(oracle.key15(metric, s, qlo, oracle.idot15(t, lv.codes[v], w.d, bits), lv.norm_term[v]))
+            key8 = float(oracle.key(metric, s8, qlo, oracle.idot(t8, lv.codes[v], w.d, bits), lv.norm_term[v]))
+            bound_dot = 0.5 * float(s) * c[v].sum()
+            if metric == oracle.L2:
+                exact = ((dec[v] - q64) ** 2).sum() - (q64 ** 2).sum()
+                tol = 2 * bound_dot + 2e-6 * (abs(exact) + (q64 ** 2).sum() + float(lv.norm_term[v]))
+            else:
+                exact = -np.dot(dec[v], q64)
+                tol = bound_dot + 2e-6 * (abs(exact) + 1)
+            assert abs(key - exact) <= tol
+            err8 += abs(key8 - exact)
+            err15 += abs(key - exact)
+    assert err15 < err8 / 8
+
+
+def test_key15_closed_forms():
+    assert oracle.key15(oracle.L2, 1.0, 0.0, 10, 100.0) == np.float32(80.0)
+    assert oracle.key15(oracle.IP, 0.5, 3.0, 8, 0.0) == np.float32(-7.0)
+    big = 16256 * 255 * 768                    # converted to fp32 once, round to nearest even
+    assert oracle.key15(oracle.IP, 1.0, 0.0, big, 0.0) == -np.float32(big)
