@@ -78,6 +78,21 @@ typedef enum { ANN_L2 = 0, ANN_IP = 1 } ann_metric;
  * returned distances stay -<q, x>.
  */
 #define ANN_DESC_UNIT_NORM_L2_KEYS 2u
+/*
+ * Fold queries to 15 bits instead of 8 (a finer low-precision distance in the
+ * sense of Appendix G): t_j = rint(a_j * 16256 / max|a|) in [-16256, 16256],
+ * s = max|a| / 16256; the value is kept as two signed bytes (t = 128 hi + lo,
+ * lo in [-64, 63]) and every code row is multiplied by both (two passes of the
+ * packed int8 dot product); the two int32 sums are joined in 64 bits,
+ * converted to fp32 with one rounding, and enter the same key formula.  The
+ * query's rounding error in q.x^ shrinks by 128; every distance evaluation
+ * costs twice the integer work and the folded query twice the bytes.  Applies
+ * to every call that folds queries for this index (search, entry scan,
+ * rescore, ann_query_prep, whose t output then is int16_t [nq][d]).  out_idot
+ * of ann_search_batch must be NULL (the products exceed 32 bits) and
+ * ann_rescore writes zeros there.
+ */
+#define ANN_DESC_QUERY_15BIT 4u
 
 /*
  * One scalar-quantization level (paper Appendix G, SQ-b with b = bits).
@@ -349,11 +364,12 @@ ann_status ann_search_batch(ann_index *index, const float *q, uint32_t nq, const
  * device image (each GPU the library runs on holds it until the process ends)
  * instead of the index's workspace.  The call makes no hipMalloc / hipFree and
  * no allocating library call.
- *   Limit: 256-byte rounded nq * folded_row + 3 * (4 * nq) bytes must fit, where
+ *   Limit: 256-byte rounded nq * folded_row + 4 * (4 * nq) bytes must fit, where
  *   folded_row is 16 bytes (8-bit codes) or 32 bytes (4-bit codes) per 16-byte
  *   chunk of a code row, for at least the chunks the search kernel's lanes
- *   cover: 128 bytes for d = 128 at 8 bits (about 59,000 queries), 1,024
- *   bytes for d = 960 at 4 bits (about 8,000).  Beyond it: ANN_ECAPACITY,
+ *   cover (twice that with ANN_DESC_QUERY_15BIT): 128 bytes for d = 128 at 8
+ *   bits (about 58,000 queries), 1,024 bytes for d = 960 at 4 bits (about
+ *   8,000).  Beyond it: ANN_ECAPACITY,
  *   nothing launched.
  *   reuse_folded_queries is refused (ANN_EINVAL): the buffer belongs to no index.
  *   Every call on a GPU shares that GPU's buffer and overwrites what the last

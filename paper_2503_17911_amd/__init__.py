@@ -24,6 +24,7 @@ MAX_EF, MAX_DEGREE, MAX_ENTRIES = 512, 64, 64
 STATIC_SCRATCH_BYTES = 8 << 20
 DESC_HOST_POINTERS = 1
 DESC_UNIT_NORM_L2_KEYS = 2
+DESC_QUERY_15BIT = 4
 OK, EINVAL, ENOMEM, EDEVICE, EUNSUPPORTED, ECAPACITY = range(6)
 _STATUS_NAMES = ["ANN_OK", "ANN_EINVAL", "ANN_ENOMEM", "ANN_EDEVICE", "ANN_EUNSUPPORTED", "ANN_ECAPACITY"]
 
@@ -135,7 +136,7 @@ def ann_sq_encode(x, n, d, bits, lo, delta, codes, norm_term, stream=None):
 
 
 def ann_upload_index(*, n, d, degree, metric, vectors, levels, adjacency, entry_point, csr_offsets=None,
-                     edge_labels=None, host_pointers=False, unit_norm_l2_keys=False, stream=None) -> int:
+                     edge_labels=None, host_pointers=False, unit_norm_l2_keys=False, query_15bit=False, stream=None) -> int:
     """levels: list of (bits, codes, lo, delta, norm_term).  Returns the opaque index handle."""
     desc = IndexDesc()
     desc.n, desc.d, desc.degree, desc.metric = n, d, degree, metric
@@ -151,7 +152,7 @@ def ann_upload_index(*, n, d, degree, metric, vectors, levels, adjacency, entry_
     desc.csr_offsets = _ptr(csr_offsets)
     desc.edge_labels = _ptr(edge_labels)
     desc.entry_point = entry_point
-    desc.flags = (DESC_HOST_POINTERS if host_pointers else 0) | (DESC_UNIT_NORM_L2_KEYS if unit_norm_l2_keys else 0)
+    desc.flags = (DESC_HOST_POINTERS if host_pointers else 0) | (DESC_UNIT_NORM_L2_KEYS if unit_norm_l2_keys else 0) | (DESC_QUERY_15BIT if query_15bit else 0)
     handle = ctypes.c_void_p()
     _check(_lib.ann_upload_index(ctypes.byref(desc), stream, ctypes.byref(handle)))
     return handle.value

@@ -30,8 +30,9 @@ struct Workspace {
   uint8_t *tq = nullptr;   // [nq_cap][tq_stride] folded query in kernel layout
   float *s = nullptr;      // [nq_cap]
   float *qlo = nullptr;    // [nq_cap]
-  int32_t *sum_t = nullptr;  // [nq_cap]
-  uint32_t tq_stride = 0;
+  int32_t *sum_t = nullptr;  // [2][nq_cap]: sums of the folded bytes, first plane then second
+  uint32_t tq_stride = 0;   // bytes per query: one plane, or two for the 15-bit query (high bytes, then low bytes)
+  uint32_t tq_plane = 0;    // bytes of one plane
   const float *folded_q = nullptr;  // the batch whose folded form the buffers hold (as last launched)
   uint32_t folded_nq = 0;
 };
@@ -52,6 +53,7 @@ struct StreamWorkspaces {
 struct ann_index {
   uint64_t n = 0;
   uint32_t d = 0, degree = 0, metric = 0, n_levels = 0, entry_point = 0;
+  uint32_t query_bits = 8;  // width of the folded query: 8, or 15 (two byte planes)
   uint32_t key_metric = 0;  // form of the low-precision keys: the metric, or ANN_L2 for unit-norm inner-product data
   float *vectors = nullptr;    // [n][d] or nullptr
   uint32_t *adjacency = nullptr;  // [n][degree]
@@ -81,10 +83,10 @@ ann_status hip_fail(hipError_t e, const char *what);
     if (e_ != hipSuccess) return ::ann::hip_fail(e_, #call); \
   } while (0)
 
-// Kernel-layout length of a folded query for a level: every 16-byte chunk of
+// Kernel-layout length of one byte plane of a folded query for a level: every 16-byte chunk of
 // codes needs 16 (8-bit) or 32 (4-bit) query bytes; zero-padded to the number
 // of chunks the kernels' lanes cover.
-inline uint32_t tq_stride_for(const LevelDev &L) {
+inline uint32_t tq_plane_for(const LevelDev &L) {
   uint32_t chunks = L.search_lanes * 4 > L.lanes_per_row ? L.search_lanes * 4 : L.lanes_per_row;
   return chunks * (L.bits == 8 ? 16u : 32u);
 }

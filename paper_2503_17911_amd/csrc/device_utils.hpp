@@ -94,6 +94,25 @@ __device__ __forceinline__ float key_from_idot(uint32_t metric, float s, float q
   return __uint_as_float(b);
 }
 
+// The same for the 15-bit folded query, whose integer dot product arrives as
+// two parts (query value = 128 * hi + lo): they are joined in 64 bits and
+// converted to fp32 with one rounding.
+__device__ __forceinline__ float key_from_idot15(uint32_t metric, float s, float qlo, int idot_hi, int idot_lo,
+                                                 float norm_term) {
+  const long long idot = (long long)idot_hi * 128 + (long long)idot_lo;
+  const float f = __ll2float_rn(idot);
+  float key;
+  if (metric == ANN_L2) {
+    float h = __fsub_rn(norm_term, __fmul_rn(2.0f, qlo));
+    key = __fmaf_rn(__fmul_rn(-2.0f, s), f, h);
+  } else {
+    key = -__fmaf_rn(s, f, qlo);
+  }
+  uint32_t b = __float_as_uint(key);
+  if ((b & 0x7FFFFFFFu) == 0) b = 0;
+  return __uint_as_float(b);
+}
+
 // Partial integer dot product of one 16-byte code chunk with this lane's
 // share of the folded query.
 //   BITS == 8: the chunk holds 16 codes stored as (c ^ 0x80), i.e. c - 128 as

@@ -19,15 +19,17 @@ __global__ __launch_bounds__(64) void entry_scan_kernel(const uint8_t *__restric
                                                         const uint32_t *__restrict__ pids, uint32_t n_pivots,
                                                         uint32_t row_stride, uint32_t n_chunks, uint32_t metric,
                                                         const uint8_t *__restrict__ tq, uint32_t tq_stride,
+                                                        uint32_t tq_plane, const int32_t *__restrict__ sum_t_lo,
                                                         const float *__restrict__ s_arr,
                                                         const float *__restrict__ qlo_arr,
                                                         const int32_t *__restrict__ sum_t, uint32_t nq,
                                                         uint32_t n_entry, uint32_t *__restrict__ out) {
+  const bool q15 = sum_t_lo != nullptr;  // 15-bit query: a second plane of low bytes
   constexpr int G = kWave / LPR, CPL = 4, TQW = TqRegs<BITS>::kWords;
   const uint32_t qi = blockIdx.x;
   if (qi >= nq) return;
   const int lane = threadIdx.x, sub = lane % LPR, grp = lane / LPR;
-  int tqr[CPL][TQW];
+  int tqr[CPL][TQW], tqr_lo[CPL][TQW];
   uint32_t coff[CPL];
 #pragma unroll
   for (int j = 0; j < CPL; ++j) {
@@ -35,10 +37,14 @@ __global__ __launch_bounds__(64) void entry_scan_kernel(const uint8_t *__restric
     coff[j] = (c < n_chunks ? c : n_chunks - 1) * 16u;
     const int *tqp = reinterpret_cast<const int *>(tq + (uint64_t)qi * tq_stride + c * (TQW * 4u));
 #pragma unroll
-    for (int w = 0; w < TQW; ++w) tqr[j][w] = tqp[w];
+    for (int w = 0; w < TQW; ++w) {
+      tqr[j][w] = tqp[w];
+      tqr_lo[j][w] = q15 ? tqp[tq_plane / 4 + w] : 0;
+    }
   }
   const float s = s_arr[qi], qlo = qlo_arr[qi];
   const int bias = BITS == 8 ? 128 * sum_t[qi] : 0;
+  const int bias_lo = BITS == 8 && q15 ? 128 * sum_t_lo[qi] : 0;
   uint64_t best[kScanKeep];
 #pragma unroll
   for (int t = 0; t < kScanKeep; ++t) best[t] = ~0ull;
@@ -46,11 +52,17 @@ __global__ __launch_bounds__(64) void entry_scan_kernel(const uint8_t *__restric
     const uint32_t pi = base + grp;
     const uint32_t pc = pi < n_pivots ? pi : n_pivots - 1;
     const uint8_t *rp = pcodes + (uint64_t)pc * row_stride;
-    int dot = 0;
+    int dot = 0, dot_lo = 0;
 #pragma unroll
-    for (int j = 0; j < CPL; ++j) dot += chunk_dot<BITS>(*reinterpret_cast<const uint4 *>(rp + coff[j]), tqr[j]);
+    for (int j = 0; j < CPL; ++j) {
+      const uint4 cj = *reinterpret_cast<const uint4 *>(rp + coff[j]);
+      dot += chunk_dot<BITS>(cj, tqr[j]);
+      if (q15) dot_lo += chunk_dot<BITS>(cj, tqr_lo[j]);
+    }
     dot = group_sum_i32<LPR>(dot) + bias;
-    const float key = key_from_idot(metric, s, qlo, dot, pnorm ? pnorm[pc] : 0.0f);
+    if (q15) dot_lo = group_sum_i32<LPR>(dot_lo) + bias_lo;
+    const float pn = pnorm ? pnorm[pc] : 0.0f;
+    const float key = q15 ? key_from_idot15(metric, s, qlo, dot, dot_lo, pn) : key_from_idot(metric, s, qlo, dot, pn);
     uint64_t c = (sub == 0 && pi < n_pivots) ? pack_ki(order_u32(key), pids[pc]) : ~0ull;
     // sorted insertion into this lane's short list
 #pragma unroll
@@ -282,7 +294,7 @@ ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_
   if (n_entry > (uint32_t)kScanKeep) return fail(ANN_ECAPACITY, "ann_entry_scan: n_entry = %u exceeds %d", n_entry, kScanKeep);
   WorkspaceLease lease;
   const LevelDev &L = index->level[0];
-  if (L.bits == 8 && n_entry == 1 && index->d <= (uint32_t)kFsMaxD) {
+  if (L.bits == 8 && n_entry == 1 && index->d <= (uint32_t)kFsMaxD && index->query_bits == 8) {
     // folding and scan in one launch, on the matrix cores
     ann_status rc = workspace_for(index, 0, nq, st, lease);
     if (rc != ANN_OK) return rc;
@@ -307,7 +319,8 @@ ann_status ann_entry_scan(ann_index *index, const float *q, uint32_t nq, uint32_
   const Workspace &w = *lease.ws;
 #define ANN_ES(B, P)                                                                                                   \
   entry_scan_kernel<B, P><<<nq, 64, 0, st>>>(index->pivot_codes, index->pivot_norm, index->pivot_ids, index->n_pivots,   \
-                                             L.row_stride, L.row_stride / 16, index->key_metric, w.tq, w.tq_stride, w.s,    \
+                                             L.row_stride, L.row_stride / 16, index->key_metric, w.tq, w.tq_stride,      \
+                                             w.tq_plane, index->query_bits == 15 ? w.sum_t + w.nq_cap : nullptr, w.s,  \
                                              w.qlo, w.sum_t, nq, n_entry, out_entry_ids)
   if (L.bits == 8) {
     switch (L.search_lanes) {

@@ -178,11 +178,12 @@ ann_status workspace_for(ann_index *ix, uint32_t level, uint32_t nq, hipStream_t
   ANN_HIP(hipDeviceSynchronize());
   free_workspace(w);
   uint32_t cap = nq < 1024 ? 1024 : nq;
-  w.tq_stride = tq_stride_for(ix->level[level]);
+  w.tq_plane = tq_plane_for(ix->level[level]);
+  w.tq_stride = w.tq_plane * (ix->query_bits == 15 ? 2u : 1u);
   ANN_HIP(hipMalloc((void **)&w.tq, (size_t)cap * w.tq_stride));
   ANN_HIP(hipMalloc((void **)&w.s, (size_t)cap * sizeof(float)));
   ANN_HIP(hipMalloc((void **)&w.qlo, (size_t)cap * sizeof(float)));
-  ANN_HIP(hipMalloc((void **)&w.sum_t, (size_t)cap * sizeof(int32_t)));
+  ANN_HIP(hipMalloc((void **)&w.sum_t, (size_t)cap * 2 * sizeof(int32_t)));
   w.nq_cap = cap;
   return ANN_OK;
 }
@@ -229,6 +230,7 @@ ann_status ann_upload_index(const ann_index_desc *desc, void *stream, ann_index 
   ix->d = desc->d;
   ix->degree = desc->degree;
   ix->metric = desc->metric;
+  ix->query_bits = (desc->flags & ANN_DESC_QUERY_15BIT) ? 15u : 8u;
   ix->key_metric = (desc->flags & ANN_DESC_UNIT_NORM_L2_KEYS) ? (uint32_t)ANN_L2 : desc->metric;
   ix->n_levels = desc->n_levels;
   ix->entry_point = desc->entry_point;

@@ -199,7 +199,9 @@ template <int BITS, int LPR>
 __global__ __launch_bounds__(64) void rescore_kernel(const uint8_t *__restrict__ codes, uint32_t row_stride,
                                                      uint32_t n_chunks, const float *__restrict__ norm_term,
                                                      uint32_t metric, uint64_t n, const uint8_t *__restrict__ tq,
-                                                     uint32_t tq_stride, const float *__restrict__ s_arr,
+                                                     uint32_t tq_stride, uint32_t tq_plane,
+                                                     const int32_t *__restrict__ sum_t_lo,
+                                                     const float *__restrict__ s_arr,
                                                      const float *__restrict__ qlo_arr,
                                                      const int32_t *__restrict__ sum_t, uint32_t nq,
                                                      const uint32_t *__restrict__ cand_ids, uint32_t n_cand,
@@ -213,12 +215,18 @@ __global__ __launch_bounds__(64) void rescore_kernel(const uint8_t *__restrict__
   const int lane = threadIdx.x, chunk = lane % LPR, grp = lane / LPR;
   constexpr int G = kWave / LPR;
   constexpr int TQW = TqRegs<BITS>::kWords;
-  int tqr[TQW];
+  // sum_t_lo given: the query has 15 bits, its low bytes are a second plane
+  const bool q15 = sum_t_lo != nullptr;
+  int tqr[TQW], tqr_lo[TQW];
   const int *tqp = reinterpret_cast<const int *>(tq + (uint64_t)qi * tq_stride + (uint32_t)chunk * (TQW * 4u));
 #pragma unroll
-  for (int w = 0; w < TQW; ++w) tqr[w] = tqp[w];
+  for (int w = 0; w < TQW; ++w) {
+    tqr[w] = tqp[w];
+    tqr_lo[w] = q15 ? tqp[tq_plane / 4 + w] : 0;
+  }
   const float s = s_arr[qi], qlo = qlo_arr[qi];
   const int bias = BITS == 8 ? 128 * sum_t[qi] : 0;
+  const int bias_lo = BITS == 8 && q15 ? 128 * sum_t_lo[qi] : 0;
   const uint32_t *cand = cand_ids + (uint64_t)qi * cand_stride;
   for (uint32_t base = 0; base < n_cand; base += G) {
     const uint32_t ci = base + grp;
@@ -232,10 +240,12 @@ __global__ __launch_bounds__(64) void rescore_kernel(const uint8_t *__restrict__
       if (norm_term && chunk == 0) nrm = norm_term[v];
     }
     const int dot = group_sum_i32<LPR>(chunk_dot<BITS>(row, tqr)) + bias;
+    int dot_lo = 0;
+    if (q15) dot_lo = group_sum_i32<LPR>(chunk_dot<BITS>(row, tqr_lo)) + bias_lo;
     if (chunk == 0 && ci < n_cand) {
-      const float key = key_from_idot(metric, s, qlo, dot, nrm);
+      const float key = q15 ? key_from_idot15(metric, s, qlo, dot, dot_lo, nrm) : key_from_idot(metric, s, qlo, dot, nrm);
       list[ci] = v == kNone ? ~0ull : pack_vi(order_u32(key), v);
-      dots[ci] = v == kNone ? 0 : dot;
+      dots[ci] = v == kNone || q15 ? 0 : dot;
     }
   }
   __syncthreads();
@@ -331,7 +341,9 @@ ann_status ann_rescore(ann_index *index, uint32_t level, const float *q, uint32_
   const size_t smem = (size_t)n_cand * (sizeof(uint64_t) + sizeof(int32_t));
 #define ANN_RS(B, P)                                                                                              \
   rescore_kernel<B, P><<<nq, 64, smem, st>>>(L.codes, L.row_stride, L.row_stride / 16, norm, index->key_metric,   \
-                                             index->n, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t, nq, cand_ids,     \
+                                             index->n, w.tq, w.tq_stride, w.tq_plane,                             \
+                                             index->query_bits == 15 ? w.sum_t + w.nq_cap : nullptr, w.s, w.qlo,  \
+                                             w.sum_t, nq, cand_ids,                                               \
                                              n_cand, cand_stride, out_ids, out_keys, out_idot)
   if (L.bits == 8) {
     switch (L.lanes_per_row) {

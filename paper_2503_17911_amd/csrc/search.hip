@@ -82,6 +82,8 @@ ann_status launch_search_with(const ann_index *index, uint32_t nq, const ann_sea
   const uint32_t ef = params->ef, p = plan.p, vis_log2 = plan.vis_log2;
   const bool cache = plan.cache, wide = plan.wide;
   const LevelDev &L = index->level[0];
+  if (index->query_bits == 15 && out_idot)
+    return fail(ANN_EINVAL, "out_idot is not available with the 15-bit query (the dot products exceed 32 bits)");
   SearchArgs a{};
   a.codes = L.codes;
   a.norm_term = index->key_metric == ANN_L2 ? L.norm_term : nullptr;
@@ -90,6 +92,9 @@ ann_status launch_search_with(const ann_index *index, uint32_t nq, const ann_sea
   a.s = w.s;
   a.qlo = w.qlo;
   a.sum_t = w.sum_t;
+  a.sum_t_lo = index->query_bits == 15 ? w.sum_t + w.nq_cap : nullptr;
+  a.tq_plane = w.tq_plane;
+  a.q15 = index->query_bits == 15 ? 1u : 0u;
   a.entry_ids = entry_ids;
   a.order = params->query_order;
   a.ef_per_query = params->ef_per_query;
@@ -123,7 +128,7 @@ ann_status launch_search_with(const ann_index *index, uint32_t nq, const ann_sea
   int m = 1;
   while (64 * m < (int)ef) m <<= 1;
   const bool multi = params->mode != 0;
-  const bool fast = packed && !a.filtered && !a.prs_codes && (!multi || (index->degree <= 32 && p == (uint32_t)kMaxExpansionsPerStep));
+  const bool fast = packed && !a.filtered && !a.prs_codes && !a.q15 && (!multi || (index->degree <= 32 && p == (uint32_t)kMaxExpansionsPerStep));
   return fast ? launch_search_fast(a, L.bits, L.search_lanes, m, multi, st)
               : launch_search_general(a, L.bits, L.search_lanes, m, multi, st);
 }
@@ -197,9 +202,10 @@ extern "C" ann_status ann_search_batch_static(ann_index *index, const float *q, 
     return fail(ANN_EINVAL, "ann_search_batch_static: reuse_folded_queries is not available (the static scratch is shared by every index)");
   // carve the folded-query buffers out of the static array
   Workspace w;
-  w.tq_stride = tq_stride_for(index->level[0]);
+  w.tq_plane = tq_plane_for(index->level[0]);
+  w.tq_stride = w.tq_plane * (index->query_bits == 15 ? 2u : 1u);
   const size_t tq_bytes = round_up_256((size_t)nq * w.tq_stride), word_bytes = round_up_256((size_t)nq * 4);
-  const size_t need = tq_bytes + 3 * word_bytes;
+  const size_t need = tq_bytes + 4 * word_bytes;
   if (need > (size_t)ANN_STATIC_SCRATCH_BYTES)
     return fail(ANN_ECAPACITY, "ann_search_batch_static: %u queries of %u folded bytes need %zu bytes of scratch, the static buffer holds %zu",
                 nq, w.tq_stride, need, (size_t)ANN_STATIC_SCRATCH_BYTES);
@@ -210,7 +216,7 @@ extern "C" ann_status ann_search_batch_static(ann_index *index, const float *q, 
   w.tq = base;
   w.s = reinterpret_cast<float *>(base + tq_bytes);
   w.qlo = reinterpret_cast<float *>(base + tq_bytes + word_bytes);
-  w.sum_t = reinterpret_cast<int32_t *>(base + tq_bytes + 2 * word_bytes);
+  w.sum_t = reinterpret_cast<int32_t *>(base + tq_bytes + 2 * word_bytes);  // two planes of nq sums
   // the folding writes every byte the search reads (rows are written whole,
   // zero padding included), so nothing of an earlier call has to be cleared
   rc = launch_query_prep_into(index, 0, q, nq, w, nullptr, nullptr, nullptr, st);

@@ -52,6 +52,7 @@ struct SearchArgs {
   const float *s;
   const float *qlo;
   const int32_t *sum_t;
+  const int32_t *sum_t_lo;  // second plane's sums (15-bit query) or nullptr
   const uint32_t *entry_ids;
   const uint32_t *order;  // processing order (workgroup -> query) or nullptr
   const uint32_t *ef_per_query;  // [nq] pool size of each query (<= ef) or nullptr
@@ -68,6 +69,8 @@ struct SearchArgs {
   uint32_t vis_cache;  // visited set is the two-way cache
   uint32_t vis_packed;  // the cache keeps 16-bit tags, two ways to a word (needs (n - 1 >> vis_log2) + 1 < 0xFFFF)
   uint32_t m_s;
+  uint32_t tq_plane;   // bytes of one plane of a folded query (tq_stride: one plane, or two for the 15-bit query)
+  uint32_t q15;        // the folded query has 15 bits: two byte planes, keys from both dot products
   uint32_t prs_slots;  // slots of every adjacency row whose code rows are in prs_codes (the first prs_slots)
   float alpha_s;
 };
@@ -149,7 +152,7 @@ struct SearchWave {
   uint32_t coff[CPL];  // byte offsets of this lane's chunks inside a code row
   uint32_t vis_mask, vis_shift, vis_limit;
   float s, qlo;
-  int bias;
+  int bias, bias_lo;
   uint32_t pk[M], pv[M];  // pool: ordered key bits; (id << 1) | expanded
   uint64_t worst;         // pool entry ef_q-1 (all ones while the pool is not full)
   int ef_q;               // this query's pool size
@@ -179,12 +182,12 @@ struct SearchWave {
 
   // This lane's part of the code/query dot product of one row: its four
   // chunks against the matching words of the folded query.
-  __device__ __forceinline__ int row_dot(const uint4 (&row)[CPL]) const {
+  __device__ __forceinline__ int row_dot(const uint4 (&row)[CPL], const int *plane) const {
     int dot = 0;
 #pragma unroll
     for (int j = 0; j < CPL; ++j) {
       int t[TQW];
-      const int4 *tp = reinterpret_cast<const int4 *>(tql + (sub + j * LPR) * TQW);
+      const int4 *tp = reinterpret_cast<const int4 *>(plane + (sub + j * LPR) * TQW);
 #pragma unroll
       for (int w = 0; w < TQW / 4; ++w) {
         const int4 v = tp[w];
@@ -196,6 +199,16 @@ struct SearchWave {
       dot += chunk_dot<BITS>(row[j], t);
     }
     return dot;
+  }
+
+  __device__ __forceinline__ int row_dot(const uint4 (&row)[CPL]) const { return row_dot(row, tql); }
+
+  // tau_l of one code row (shared by the LPR lanes that hold its chunks).
+  __device__ __forceinline__ float row_key(const uint4 (&row)[CPL], float nrm) const {
+    const int dot = group_sum_i32<LPR>(row_dot(row, tql)) + bias;
+    if (FAST || !a.q15) return key_from_idot(a.metric, s, qlo, dot, nrm);
+    const int dot_lo = group_sum_i32<LPR>(row_dot(row, tql + a.tq_plane / 4)) + bias_lo;
+    return key_from_idot15(a.metric, s, qlo, dot, dot_lo, nrm);
   }
 
   __device__ __forceinline__ void clear_table() {
@@ -578,8 +591,7 @@ struct SearchWave {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         if (base + u * G < n_cand) {
-          const int dot = group_sum_i32<LPR>(row_dot(rows[u])) + bias;
-          const float key = key_from_idot(a.metric, s, qlo, dot, nrm[u]);
+          const float key = row_key(rows[u], nrm[u]);
           const uint64_t c64 = pack64(order_u32(key), vid[u] << 1);
           const bool q = sub == 0 && base + u * G + grp < n_cand && c64 < worst;
           const uint64_t bm = __ballot(q);
@@ -631,9 +643,8 @@ struct SearchWave {
         if ((rest >> lane) & 1ull) cand_at(n_cand + lanes_below(rest)) = nb;
         n_cand += __popcll(rest);
       }
-      const int dot = group_sum_i32<LPR>(row_dot(rows)) + bias;
       const uint32_t vid = (uint32_t)__shfl((int)nb, slot & 63);
-      const float key = key_from_idot(a.metric, s, qlo, dot, nrm);
+      const float key = row_key(rows, nrm);
       const uint64_t c64 = pack64(order_u32(key), vid << 1);
       const bool q = sub == 0 && slot < S && ((fm >> (slot & 63)) & 1ull) && c64 < worst;
       const uint64_t bm = __ballot(q);
@@ -659,6 +670,7 @@ struct SearchWave {
     s = a.s[qi];
     qlo = a.qlo[qi];
     bias = BITS == 8 ? 128 * a.sum_t[qi] : 0;
+    bias_lo = BITS == 8 && a.sum_t_lo ? 128 * a.sum_t_lo[qi] : 0;
 #pragma unroll
     for (int r = 0; r < M; ++r) {
       pk[r] = kEmpty;

@@ -160,9 +160,14 @@ template <int BITS>
 __global__ __launch_bounds__(64) void query_prep_kernel(const float *__restrict__ q, uint32_t nq, uint32_t d,
                                                         const float *__restrict__ lo, const float *__restrict__ delta,
                                                         uint8_t *__restrict__ tq, uint32_t tq_stride,
+                                                        uint32_t tq_plane, uint32_t nq_cap,
                                                         float *__restrict__ s_ws, float *__restrict__ qlo_ws,
                                                         int32_t *__restrict__ sum_t_ws, int8_t *__restrict__ t_plain,
                                                         float *__restrict__ s_out, float *__restrict__ qlo_out) {
+  // One plane: the int8 query.  Two planes (tq_stride == 2 * tq_plane): the
+  // 15-bit query t = 128 * hi + lo with lo in [-64, 63], high bytes first.
+  const bool q15 = tq_stride != tq_plane;
+  const float top = q15 ? 16256.0f : 127.0f;
   const uint32_t qi = blockIdx.x;
   if (qi >= nq) return;
   const int lane = threadIdx.x;
@@ -172,12 +177,13 @@ __global__ __launch_bounds__(64) void query_prep_kernel(const float *__restrict_
   amax = wave_max_f32(amax);
   float s = 1.0f, r = 0.0f;
   if (amax > 0.0f) {
-    s = __fdiv_rn(amax, 127.0f);
-    r = __fdiv_rn(127.0f, amax);
+    s = __fdiv_rn(amax, top);
+    r = __fdiv_rn(top, amax);
   }
   uint8_t *tq_row = tq + (uint64_t)qi * tq_stride;
-  int sum = 0;
-  for (uint32_t j = lane; j < tq_stride; j += kWave) {
+  int sum = 0, sum_lo = 0;
+  const int limit = q15 ? 16256 : 127;
+  for (uint32_t j = lane; j < tq_plane; j += kWave) {
     // byte j of the kernel layout holds dimension dim(j)
     uint32_t dim;
     if constexpr (BITS == 8) {
@@ -190,13 +196,27 @@ __global__ __launch_bounds__(64) void query_prep_kernel(const float *__restrict_
     if (dim < d) {
       float a = __fmul_rn(delta[dim], qr[dim]);
       ti = __float2int_rn(__fmul_rn(a, r));  // round half to even
-      ti = ti > 127 ? 127 : (ti < -127 ? -127 : ti);
-      if (t_plain) t_plain[(uint64_t)qi * d + dim] = (int8_t)ti;
+      ti = ti > limit ? limit : (ti < -limit ? -limit : ti);
+      if (t_plain) {
+        if (q15)
+          reinterpret_cast<int16_t *>(t_plain)[(uint64_t)qi * d + dim] = (int16_t)ti;
+        else
+          t_plain[(uint64_t)qi * d + dim] = (int8_t)ti;
+      }
     }
-    tq_row[j] = (uint8_t)(int8_t)ti;
-    sum += ti;
+    if (q15) {
+      const int low = ((ti + 64) & 127) - 64, high = (ti - low) >> 7;
+      tq_row[j] = (uint8_t)(int8_t)high;
+      tq_row[tq_plane + j] = (uint8_t)(int8_t)low;
+      sum += high;
+      sum_lo += low;
+    } else {
+      tq_row[j] = (uint8_t)(int8_t)ti;
+      sum += ti;
+    }
   }
   sum = group_sum_i32<64>(sum);
+  sum_lo = group_sum_i32<64>(sum_lo);
   // every product of two floats is exact in fp64; they are formed by all lanes
   // and then added by one lane in dimension order, which fixes the rounding
   extern __shared__ double prod[];
@@ -209,6 +229,7 @@ __global__ __launch_bounds__(64) void query_prep_kernel(const float *__restrict_
     s_ws[qi] = s;
     qlo_ws[qi] = qlo;
     sum_t_ws[qi] = sum;
+    sum_t_ws[nq_cap + qi] = sum_lo;
     if (s_out) s_out[qi] = s;
     if (qlo_out) qlo_out[qi] = qlo;
   }
@@ -219,10 +240,10 @@ ann_status launch_query_prep_into(const ann_index *ix, uint32_t level, const flo
   const LevelDev &L = ix->level[level];
   const size_t smem = (size_t)ix->d * sizeof(double);
   if (L.bits == 8)
-    query_prep_kernel<8><<<nq, 64, smem, st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t,
+    query_prep_kernel<8><<<nq, 64, smem, st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.tq_plane, w.nq_cap, w.s, w.qlo, w.sum_t,
                                                t_plain, s_out, qlo_out);
   else
-    query_prep_kernel<4><<<nq, 64, smem, st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.s, w.qlo, w.sum_t,
+    query_prep_kernel<4><<<nq, 64, smem, st>>>(q, nq, ix->d, L.lo, L.delta, w.tq, w.tq_stride, w.tq_plane, w.nq_cap, w.s, w.qlo, w.sum_t,
                                                t_plain, s_out, qlo_out);
   ANN_HIP(hipGetLastError());
   return ANN_OK;

@@ -51,9 +51,10 @@ def gpu_sq_fit(X, bits, coverage=1.0):
 class GpuIndex:
     """Device index built from numpy arrays (oracle-encoded or GPU-encoded levels)."""
 
-    def __init__(self, X, adj, entry, levels, metric, csr=None, host_pointers=False, labels=None, unit_norm_l2_keys=False):
+    def __init__(self, X, adj, entry, levels, metric, csr=None, host_pointers=False, labels=None, unit_norm_l2_keys=False, query_15bit=False):
         self.n, self.d = X.shape
         self.metric = metric
+        self.query_15bit = query_15bit
         keep = []
         if host_pointers:
             conv_f = lambda a: np.ascontiguousarray(a, np.float32)
@@ -78,14 +79,14 @@ class GpuIndex:
             self.degree = degree
             self.handle = ann.ann_upload_index(n=self.n, d=self.d, degree=degree, metric=metric, vectors=xv,
                                                levels=lv, adjacency=cols_d, csr_offsets=offs_d, entry_point=entry,
-                                               edge_labels=lab, host_pointers=host_pointers, unit_norm_l2_keys=unit_norm_l2_keys,
+                                               edge_labels=lab, host_pointers=host_pointers, unit_norm_l2_keys=unit_norm_l2_keys, query_15bit=query_15bit,
                                                stream=stream_ptr())
         else:
             self.degree = adj.shape[1]
             adj_d = conv_u32(adj)
             self.handle = ann.ann_upload_index(n=self.n, d=self.d, degree=self.degree, metric=metric, vectors=xv,
                                                levels=lv, adjacency=adj_d, entry_point=entry, edge_labels=lab,
-                                               host_pointers=host_pointers, unit_norm_l2_keys=unit_norm_l2_keys,
+                                               host_pointers=host_pointers, unit_norm_l2_keys=unit_norm_l2_keys, query_15bit=query_15bit,
                                                stream=stream_ptr())
         torch.cuda.synchronize()
 
@@ -103,7 +104,7 @@ class GpuIndex:
     def query_prep(self, Q, level=0):
         nq = Q.shape[0]
         qd = dev(Q)
-        t = torch.empty((nq, self.d), dtype=torch.int8, device=DEV)
+        t = torch.empty((nq, self.d), dtype=torch.int16 if getattr(self, "query_15bit", False) else torch.int8, device=DEV)
         s = torch.empty(nq, dtype=torch.float32, device=DEV)
         qlo = torch.empty(nq, dtype=torch.float32, device=DEV)
         ann.ann_query_prep(self.handle, level, qd, nq, t, s, qlo, stream_ptr())

@@ -424,6 +424,51 @@ def test_unit_norm_index_with_euclidean_form_keys(H, bits, d, R, P):
         H.GpuIndex(X, adj, 0, [lv], oracle.L2, unit_norm_l2_keys=True)
 
 
+@pytest.mark.parametrize("metric,bits,d,R", [("l2", 8, 128, 32), ("ip", 8, 768, 48), ("l2", 4, 960, 32), ("ip", 4, 100, 16),
+                                              ("l2", 8, 30, 7)])
+def test_index_with_15_bit_queries(H, metric, bits, d, R):
+    """ANN_DESC_QUERY_15BIT: folding, search (both modes, both kinds of visited
+    set, gathered and redundant layout), entry scan and rescore against the
+    oracle run with query_bits = 15.  At d = 768 with 8-bit codes the integer
+    dot products exceed 32 bits."""
+    n, nq, ef = 2000, 16, 80
+    w, X, Q, adj = small_case(n, d, R, nq, seed=d + bits + 15, metric=metric, bits=bits, normalize=(metric == "ip"))
+    Q[2] = 0.0
+    m = metric_id(metric)
+    lv, l8 = oracle.sq_fit(X, bits), oracle.sq_fit(X, 8)
+    ix = H.GpuIndex(X, adj, 0, [lv, l8], m, query_15bit=True)
+    t, s, qlo = ix.query_prep(Q)
+    for qi in range(nq):
+        ot, os_, oq = oracle.query_prep15(Q[qi], lv.lo, lv.delta)
+        assert (t[qi] == ot).all() and s[qi].view(np.uint32) == os_.view(np.uint32)
+        assert qlo[qi].view(np.uint32) == oq.view(np.uint32)
+    for P in (1, 4):
+        orc = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=P, query_bits=15)
+        for kw in (dict(), dict(visited_slots=0)):
+            gpu = ix.search(Q, ef, want_idot=False, mode=int(P > 1), expansions_per_step=P if P > 1 else 0, **kw)
+            assert (gpu[0] == orc[0]).all() and (gpu[1].view(np.uint32) == orc[1].view(np.uint32)).all()
+            assert (gpu[3][:, 0] == orc[3][:, 0]).all() and (gpu[3][:, 2] == orc[3][:, 2]).all()
+            if not kw:
+                assert (gpu[3][:, 1] == orc[3][:, 1]).all()
+    ix.build_prs(0.5)
+    gpu = ix.search(Q, ef, want_idot=False, layout=1)
+    orc = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, query_bits=15)
+    assert (gpu[0] == orc[0]).all() and (gpu[1].view(np.uint32) == orc[1].view(np.uint32)).all()
+    with pytest.raises(H.ann.AnnError):          # the dot products do not fit the int32 output
+        ix.search(Q, ef, want_idot=True)
+    for n_piv, n_ent in ((300, 1), (64, 4)):
+        want = oracle.entry_scan(lv, d, Q, n_piv, n_ent, metric=m, query_bits=15)
+        assert (ix.entry_scan(Q, n_piv, n_ent) == want).all()
+    oid, okeys, _ = oracle.rescore_batch(l8, d, Q, orc[0], metric=m, query_bits=15)
+    gid, gkeys, gdots = ix.rescore(Q, gpu[0], level=1)
+    assert (gid == oid).all() and (gkeys.view(np.uint32) == okeys.view(np.uint32)).all() and (gdots == 0).all()
+    # the finer query changes keys, not the algorithm: an 8-bit index on the same data still matches its own oracle
+    ix8 = H.GpuIndex(X, adj, 0, [lv, l8], m)
+    assert_search_equal(ix8.search(Q, ef), oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m))
+    ix8.close()
+    ix.close()
+
+
 @pytest.mark.parametrize("metric,bits,d", [("l2", 4, 960), ("ip", 8, 96), ("l2", 8, 30)])
 def test_adaptive_rerank_length(H, metric, bits, d):
     """ann_rerank_adaptive: the per-query prefix length equals the oracle's rule

@@ -26,6 +26,8 @@ def run(H, ix, Q, ef, static, **kw):
 
 
 def test_static_scratch_entry_point_matches_the_allocating_one():
+    import torch
+
     import gpu_harness as H
     w = inputs.WORKLOADS["c1"]
     X, Q = inputs.base_vectors(w), inputs.queries(w)
@@ -52,8 +54,23 @@ def test_static_scratch_entry_point_matches_the_allocating_one():
     oi, ok, od, oc = oracle.search_batch(lv, w.d, adj, entry, Q, 64, expansions_per_step=4)
     got = run(H, ix, Q, 64, True, mode=1, expansions_per_step=4)
     assert (got[0] == oi).all() and (got[1].view(np.uint32) == ok.view(np.uint32)).all() and (got[2] == od).all()
+    # an index with 15-bit queries (two byte planes in the static buffer)
+    ix15 = H.GpuIndex(X, adj, entry, [lv], oracle.L2, query_15bit=True)
+    for q in (Q[:50], Q[:11]):
+        nq = q.shape[0]
+        outs = []
+        for static in (False, True):
+            ids = torch.full((nq, 64), -7, dtype=torch.int32, device=H.DEV)
+            keys = torch.full((nq, 64), -7.0, dtype=torch.float32, device=H.DEV)
+            fn = H.ann.ann_search_batch_static if static else H.ann.ann_search_batch
+            fn(ix15.handle, H.dev(q), nq, k=10, ef=64, out_ids=ids, out_keys=keys, stream=H.stream_ptr())
+            torch.cuda.synchronize()
+            outs.append((H.as_u32(ids), keys.cpu().numpy()))
+        assert (outs[0][0] == outs[1][0]).all() and (outs[0][1].view(np.uint32) == outs[1][1].view(np.uint32)).all()
+        oi, ok, _, _ = oracle.search_batch(lv, w.d, adj, entry, q, 64, query_bits=15)
+        assert (outs[1][0] == oi).all() and (outs[1][1].view(np.uint32) == ok.view(np.uint32)).all()
+    ix15.close()
     # beyond the static buffer: refused on the host, nothing launched
-    import torch
     big = H.ann.STATIC_SCRATCH_BYTES // 128 + 1
     with pytest.raises(H.ann.AnnError) as e:
         H.ann.ann_search_batch_static(ix.handle, H.dev(Q), big, k=10, ef=64,
