@@ -36,7 +36,8 @@ KERNEL_SOURCES = ("paper_2503_17911_amd/csrc/search_kernel.hpp", "paper_2503_179
                   "paper_2503_17911_amd/csrc/entry.hip")
 MEASURED_TRAFFIC = {
     # sha256 of KERNEL_SOURCES -> bytes per launch on c2, ef=128, multi-expansion, 10,000 queries scheduled by 256 pivots
-    "35565660437b0d78a02ad85c5ea95455342e08a1aec7a99d1e71cdf3ec5d770b": 1241229 * 1024 * 2.0 + 5002 * 1024 * 1.0,
+    # (means over the 469 launches of that grid in one run of this script under rocprofv3 --pmc, profiles/)
+    "6f6d2dced02009e358c28831c4a7bb440a2a4e96e06e8c925b84da473551a56c": 1208650 * 1024 * 2.0 + 5000.67 * 1024 * 1.0,
 }
 
 
@@ -85,6 +86,7 @@ def main():
                     help="codebook range: 1 = per-dimension min/max, below 1 = truncated (symmetric order statistics)")
     ap.add_argument("--unit-norm-l2-keys", action="store_true",
                     help="inner-product workloads with unit-norm vectors: low-precision keys in the Euclidean form")
+    ap.add_argument("--query-15bit", action="store_true", help="fold queries to 15 bits (two packed-dot passes per code row)")
     ap.add_argument("--rerank-gamma", type=float, default=-1.0,
                     help=">= 0: per-query rerank length from the key gap (ann_rerank_adaptive) instead of the fixed prefix")
     ap.add_argument("--rerank-max", type=int, default=0, help="longest reranked prefix with --rerank-gamma (0 = ef)")
@@ -158,7 +160,7 @@ def main():
     adj_d = torch.from_numpy(adj.view(np.int32)).to(dev)
     index = ann.ann_upload_index(n=n, d=d, degree=adj.shape[1], metric=metric, vectors=xd,
                                  levels=levels, adjacency=adj_d, entry_point=entry,
-                                 unit_norm_l2_keys=args.unit_norm_l2_keys, stream=st)
+                                 unit_norm_l2_keys=args.unit_norm_l2_keys, query_15bit=args.query_15bit, stream=st)
     del codes, adj_d, levels
     torch.cuda.synchronize()
 
@@ -604,7 +606,7 @@ def main():
     # make; ids are mapped back before recall is taken).  Region = the closest of
     # 1024 pivots, found with the library's own pivot scan over the base vectors.
     relabel = None
-    if entries is None and len(w.bits) == 1 and not args.layout and args.coverage == 1.0 and not adaptive and not args.unit_norm_l2_keys:
+    if entries is None and len(w.bits) == 1 and not args.layout and args.coverage == 1.0 and not adaptive and not args.unit_norm_l2_keys and not args.query_15bit:
         ann.ann_build_entry_table(index, 1024, st)
         region = torch.empty(n, dtype=torch.int32, device=dev)
         ann.ann_entry_scan(index, xd, n, 1, region, st)
@@ -663,7 +665,7 @@ def main():
     shape_label = {1_000_000: "1M", 10_000_000: "10M", 5_000_000: "5M"}.get(n, str(n)) + f" x {d} " + \
         "->".join(f"SQ{b}" for b in w.bits)
     mfma_scan = scheduling and bits == 8 and d <= 256 and (entries is None or args.n_entry == 1)
-    default_config = (not adaptive and not args.unit_norm_l2_keys and not args.rerank_mult and args.workload == "c2" and not args.n and not args.nq and not args.visited_slots and not args.visited_kind
+    default_config = (not args.query_15bit and not adaptive and not args.unit_norm_l2_keys and not args.rerank_mult and args.workload == "c2" and not args.n and not args.nq and not args.visited_slots and not args.visited_kind
                       and not args.pivots and not args.layout and not args.expansions and args.coverage == 1.0
                       and args.schedule_pivots == 256
                       and ef == 128 and mode == 1)
@@ -692,6 +694,7 @@ def main():
                    "matrix_cores_in_timed_step": ("int8 MFMA in the pivot scan that orders the batch (a dense integer contraction, "
                                                   "exact); none in the search, rescore or rerank kernels") if mfma_scan else "none",
                    "codebook": "per-dimension min/max" if args.coverage >= 1.0 else f"truncated range, coverage {args.coverage}",
+                   "query_bits": 15 if args.query_15bit else 8,
                    "key_form": "Euclidean form on unit-norm inner-product data" if args.unit_norm_l2_keys else "the metric's own",
                    "rerank": (f"per-query prefix from the key gap: gamma {args.rerank_gamma}, {min(n_rerank, ef)}..{min(args.rerank_max or ef, ef)} "
                               f"candidates, mean {float(n_reranked[nq].float().mean()):.1f}" if adaptive else f"fixed prefix of {min(n_rerank, ef)}"),
@@ -736,7 +739,8 @@ def main():
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, args.coverage,
-                                              key_metric=ann.L2 if args.unit_norm_l2_keys else metric)
+                                              key_metric=ann.L2 if args.unit_norm_l2_keys else metric,
+                                              query_bits=15 if args.query_15bit else 8)
 
     ann.ann_free_index(index)
     print(json.dumps(result), flush=True)
@@ -804,7 +808,7 @@ def oracle_fit_threaded(oracle, X, bits, coverage, threads):
     return oracle.SQLevel(bits, lo, delta, codes, norm)
 
 
-def cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, coverage=1.0, key_metric=None):
+def cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, coverage=1.0, key_metric=None, query_bits=8):
     """The CPU oracle as it stands (plain C++, -O2, no SIMD intrinsics), timed
     on this host: same workload, same ef, search + rerank, on a bounded sample
     of the queries split over the host's cores (queries are independent)."""
@@ -823,7 +827,7 @@ def cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, coverage=1.0, key
     # size the sample from a short probe so that the timed part is ~15 s of CPU work
     probe = Q[:32]
     t0 = time.perf_counter()
-    oracle.search_batch(level, w.d, adj, entry, probe, ef, metric=key_metric)
+    oracle.search_batch(level, w.d, adj, entry, probe, ef, metric=key_metric, query_bits=query_bits)
     per_q = (time.perf_counter() - t0) / len(probe)
     want = 15.0 / max(per_q, 1e-6)                      # queries worth ~15 s of CPU work
     sample = int(min(len(Q), max(threads * 8, want)))
@@ -835,7 +839,7 @@ def cpu_baseline(w, X, Q, adj, entry, ef, k, n_rerank, metric, coverage=1.0, key
         if len(idx) == 0:
             return
         for _ in range(passes):
-            ids, _, _, _ = oracle.search_batch(level, w.d, adj, entry, Qs[idx], ef, metric=key_metric)
+            ids, _, _, _ = oracle.search_batch(level, w.d, adj, entry, Qs[idx], ef, metric=key_metric, query_bits=query_bits)
             oracle.rerank_batch(X, Qs[idx], ids[:, :min(n_rerank, ef)], k, metric=metric)
 
     ts = [threading.Thread(target=work, args=(p,)) for p in parts]
