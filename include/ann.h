@@ -195,7 +195,10 @@ typedef struct {
  *                 folding pass.  ANN_EINVAL if q or nq differ from that call's.
  *   layout        0: neighbour code rows are gathered from the code table;
  *                 1: they are read from the redundant copy made by
- *                    ann_build_prs (same results; not with alpha_s / m_s).
+ *                    ann_build_prs (same results; not with alpha_s / m_s);
+ *                 2: code rows are gathered, and a neighbour's norm term is
+ *                    read with the adjacency row (ann_build_row_norms) instead
+ *                    of from the per-node array (same results).
  */
 typedef enum {
   ANN_VISITED_AUTO = 0,
@@ -287,6 +290,18 @@ ann_status ann_query_prep(ann_index *index, uint32_t level, const float *q, uint
  * Errors: ANN_EINVAL, ANN_ENOMEM.
  */
 ann_status ann_build_prs(ann_index *index, void *stream);
+/*
+ * Redundant storage of the norm terms alone (the light end of the paper's
+ * redundant layout, Section 3.3; the norm term is the extra fp32 per vector of
+ * Section 5.2's decomposition): every adjacency row is stored followed by the
+ * level-0 norm terms of its neighbours in slot order, so that a distance
+ * evaluation needs the neighbour's code row only, not a second scattered read
+ * for four bytes.  Used by searches with layout = 2.  Costs n * degree * 8
+ * bytes of device memory beside the plain adjacency.  Synchronous; a second
+ * call is a no-op.  Errors: ANN_EINVAL (NULL index; keys of the index use no
+ * norm term: inner-product keys), ANN_ENOMEM.
+ */
+ann_status ann_build_row_norms(ann_index *index, void *stream);
 /*
  * The same with a redundancy ratio below 1 (the paper's delta, Section 3.3):
  * only the first ceil(ratio * degree) slots of every adjacency row get their

@@ -30,7 +30,7 @@ _STATUS_NAMES = ["ANN_OK", "ANN_EINVAL", "ANN_ENOMEM", "ANN_EDEVICE", "ANN_EUNSU
 
 EXPORTED_SYMBOLS = ["ann_sq_train", "ann_sq_train_truncated", "ann_sq_encode", "ann_upload_index", "ann_free_index", "ann_query_prep",
                     "ann_search_batch", "ann_rescore", "ann_rerank", "ann_rerank_adaptive", "ann_bruteforce_topk", "ann_build_entry_table",
-                    "ann_entry_scan", "ann_build_prs", "ann_build_prs_ratio", "ann_schedule_queries", "ann_reserve_workspace",
+                    "ann_entry_scan", "ann_build_prs", "ann_build_prs_ratio", "ann_build_row_norms", "ann_schedule_queries", "ann_reserve_workspace",
                     "ann_search_batch_static", "ann_last_error", "ann_version"]
 
 
@@ -83,6 +83,7 @@ def _load_library() -> ctypes.CDLL:
     lib.ann_rerank_adaptive.argtypes = [vp, vp, u32, vp, vp, u32, u32, u32, ctypes.c_float, u32, vp, vp, vp, vp]
     lib.ann_bruteforce_topk.argtypes = [vp, u64, u32, vp, u32, u32, u32, vp, vp, vp]
     lib.ann_build_prs.argtypes = [vp, vp]
+    lib.ann_build_row_norms.argtypes = [vp, vp]
     lib.ann_build_prs_ratio.argtypes = [vp, ctypes.c_float, vp]
     lib.ann_build_entry_table.argtypes = [vp, u32, vp]
     lib.ann_entry_scan.argtypes = [vp, vp, u32, u32, vp, vp]
@@ -206,6 +207,10 @@ def ann_rerank_adaptive(index, q, nq, cand_ids, cand_keys, n_min, n_max, cand_st
 
 def ann_build_prs(index, stream=None):
     _check(_lib.ann_build_prs(index, stream))
+
+
+def ann_build_row_norms(index, stream=None):
+    _check(_lib.ann_build_row_norms(index, stream))
 
 
 def ann_build_prs_ratio(index, ratio, stream=None):

@@ -58,6 +58,7 @@ struct ann_index {
   float *vectors = nullptr;    // [n][d] or nullptr
   uint32_t *adjacency = nullptr;  // [n][degree]
   float *labels = nullptr;        // [n][degree] edge labels or nullptr
+  uint32_t *adjacency_norms = nullptr;  // [n][2 * degree]: every adjacency row followed by its neighbours' level-0 norm terms (bits), or nullptr
   uint8_t *prs_codes = nullptr;    // redundant layout: [n][prs_slots][row_stride] level-0 code rows of each node's first neighbours
   float *prs_norm = nullptr;       // [n][prs_slots] their norm terms (L2)
   uint32_t prs_slots = 0;          // slots per node stored that way (redundancy ratio = prs_slots / degree)

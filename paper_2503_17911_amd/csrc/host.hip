@@ -88,6 +88,22 @@ __global__ void build_prs_kernel(const uint32_t *__restrict__ adj, const uint8_t
   }
 }
 
+// Adjacency rows with the neighbours' norm terms behind them: row i is
+// adjacency[i][0 .. degree) followed by norm[adjacency[i][t]] for t in
+// 0 .. degree (zero for padding slots).
+__global__ void build_row_norms_kernel(const uint32_t *__restrict__ adj, const float *__restrict__ norm, uint64_t n,
+                                       uint32_t degree, uint32_t *__restrict__ out) {
+  const uint64_t total = n * degree;
+  for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < total; e += (uint64_t)gridDim.x * blockDim.x) {
+    const uint64_t node = e / degree;
+    const uint32_t t = (uint32_t)(e - node * degree);
+    const uint32_t v = adj[e];
+    const bool real = v != ANN_PAD_ID && v < n;
+    out[node * 2 * degree + t] = v;
+    out[node * 2 * degree + degree + t] = real ? __float_as_uint(norm[v]) : 0u;
+  }
+}
+
 __global__ void check_adjacency_kernel(const uint32_t *__restrict__ adj, uint64_t total, uint64_t n, uint32_t *bad) {
   for (uint64_t e = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; e < total; e += (uint64_t)gridDim.x * blockDim.x) {
     uint32_t v = adj[e];
@@ -121,6 +137,7 @@ void destroy(ann_index *ix) {
   (void)hipFree(ix->vectors);
   (void)hipFree(ix->adjacency);
   (void)hipFree(ix->labels);
+  (void)hipFree(ix->adjacency_norms);
   (void)hipFree(ix->pivot_codes);
   (void)hipFree(ix->prs_codes);
   (void)hipFree(ix->prs_norm);
@@ -382,6 +399,26 @@ ann_status ann_build_prs_ratio(ann_index *index, float ratio, void *stream) {
   ANN_HIP(hipGetLastError());
   ANN_HIP(hipStreamSynchronize(st));
   index->prs_slots = stored;
+  return ANN_OK;
+}
+
+ann_status ann_build_row_norms(ann_index *index, void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  if (!index) return fail(ANN_EINVAL, "ann_build_row_norms: index is NULL");
+  if (index->adjacency_norms) return ANN_OK;
+  const LevelDev &L = index->level[0];
+  if (index->key_metric != ANN_L2 || !L.norm_term)
+    return fail(ANN_EINVAL, "ann_build_row_norms: the index's keys use no norm term (inner-product keys)");
+  ANN_HIP(hipMalloc((void **)&index->adjacency_norms, (size_t)index->n * index->degree * 2 * sizeof(uint32_t)));
+  build_row_norms_kernel<<<grid_for(index->n * index->degree, 256), 256, 0, st>>>(index->adjacency, L.norm_term, index->n,
+                                                                                  index->degree, index->adjacency_norms);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) {
+    (void)hipFree(index->adjacency_norms);
+    index->adjacency_norms = nullptr;
+    return hip_fail(e, "build_row_norms_kernel");
+  }
   return ANN_OK;
 }
 

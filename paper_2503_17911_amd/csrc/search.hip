@@ -24,7 +24,8 @@ ann_status check_search_args(const char *fn, const ann_index *index, const float
   if (params->k == 0) return fail(ANN_EINVAL, "%s: k == 0", fn);
   if (params->ef < params->k) return fail(ANN_EINVAL, "%s: ef = %u < k = %u", fn, params->ef, params->k);
   if (params->ef > ANN_MAX_EF) return fail(ANN_ECAPACITY, "%s: ef = %u exceeds ANN_MAX_EF = %u", fn, params->ef, ANN_MAX_EF);
-  if (params->layout > 1) return fail(ANN_EINVAL, "%s: unknown layout %u", fn, params->layout);
+  if (params->layout > 2) return fail(ANN_EINVAL, "%s: unknown layout %u", fn, params->layout);
+  if (params->layout == 2 && !index->adjacency_norms) return fail(ANN_EINVAL, "%s: layout 2 needs ann_build_row_norms first", fn);
   if (params->layout == 1 && !index->prs_codes) return fail(ANN_EINVAL, "%s: layout 1 needs ann_build_prs first", fn);
   if (params->layout == 1 && (params->alpha_s > 0.0f || (params->m_s != 0 && params->m_s < index->degree)))
     return fail(ANN_EUNSUPPORTED, "%s: the edge filter is not available with the redundant layout", fn);
@@ -87,7 +88,9 @@ ann_status launch_search_with(const ann_index *index, uint32_t nq, const ann_sea
   SearchArgs a{};
   a.codes = L.codes;
   a.norm_term = index->key_metric == ANN_L2 ? L.norm_term : nullptr;
-  a.adjacency = index->adjacency;
+  a.adj_norms = params->layout == 2 ? 1u : 0u;
+  a.adjacency = a.adj_norms ? index->adjacency_norms : index->adjacency;
+  a.adj_stride = a.adj_norms ? 2 * index->degree : index->degree;
   a.tq = w.tq;
   a.s = w.s;
   a.qlo = w.qlo;

@@ -72,6 +72,8 @@ struct SearchArgs {
   uint32_t tq_plane;   // bytes of one plane of a folded query (tq_stride: one plane, or two for the 15-bit query)
   uint32_t q15;        // the folded query has 15 bits: two byte planes, keys from both dot products
   uint32_t prs_slots;  // slots of every adjacency row whose code rows are in prs_codes (the first prs_slots)
+  uint32_t adj_stride;  // words from one adjacency row to the next: degree, or 2 * degree with adj_norms
+  uint32_t adj_norms;   // every adjacency row is followed by the norm terms of its neighbours, in slot order
   float alpha_s;
 };
 
@@ -98,8 +100,9 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
 __host__ __device__ constexpr int merge_buf_entries(int m) { return 64 * m; }
 // Staging area of a step's qualifying candidates; during a merge (candidates
 // are in registers then) it serves as integer counters.  In the FAST kernels
-// it also holds the step's unvisited ids, in the upper word of entry i: entry j
-// is written only after id j has been read.
+// it also holds the step's unvisited ids, in the upper word of entry i (the
+// lower word: the node's norm term where it came with the adjacency row):
+// entry j is written only after id j has been read.
 __host__ __device__ constexpr int stage_entries(int m, int pmax, bool fast) {
   return fast && 32 * pmax > 64 * m ? 32 * pmax : 64 * m;
 }
@@ -119,7 +122,7 @@ __host__ __device__ inline uint32_t cand_entries(uint32_t degree, int pmax) {
 __host__ __device__ inline size_t search_smem_bytes(int m, int pmax, bool fast, uint32_t vis_log2, uint32_t degree,
                                                     uint32_t tq_stride) {
   return (size_t)(merge_buf_entries(m) + stage_area_entries(m, pmax, fast)) * 8 + ((size_t)1 << vis_log2) * 4 +
-         (fast ? 0 : (size_t)cand_entries(degree, pmax) * 4) + tq_stride;
+         (fast ? 0 : (size_t)cand_entries(degree, pmax) * 8) + tq_stride;
 }
 
 // FAST: the configuration that matters for throughput, with the run-time
@@ -133,8 +136,19 @@ struct SearchWave {
   static constexpr int U = PMAX > 1 ? ANN_U : 1;  // groups of G rows in flight
   static constexpr int TQW = TqRegs<BITS>::kWords;
 
-  // the i-th unvisited id of the current step
-  __device__ __forceinline__ uint32_t &cand_at(int i) const { return cand[FAST ? 2 * i + 1 : i]; }
+  // the i-th unvisited neighbour of the current step: id in the upper word,
+  // in the lower one the bits of its norm term if that came with the row
+  __device__ __forceinline__ uint64_t &cand_at(int i) const { return cand[i]; }
+  // Slot `slot` of node u's adjacency row: the neighbour's id and, where the
+  // rows carry them, the bits of its norm term.  The norm terms follow the ids
+  // as a block of their own (ids first: the visited filter can start when the
+  // first 4 * degree bytes have arrived; measured against (id, norm) pairs, which
+  // cost the one-expansion-per-step kernel 4 % more).
+  __device__ __forceinline__ void load_slot(uint32_t u, int slot, uint32_t &id, uint32_t &nrm) const {
+    const uint32_t *row = a.adjacency + (uint64_t)u * a.adj_stride;
+    id = row[slot];
+    nrm = a.adj_norms ? row[a.degree + slot] : 0u;
+  }
 
   __device__ __forceinline__ bool use_cache() const { return FAST || a.vis_cache != 0; }
   __device__ __forceinline__ bool use_packed() const { return FAST || a.vis_packed != 0; }
@@ -146,7 +160,7 @@ struct SearchWave {
   uint64_t *mbuf;   // LDS: sorted copy of the pool as of the last merge; merge scatter buffer
   uint64_t *stage;  // LDS: a step's qualifying candidates; counters during a merge
   uint32_t *vis;   // LDS [cap]
-  uint32_t *cand;  // LDS: unvisited neighbour ids of this step
+  uint64_t *cand;  // LDS: unvisited neighbours of this step
   const int *tql;  // LDS: the folded query, TQW words per 16-byte code chunk
   int lane, sub, grp;
   uint32_t coff[CPL];  // byte offsets of this lane's chunks inside a code row
@@ -173,8 +187,8 @@ struct SearchWave {
     mbuf = smem;
     stage = mbuf + merge_buf_entries(M);
     vis = reinterpret_cast<uint32_t *>(stage + stage_area_entries(M, PMAX, FAST));
-    cand = FAST ? reinterpret_cast<uint32_t *>(stage) : vis + cap;
-    tql = reinterpret_cast<const int *>(vis + cap + (FAST ? 0 : cand_entries(a.degree, PMAX)));
+    cand = FAST ? stage : reinterpret_cast<uint64_t *>(vis + cap);
+    tql = reinterpret_cast<const int *>(vis + cap + (FAST ? 0 : 2 * cand_entries(a.degree, PMAX)));
     vis_mask = cap - 1;
     vis_shift = 32 - a.vis_log2;
     vis_limit = use_cache() ? 0xFFFFFFFFu : cap - cap / 4;  // the cache is never rebuilt
@@ -508,18 +522,18 @@ struct SearchWave {
 
   // Visited filter and compaction for one list of node ids (one per lane):
   // unvisited ids are marked and appended to cand[n_cand ..].
-  __device__ __forceinline__ void filter_ids(uint32_t nb, int &n_cand) {
+  __device__ __forceinline__ void filter_ids(uint32_t nb, uint32_t nrm, int &n_cand) {
     const bool valid = nb != kEmpty && nb < a.n;
     const bool fresh = valid && test_and_set(nb);
     const uint64_t fm = __ballot(fresh);
-    if (fresh) cand_at(n_cand + lanes_below(fm)) = nb;
+    if (fresh) cand_at(n_cand + lanes_below(fm)) = pack64(nb, nrm);
     n_cand += __popcll(fm);
   }
 
   // The same with the cap of Algorithm 1's inner condition |N| < m_s: only the
   // first m_s unvisited ids (in lane = stored order) are taken and marked;
   // the others stay unvisited.
-  __device__ __forceinline__ void filter_ids_capped(uint32_t nb, uint32_t m_s, int &n_cand) {
+  __device__ __forceinline__ void filter_ids_capped(uint32_t nb, uint32_t nrm, uint32_t m_s, int &n_cand) {
     const bool valid = nb != kEmpty && nb < a.n;
     const bool open = valid && !lookup(nb);
     const uint64_t om = __ballot(open);
@@ -527,17 +541,17 @@ struct SearchWave {
     wave_sync();
     const bool fresh = take && test_and_set(nb);
     const uint64_t fm = __ballot(fresh);
-    if (fresh) cand_at(n_cand + lanes_below(fm)) = nb;
+    if (fresh) cand_at(n_cand + lanes_below(fm)) = pack64(nb, nrm);
     n_cand += __popcll(fm);
   }
 
   // Same for two lists at once (list 0's survivors are appended first).
-  __device__ __forceinline__ void filter_ids2(uint32_t nb0, uint32_t nb1, int &n_cand) {
+  __device__ __forceinline__ void filter_ids2(uint32_t nb0, uint32_t nrm0, uint32_t nb1, uint32_t nrm1, int &n_cand) {
     const int f = test_and_set2(nb0 != kEmpty && nb0 < a.n, nb0, nb1 != kEmpty && nb1 < a.n, nb1);
     const uint64_t fm0 = __ballot(f & 1), fm1 = __ballot(f & 2);
     const int c0 = __popcll(fm0);
-    if (f & 1) cand_at(n_cand + lanes_below(fm0)) = nb0;
-    if (f & 2) cand_at(n_cand + c0 + lanes_below(fm1)) = nb1;
+    if (f & 1) cand_at(n_cand + lanes_below(fm0)) = pack64(nb0, nrm0);
+    if (f & 2) cand_at(n_cand + c0 + lanes_below(fm1)) = pack64(nb1, nrm1);
     n_cand += c0 + __popcll(fm1);
   }
 
@@ -581,11 +595,12 @@ struct SearchWave {
           // lanes past the end of the list recompute its last node; the
           // duplicate is ignored below, and no branch is needed around loads
           const int ci = base + u * G + grp;
-          vid[u] = cand_at(ci < n_cand ? ci : n_cand - 1);
+          const uint64_t ce = cand_at(ci < n_cand ? ci : n_cand - 1);
+          vid[u] = (uint32_t)(ce >> 32);
           const uint8_t *rp = a.codes + (uint64_t)vid[u] * a.row_stride;
 #pragma unroll
           for (int j = 0; j < CPL; ++j) rows[u][j] = *reinterpret_cast<const uint4 *>(rp + coff[j]);
-          nrm[u] = a.norm_term ? a.norm_term[vid[u]] : 0.0f;
+          nrm[u] = a.adj_norms ? __uint_as_float((uint32_t)ce) : (a.norm_term ? a.norm_term[vid[u]] : 0.0f);
         }
       }
 #pragma unroll
@@ -615,7 +630,8 @@ struct SearchWave {
   // gathered from the code table the usual way by the caller.
   __device__ __forceinline__ void expand_prs(uint32_t uid, int &n_q, int &n_cand) {
     const int S = (int)a.prs_slots;
-    const uint32_t nb = lane < (int)a.degree ? a.adjacency[(uint64_t)uid * a.degree + lane] : kEmpty;
+    uint32_t nb = kEmpty, nb_nrm = 0;
+    if (lane < (int)a.degree) load_slot(uid, lane, nb, nb_nrm);
     const uint64_t rowbase = (uint64_t)uid * (uint32_t)S;
     uint64_t fm = 0;
     for (int sg = 0; sg < S; sg += G) {
@@ -640,7 +656,7 @@ struct SearchWave {
         n_dist += n_new;
         // the rest of the row: unvisited neighbours whose rows are not stored with u
         const uint64_t rest = fm & ~stored;
-        if ((rest >> lane) & 1ull) cand_at(n_cand + lanes_below(rest)) = nb;
+        if ((rest >> lane) & 1ull) cand_at(n_cand + lanes_below(rest)) = pack64(nb, nb_nrm);
         n_cand += __popcll(rest);
       }
       const uint32_t vid = (uint32_t)__shfl((int)nb, slot & 63);
@@ -690,13 +706,15 @@ struct SearchWave {
       } else if (lane == 0) {
         nb = a.entry_point;
       }
+      uint32_t nrm = 0;
+      if (a.adj_norms && nb != kEmpty && nb < a.n) nrm = __float_as_uint(a.norm_term[nb]);
       int n_cand = 0;
-      filter_ids(nb, n_cand);
+      filter_ids(nb, nrm, n_cand);
       evaluate_and_merge(n_cand);
     }
 
     const int p = PMAX == 1 || FAST ? PMAX : (int)a.p;
-    uint32_t pre_id = kEmpty, pre_row = kEmpty;  // adjacency row fetched ahead (PMAX == 1)
+    uint32_t pre_id = kEmpty, pre_row = kEmpty, pre_nrm = 0;  // adjacency row fetched ahead (PMAX == 1)
     for (;;) {
       // the p closest un-expanded pool entries, in pool order: their ids as
       // wave-uniform values, their expanded marks set in one pass per register
@@ -774,47 +792,52 @@ struct SearchWave {
 #pragma unroll
         for (int e = 0; e < PMAX; ++e) {
           if (e >= got) break;
-          uint32_t nb = kEmpty;
+          uint32_t nb = kEmpty, nrm = 0;
           if (lane < (int)a.degree) {
-            const uint64_t at = (uint64_t)uid[e] * a.degree + lane;
-            nb = a.adjacency[at];
-            if (a.labels && !(a.labels[at] <= a.alpha_s)) nb = kEmpty;
+            load_slot(uid[e], lane, nb, nrm);
+            if (a.labels && !(a.labels[(uint64_t)uid[e] * a.degree + lane] <= a.alpha_s)) nb = kEmpty;
           }
           if (PMAX == 1) {
             const uint32_t incoming = (uint32_t)__popcll(__ballot(nb != kEmpty));
             if (n_vis + incoming > vis_limit) rebuild_table();
           }
-          filter_ids_capped(nb, a.m_s, n_cand);
+          filter_ids_capped(nb, nrm, a.m_s, n_cand);
         }
       } else if (use_pairs()) {
         // two adjacency rows per pass: lanes 0-31 take one, lanes 32-63 the next
         const int slot = lane & 31;
-        uint32_t rows[PMAX / 2 > 0 ? PMAX / 2 : 1];
+        uint32_t rows[PMAX / 2 > 0 ? PMAX / 2 : 1], nrms[PMAX / 2 > 0 ? PMAX / 2 : 1];
 #pragma unroll
         for (int t = 0; t < PMAX / 2; ++t) {
           rows[t] = kEmpty;
+          nrms[t] = 0;
           if (2 * t < got) {
             const uint32_t u = lane < 32 ? uid[2 * t] : uid[2 * t + 1 < PMAX ? 2 * t + 1 : 2 * t];
-            if (u != kEmpty && slot < (int)a.degree) rows[t] = a.adjacency[(uint64_t)u * a.degree + slot];
+            if (u != kEmpty && slot < (int)a.degree) load_slot(u, slot, rows[t], nrms[t]);
           }
         }
 #pragma unroll
         for (int t = 0; t < PMAX / 2; t += 2) {
+          constexpr int kLast = PMAX / 2 > 0 ? PMAX / 2 - 1 : 0;
+          const int t1 = t + 1 < PMAX / 2 ? t + 1 : kLast;
           if (t + 1 < PMAX / 2 && 2 * (t + 1) < got)
-            filter_ids2(rows[t], rows[t + 1 < PMAX / 2 ? t + 1 : t], n_cand);
+            filter_ids2(rows[t], nrms[t], rows[t1], nrms[t1], n_cand);
           else if (2 * t < got)
-            filter_ids(rows[t], n_cand);
+            filter_ids(rows[t], nrms[t], n_cand);
         }
       } else {
-        uint32_t rows[PMAX];
+        uint32_t rows[PMAX], nrms[PMAX];
 #pragma unroll
         for (int e = 0; e < PMAX; ++e) {
           rows[e] = kEmpty;
+          nrms[e] = 0;
           if (e < got) {
-            if (PMAX == 1 && uid[e] == pre_id)
+            if (PMAX == 1 && uid[e] == pre_id) {
               rows[e] = pre_row;
-            else if (lane < (int)a.degree)
-              rows[e] = a.adjacency[(uint64_t)uid[e] * a.degree + lane];
+              nrms[e] = pre_nrm;
+            } else if (lane < (int)a.degree) {
+              load_slot(uid[e], lane, rows[e], nrms[e]);
+            }
           }
         }
         if (PMAX == 1) {
@@ -822,7 +845,8 @@ struct SearchWave {
           // candidate of this step overtakes it
           pre_id = next_id;
           pre_row = kEmpty;
-          if (next_id != kEmpty && lane < (int)a.degree) pre_row = a.adjacency[(uint64_t)next_id * a.degree + lane];
+          pre_nrm = 0;
+          if (next_id != kEmpty && lane < (int)a.degree) load_slot(next_id, lane, pre_row, pre_nrm);
         }
 #pragma unroll
         for (int e = 0; e < PMAX; ++e) {
@@ -831,7 +855,7 @@ struct SearchWave {
               const uint32_t incoming = (uint32_t)__popcll(__ballot(rows[e] != kEmpty));
               if (n_vis + incoming > vis_limit) rebuild_table();
             }
-            filter_ids(rows[e], n_cand);
+            filter_ids(rows[e], nrms[e], n_cand);
           }
         }
       }

@@ -139,6 +139,10 @@ class GpuIndex:
             ann.ann_build_prs_ratio(self.handle, ratio, stream_ptr())
         torch.cuda.synchronize()
 
+    def build_row_norms(self):
+        ann.ann_build_row_norms(self.handle, stream_ptr())
+        torch.cuda.synchronize()
+
     def entry_scan(self, Q, n_pivots, n_entry):
         nq = Q.shape[0]
         ann.ann_build_entry_table(self.handle, n_pivots, stream_ptr())

@@ -189,6 +189,63 @@ def test_redundant_layout_gives_identical_results(H, n, d, R, nq, metric, bits, 
     ix.close()
 
 
+@pytest.mark.parametrize("n,d,R,nq,metric,bits,efs", CASES)
+def test_norm_terms_read_with_the_adjacency_row_give_identical_results(H, n, d, R, nq, metric, bits, efs):
+    """Layout 2 (every adjacency row followed by its neighbours' norm terms) is a
+    storage choice: pools, keys, dots and counts equal the oracle's, with both
+    kernel families (default visited cache / complete table), in both modes,
+    with the PRS layout built beside it, and from several entries per query."""
+    import paper_2503_17911_amd as ann
+    w, X, Q, adj = small_case(n, d, R, nq, seed=n + d + R + 1, metric=metric, bits=bits, normalize=(metric == "ip"))
+    m = metric_id(metric)
+    lv = oracle.sq_fit(X, bits)
+    ix = H.GpuIndex(X, adj, 0, [lv], m)
+    if metric == "ip":
+        with pytest.raises(ann.AnnError) as e:
+            ix.build_row_norms()
+        assert e.value.status == ann.EINVAL
+        with pytest.raises(ann.AnnError):
+            ix.search(Q, efs[0], layout=2)
+        ix.close()
+        return
+    with pytest.raises(ann.AnnError):
+        ix.search(Q, efs[0], layout=2)            # not built yet
+    ix.build_row_norms()
+    ix.build_row_norms()                          # a second call is a no-op
+    for ef in efs:
+        orc = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m)
+        assert_search_equal(ix.search(Q, ef, layout=2), orc)
+        assert_search_equal(ix.search(Q, ef, layout=2, visited_slots=0), orc, check_counts=False)
+        assert_search_equal(ix.search(Q, ef), orc)                       # the plain layout still works beside it
+        for P in (3, 4):
+            orcp = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=P)
+            assert_search_equal(ix.search(Q, ef, layout=2, mode=1, expansions_per_step=P), orcp)
+            assert_search_equal(ix.search(Q, ef, layout=2, mode=1, expansions_per_step=P, visited_slots=0), orcp,
+                                check_counts=False)
+    if n > 64:
+        ent = np.stack([(np.arange(3) * 17 + 5 * q) % n for q in range(nq)]).astype(np.uint32)
+        orc = oracle.search_batch(lv, d, adj, 0, Q, efs[-1], metric=m, entries=ent)
+        assert_search_equal(ix.search(Q, efs[-1], layout=2, entries=ent), orc)
+    ix.close()
+
+
+def test_norm_terms_with_the_adjacency_row_and_the_edge_filter(H):
+    """Layout 2 under the label test and the per-expansion cap (general kernel)."""
+    w, X, Q, adj = small_case(1500, 64, 16, 16, seed=77)
+    rng = np.random.default_rng(3)
+    labels = rng.choice(np.array([1.0, 1.2, 1.4, 1.6], np.float32), size=adj.shape).astype(np.float32)
+    lv = oracle.sq_fit(X, 8)
+    ix = H.GpuIndex(X, adj, 0, [lv], oracle.L2, labels=labels)
+    ix.build_row_norms()
+    for alpha, m_s, P in ((1.2, 0, 1), (1.4, 5, 1), (0.0, 3, 1), (1.4, 0, 4)):
+        kw = dict(labels=labels, alpha_s=alpha) if alpha > 0 else {}     # alpha_s = 0 switches the label test off
+        orc = oracle.search_batch(lv, w.d, adj, 0, Q, 48, metric=oracle.L2, m_s=m_s, expansions_per_step=P, **kw)
+        gpu = ix.search(Q, 48, layout=2, alpha_s=alpha, m_s=m_s, mode=1 if P > 1 else 0,
+                        expansions_per_step=P if P > 1 else 0)
+        assert_search_equal(gpu, orc)
+    ix.close()
+
+
 @pytest.mark.parametrize("n,d,R,metric,bits", [(5000, 128, 32, "l2", 8), (2000, 960, 16, "l2", 4), (3000, 96, 32, "ip", 8),
                                                  (300, 16, 4, "ip", 8), (1500, 256, 16, "l2", 8), (1200, 300, 8, "l2", 8),
                                                  (900, 100, 8, "ip", 8)])
