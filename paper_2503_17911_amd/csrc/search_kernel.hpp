@@ -907,7 +907,7 @@ struct SearchWave {
 };
 
 template <int BITS, int LPR, int M, int PMAX, bool FAST>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? (FAST ? (PMAX > 1 ? (BITS == 8 ? ANN_WPE : 5) : 8) : 5) : (M == 4 ? 4 : 3)))) void search_kernel(SearchArgs args) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? (FAST ? (PMAX > 1 ? (BITS == 8 ? ANN_WPE : 5) : 6) : 5) : (M == 4 ? 4 : 3)))) void search_kernel(SearchArgs args) {
   extern __shared__ uint64_t smem[];
   if (blockIdx.x >= args.nq) return;
   const uint32_t qi = args.order ? args.order[blockIdx.x] : blockIdx.x;
