@@ -70,6 +70,7 @@ def main():
     ap.add_argument("--n", type=int, default=0, help="scale the base set down (debugging)")
     ap.add_argument("--nq", type=int, default=0)
     ap.add_argument("--ef", type=int, default=0, help="skip the sweep and use this ef")
+    ap.add_argument("--ef-list", default="", help="comma-separated pool sizes to sweep instead of the workload's own list")
     ap.add_argument("--mode", type=int, default=-1, help="0 exact, 1 multi-expansion; -1: fastest that meets recall")
     ap.add_argument("--expansions", type=int, default=0, help="expansions per step in mode 1 (0 = library default)")
     ap.add_argument("--visited-slots", type=int, default=0, help="LDS visited-set slots (0 = library default)")
@@ -265,7 +266,7 @@ def main():
                        out_dist if dist_ is None else dist_, st)
 
     # recall sweep
-    efs = [args.ef] if args.ef else list(w.ef)
+    efs = [args.ef] if args.ef else ([int(e) for e in args.ef_list.split(",")] if args.ef_list else list(w.ef))
     modes = [args.mode] if args.mode >= 0 else [0, 1]
     sweep = []
     sweep_counts = {}

@@ -133,7 +133,12 @@ template <int BITS, int LPR, int M, int PMAX, bool FAST>
 struct SearchWave {
   static constexpr int G = kWave / LPR;      // code rows evaluated side by side
   static constexpr int CPL = 4;              // 16-byte chunks of a row per lane
-  static constexpr int U = PMAX > 1 ? ANN_U : 1;  // groups of G rows in flight
+  // groups of G rows in flight.  With one expansion per step and wide rows
+  // (eight or more lanes to a row) a group is fewer rows than a step has
+  // candidates, so two are requested together (1M x 960 4-bit: 6 % faster;
+  // four groups, or four in the multi-expansion kernels, cost more in
+  // registers than they gain)
+  static constexpr int U = PMAX > 1 ? ANN_U : (LPR >= 8 ? 2 : 1);
   static constexpr int TQW = TqRegs<BITS>::kWords;
 
   // the i-th unvisited neighbour of the current step: id in the upper word,
