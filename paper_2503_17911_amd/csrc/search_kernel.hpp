@@ -34,6 +34,9 @@
 #ifndef ANN_U
 #define ANN_U 2
 #endif
+#ifndef ANN_FEW
+#define ANN_FEW 4
+#endif
 #ifndef ANN_WPE
 #define ANN_WPE 6
 #endif
@@ -525,6 +528,68 @@ struct SearchWave {
     refresh_worst();
   }
 
+  // Merge of a few candidates (lanes 0 .. n-1 hold them, all below the pool's
+  // last entry): one pass per candidate, its value broadcast to all lanes.
+  // Every pool entry counts the candidates below it (it moves up by that
+  // many), the candidate gets the number of pool entries and of other
+  // candidates below it; a candidate that names a node of the pool, or the same
+  // node as an earlier candidate (both: forgotten by the visited cache and
+  // evaluated again), is left out.  Then the scatter through the sorted copy as
+  // in merge().  No search, no counters, no prefix sums: cheaper than merge()
+  // while the candidates are few, and the result is the same pool.
+  __device__ __forceinline__ void merge_few(int n, uint64_t c64) {
+    uint64_t pool64[M];
+    int shift[M];
+#pragma unroll
+    for (int r = 0; r < M; ++r) {
+      pool64[r] = pack64(pk[r], pv[r]);
+      shift[r] = 0;
+    }
+    int dest = 0;
+    bool in = false;
+    int n_in = 0;
+#pragma nounroll
+    for (int j = 0; j < n; ++j) {
+      const uint32_t ck = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(c64 >> 32), j);
+      const uint32_t cv = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)c64, j);
+      const uint64_t cj = pack64(ck, cv);
+      uint64_t same = __ballot(lane < j && c64 == cj);
+#pragma unroll
+      for (int r = 0; r < M; ++r) same |= __ballot((pv[r] | 1u) == (cv | 1u));
+      if (same != 0) continue;
+      int below = 0;
+#pragma unroll
+      for (int r = 0; r < M; ++r) {
+        const bool lt = pool64[r] < cj;
+        below += __popcll(__ballot(lt));
+        shift[r] += lt ? 0 : 1;
+      }
+      if (lane == j) {
+        dest += below;
+        in = true;
+      }
+      if (lane < n && cj < c64) ++dest;
+      ++n_in;
+    }
+    if (n_in == 0) return;
+#pragma unroll
+    for (int r = 0; r < M; ++r) {
+      const int to = r * kWave + lane + shift[r];
+      if (to < 64 * M) mbuf[to] = pool64[r];
+    }
+    if (in && dest < 64 * M) mbuf[dest] = c64;
+    wave_sync();
+#pragma unroll
+    for (int r = 0; r < M; ++r) {
+      const uint64_t v = mbuf[r * kWave + lane];
+      const bool beyond = r * kWave + lane >= ef_q;  // entries pushed past the pool size are dropped
+      pk[r] = beyond ? kEmpty : (uint32_t)(v >> 32);
+      pv[r] = beyond ? kEmpty : (uint32_t)v;
+    }
+    wave_sync();
+    refresh_worst();
+  }
+
   // Visited filter and compaction for one list of node ids (one per lane):
   // unvisited ids are marked and appended to cand[n_cand ..].
   __device__ __forceinline__ void filter_ids(uint32_t nb, uint32_t nrm, int &n_cand) {
@@ -566,6 +631,13 @@ struct SearchWave {
   __device__ __forceinline__ void merge_staged(int &n_q) {
     if (n_q == 0) return;
     wave_sync();
+    if (n_q <= ANN_FEW) {
+      const uint64_t c = lane < n_q ? stage[lane] : 0;
+      wave_sync();
+      merge_few(n_q, c);
+      n_q = 0;
+      return;
+    }
     constexpr int kBatches = kStage / kWave;
     uint64_t batch[kBatches];
 #pragma unroll
