@@ -735,7 +735,7 @@ __global__ __launch_bounds__(512) void bf_own_kernel(const float *__restrict__ X
         for (int b = 0; b < 2; ++b) v = bit == 2 * i + b ? acc[b][i] : v;
       const int i_el = bit >> 1;
       const int erow = 8 * (i_el >> 2) + 4 * half + (i_el & 3);
-      const uint64_t ent = ((uint64_t)order_u32(scale * v) << 32) | ((bit & 1) ? col_id[1] : col_id[0]);
+      const uint64_t ent = ((uint64_t)order_u32(scale * v) << 32) | (col_id[0] + ((uint32_t)(bit & 1) << 5));   // column b is col_id[0] + 32 b (a select between the two array elements became an indexed read from scratch memory)
       bool pending = active && (uint32_t)(ent >> 32) < thr[erow];
       while (__ballot(pending)) {
         if (pending) {
