@@ -18,14 +18,26 @@ __device__ __forceinline__ uint64_t pack_vi(uint32_t hi, uint32_t lo) { return (
 // `emit(rank, index)` is called for every element by the lane that owns it.
 template <typename Emit>
 __device__ __forceinline__ void rank_all(const uint64_t *list, uint32_t n, int lane, Emit emit) {
-  for (uint32_t i = lane; i < n; i += kWave) {
-    const uint64_t e = list[i];
-    uint32_t rank = 0;
+  // a lane ranks four of its elements per sweep over the list: one (broadcast)
+  // LDS read serves four comparisons
+  constexpr int T = 4;
+  for (uint32_t i0 = 0; i0 < n; i0 += kWave * T) {
+    uint64_t e[T];
+    uint32_t rank[T], idx[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      idx[t] = i0 + t * kWave + lane;
+      e[t] = idx[t] < n ? list[idx[t]] : ~0ull;
+      rank[t] = 0;
+    }
     for (uint32_t j = 0; j < n; ++j) {
       const uint64_t o = list[j];
-      rank += (o < e || (o == e && j < i)) ? 1u : 0u;
+#pragma unroll
+      for (int t = 0; t < T; ++t) rank[t] += (o < e[t] || (o == e[t] && j < idx[t])) ? 1u : 0u;
     }
-    emit(rank, i, e);
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+      if (idx[t] < n) emit(rank[t], idx[t], e[t]);
   }
 }
 
@@ -228,24 +240,44 @@ __global__ __launch_bounds__(64) void rescore_kernel(const uint8_t *__restrict__
   const int bias = BITS == 8 ? 128 * sum_t[qi] : 0;
   const int bias_lo = BITS == 8 && q15 ? 128 * sum_t_lo[qi] : 0;
   const uint32_t *cand = cand_ids + (uint64_t)qi * cand_stride;
-  for (uint32_t base = 0; base < n_cand; base += G) {
-    const uint32_t ci = base + grp;
-    uint32_t v = ci < n_cand ? cand[ci] : kNone;
-    if (v != kNone && v >= n) v = kNone;
-    uint4 row = make_uint4(0, 0, 0, 0);
-    float nrm = 0.0f;
-    if (v != kNone) {
-      if (chunk < (int)n_chunks)
-        row = *reinterpret_cast<const uint4 *>(codes + (uint64_t)v * row_stride + (uint32_t)chunk * 16u);
-      if (norm_term && chunk == 0) nrm = norm_term[v];
+  // the candidate ids go to LDS first (they share the words of `dots`: entry i
+  // is read before dot product i is written), so that the rows of several
+  // groups can be requested together instead of one id and one row at a time
+  uint32_t *ids_s = reinterpret_cast<uint32_t *>(dots);
+  for (uint32_t i = lane; i < n_cand; i += kWave) {
+    const uint32_t v = cand[i];
+    ids_s[i] = v != kNone && v >= n ? kNone : v;
+  }
+  __syncthreads();
+  constexpr int UNR = 8;  // groups of G rows in flight
+  for (uint32_t base = 0; base < n_cand; base += G * UNR) {
+    uint32_t vs[UNR];
+    uint4 rows[UNR];
+    float nrms[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const uint32_t ci = base + u * G + grp;
+      vs[u] = ci < n_cand ? ids_s[ci] : kNone;
+      rows[u] = make_uint4(0, 0, 0, 0);
+      nrms[u] = 0.0f;
+      if (vs[u] != kNone) {
+        if (chunk < (int)n_chunks)
+          rows[u] = *reinterpret_cast<const uint4 *>(codes + (uint64_t)vs[u] * row_stride + (uint32_t)chunk * 16u);
+        if (norm_term && chunk == 0) nrms[u] = norm_term[vs[u]];
+      }
     }
-    const int dot = group_sum_i32<LPR>(chunk_dot<BITS>(row, tqr)) + bias;
-    int dot_lo = 0;
-    if (q15) dot_lo = group_sum_i32<LPR>(chunk_dot<BITS>(row, tqr_lo)) + bias_lo;
-    if (chunk == 0 && ci < n_cand) {
-      const float key = q15 ? key_from_idot15(metric, s, qlo, dot, dot_lo, nrm) : key_from_idot(metric, s, qlo, dot, nrm);
-      list[ci] = v == kNone ? ~0ull : pack_vi(order_u32(key), v);
-      dots[ci] = v == kNone || q15 ? 0 : dot;
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const uint32_t ci = base + u * G + grp;
+      const uint32_t v = vs[u];
+      const int dot = group_sum_i32<LPR>(chunk_dot<BITS>(rows[u], tqr)) + bias;
+      int dot_lo = 0;
+      if (q15) dot_lo = group_sum_i32<LPR>(chunk_dot<BITS>(rows[u], tqr_lo)) + bias_lo;
+      if (chunk == 0 && ci < n_cand) {
+        const float key = q15 ? key_from_idot15(metric, s, qlo, dot, dot_lo, nrms[u]) : key_from_idot(metric, s, qlo, dot, nrms[u]);
+        list[ci] = v == kNone ? ~0ull : pack_vi(order_u32(key), v);
+        dots[ci] = v == kNone || q15 ? 0 : dot;
+      }
     }
   }
   __syncthreads();
