@@ -131,7 +131,9 @@ ann_status launch_search_with(const ann_index *index, uint32_t nq, const ann_sea
   int m = 1;
   while (64 * m < (int)ef) m <<= 1;
   const bool multi = params->mode != 0;
-  const bool fast = packed && !a.filtered && !a.prs_codes && !a.q15 && (!multi || (index->degree <= 32 && p == (uint32_t)kMaxExpansionsPerStep));
+  // FAST multi-expansion kernels: the staging area (64 m entries, at least 32 per expansion) must hold a step's ids
+  const bool ids_fit = index->degree <= 32 || 64 * m >= (int)(64 * p);
+  const bool fast = packed && !a.filtered && !a.prs_codes && !a.q15 && (!multi || (ids_fit && p == (uint32_t)kMaxExpansionsPerStep));
   return fast ? launch_search_fast(a, L.bits, L.search_lanes, m, multi, st)
               : launch_search_general(a, L.bits, L.search_lanes, m, multi, st);
 }

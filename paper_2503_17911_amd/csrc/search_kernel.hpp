@@ -130,7 +130,8 @@ __host__ __device__ inline size_t search_smem_bytes(int m, int pmax, bool fast, 
 
 // FAST: the configuration that matters for throughput, with the run-time
 // switches folded away (two-way visited cache, no edge filter, plain
-// layout, PMAX expansions per step, degree <= 32 when PMAX > 1).  The general
+// layout, PMAX expansions per step; degree <= 32 when PMAX > 1, degree <= 64
+// with four or more pool registers per lane).  The general
 // kernel (FAST = false) takes every switch from SearchArgs.
 template <int BITS, int LPR, int M, int PMAX, bool FAST>
 struct SearchWave {
@@ -162,7 +163,10 @@ struct SearchWave {
   __device__ __forceinline__ bool use_packed() const { return FAST || a.vis_packed != 0; }
   __device__ __forceinline__ bool use_prs() const { return !FAST && a.prs_codes != nullptr; }
   __device__ __forceinline__ bool use_filter() const { return !FAST && a.filtered != 0; }
-  __device__ __forceinline__ bool use_pairs() const { return PMAX > 1 && (FAST || a.degree <= 32); }
+  // two adjacency rows of at most 32 slots per pass (FAST kernels with up to
+  // two pool registers per lane are only launched for such degrees: their
+  // staging area holds 32 PMAX ids; with four or more it holds 64 PMAX)
+  __device__ __forceinline__ bool use_pairs() const { return PMAX > 1 && ((FAST && M < 4) || a.degree <= 32); }
 
   const SearchArgs &a;
   uint64_t *mbuf;   // LDS: sorted copy of the pool as of the last merge; merge scatter buffer

@@ -139,9 +139,9 @@ def test_search_bit_exact_small_cases(H, n, d, R, nq, metric, bits, efs):
         assert_search_equal(gpu, orc)
         # the default configuration (visited cache: the kernels with the switches folded away)
         assert_search_equal(ix.search(Q, ef, visited_slots=0), orc, check_counts=False)
-        if R <= 32:
-            orc4 = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=4)
-            assert_search_equal(ix.search(Q, ef, mode=1, visited_slots=0), orc4, check_counts=False)
+        # multi-expansion, default configuration: degrees above 32 take the folded kernels only with ef > 192
+        orc4 = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=4)
+        assert_search_equal(ix.search(Q, ef, mode=1, visited_slots=0), orc4, check_counts=False)
     ix.close()
 
 
