@@ -36,8 +36,8 @@ KERNEL_SOURCES = ("paper_2503_17911_amd/csrc/search_kernel.hpp", "paper_2503_179
                   "paper_2503_17911_amd/csrc/entry.hip")
 MEASURED_TRAFFIC = {
     # sha256 of KERNEL_SOURCES -> bytes per launch on c2, ef=128, multi-expansion, 10,000 queries scheduled by 256 pivots
-    # (means over the 469 launches of that grid in one run of this script under rocprofv3 --pmc, profiles/)
-    "6f6d2dced02009e358c28831c4a7bb440a2a4e96e06e8c925b84da473551a56c": 1208650 * 1024 * 2.0 + 5000.67 * 1024 * 1.0,
+    # (medians over the 140 launches of that grid in one run of this script under rocprofv3 --pmc, profiles/)
+    "455df8bfb70c79868cce434f3000848ecb1fa5abf4fd9345fc7f130b256d4ca8": 837156.25 * 1024 * 2.0 + 5000.0 * 1024 * 1.0,
 }
 
 

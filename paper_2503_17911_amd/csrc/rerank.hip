@@ -16,11 +16,10 @@ __device__ __forceinline__ uint64_t pack_vi(uint32_t hi, uint32_t lo) { return (
 // Rank of every element of list[0..n) under (value, position) order, written
 // to out positions; elements equal to the all-ones sentinel sort last.
 // `emit(rank, index)` is called for every element by the lane that owns it.
-template <typename Emit>
-__device__ __forceinline__ void rank_all(const uint64_t *list, uint32_t n, int lane, Emit emit) {
-  // a lane ranks four of its elements per sweep over the list: one (broadcast)
-  // LDS read serves four comparisons
-  constexpr int T = 4;
+template <int T, typename Emit>
+__device__ __forceinline__ void rank_blocks(const uint64_t *list, uint32_t n, int lane, Emit emit) {
+  // a lane ranks T of its elements per sweep over the list: one (broadcast)
+  // LDS read serves T comparisons
   for (uint32_t i0 = 0; i0 < n; i0 += kWave * T) {
     uint64_t e[T];
     uint32_t rank[T], idx[T];
@@ -39,6 +38,14 @@ __device__ __forceinline__ void rank_all(const uint64_t *list, uint32_t n, int l
     for (int t = 0; t < T; ++t)
       if (idx[t] < n) emit(rank[t], idx[t], e[t]);
   }
+}
+
+template <typename Emit>
+__device__ __forceinline__ void rank_all(const uint64_t *list, uint32_t n, int lane, Emit emit) {
+  if (n <= (uint32_t)kWave)
+    rank_blocks<1>(list, n, lane, emit);
+  else
+    rank_blocks<4>(list, n, lane, emit);
 }
 
 // ------------------------------------------------------------------ rerank
