@@ -106,14 +106,20 @@ __host__ __device__ constexpr int merge_buf_entries(int m) { return 64 * m; }
 // it also holds the step's unvisited ids, in the upper word of entry i (the
 // lower word: the node's norm term where it came with the adjacency row):
 // entry j is written only after id j has been read.
+// With one expansion per step a step has at most ANN_MAX_DEGREE = 64 candidates.
 __host__ __device__ constexpr int stage_entries(int m, int pmax, bool fast) {
-  return fast && 32 * pmax > 64 * m ? 32 * pmax : 64 * m;
+  return pmax == 1 ? 64 : (fast && 32 * pmax > 64 * m ? 32 * pmax : 64 * m);
 }
-// During a merge the area holds 64 m integer counters (32 m entries) and,
-// behind them, the list of the batch's candidates (64 and 4 of padding).
+// During a merge the area holds 64 m integer counters (32 m entries).  The
+// list of the batch's candidates (64 and 4 of padding) lies in the merge
+// buffer itself when that has 128 entries or more: the buffer's old contents
+// are not read again once the candidates are ranked, and the scatter that
+// ends the merge rewrites every slot of it.  With 64 entries the list follows
+// the counters.
 __host__ __device__ constexpr int merge_list_at(int m) { return 32 * m; }
 __host__ __device__ constexpr int stage_area_entries(int m, int pmax, bool fast) {
-  return stage_entries(m, pmax, fast) > merge_list_at(m) + 68 ? stage_entries(m, pmax, fast) : merge_list_at(m) + 68;
+  const int need = m >= 2 ? merge_list_at(m) : merge_list_at(m) + 68;
+  return stage_entries(m, pmax, fast) > need ? stage_entries(m, pmax, fast) : need;
 }
 
 // Ids of one step's unvisited neighbours: up to pmax rows of `degree` ids.
@@ -469,7 +475,7 @@ struct SearchWave {
     if (km == 0) return;
     const int rank_p = (int)(pos >> 3);
     int *cnt = reinterpret_cast<int *>(stage);
-    uint64_t *lst = stage + merge_list_at(M);
+    uint64_t *lst = M >= 2 ? mbuf : stage + merge_list_at(M);
     int shift[M];
     int dest;
     for (;;) {
@@ -988,7 +994,7 @@ struct SearchWave {
 };
 
 template <int BITS, int LPR, int M, int PMAX, bool FAST>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? (FAST ? (PMAX > 1 ? (BITS == 8 ? ANN_WPE : 5) : 6) : 5) : (M == 4 ? 4 : 3)))) void search_kernel(SearchArgs args) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? (FAST ? (PMAX > 1 ? (BITS == 8 ? ANN_WPE : 5) : 7) : 5) : (M == 4 ? 4 : 3)))) void search_kernel(SearchArgs args) {
   extern __shared__ uint64_t smem[];
   if (blockIdx.x >= args.nq) return;
   const uint32_t qi = args.order ? args.order[blockIdx.x] : blockIdx.x;
