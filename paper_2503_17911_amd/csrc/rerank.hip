@@ -63,6 +63,11 @@ __global__ __launch_bounds__(64) void rerank_kernel(const float *__restrict__ X,
   extern __shared__ uint64_t smem64[];
   float *qs = reinterpret_cast<float *>(smem64);             // [d], 16-byte aligned
   uint64_t *list = smem64 + ((d + 3) / 4) * 2;               // [n_max]
+  // [n_max] the candidates' ids (padding and ids >= n as kNone), in the upper
+  // half of the list's memory: result j is written after id j has been read
+  // (results come in order, at most one per id), and result j ends at byte
+  // 8 j + 8 <= 4 n_max + 4 i, where id i >= j + 1 begins, as long as j < n_max
+  uint32_t *ids_s = reinterpret_cast<uint32_t *>(list) + n_max;
   const uint32_t qi = blockIdx.x;
   if (qi >= nq) return;
   const int lane = threadIdx.x, chunk = lane % LPR, grp = lane / LPR;
@@ -84,8 +89,14 @@ __global__ __launch_bounds__(64) void rerank_kernel(const float *__restrict__ X,
     if (out_n && lane == 0) out_n[qi] = n_cand;
   }
   for (uint32_t j = lane; j < d; j += kWave) qs[j] = Q[(uint64_t)qi * d + j];
-  __syncthreads();
+  // the ids go to LDS with the query, so that a round of rows costs one
+  // memory round trip instead of two (id, then row)
   const uint32_t *cand = cand_ids + (uint64_t)qi * cand_stride;
+  for (uint32_t i = lane; i < n_cand; i += kWave) {
+    const uint32_t v = cand[i];
+    ids_s[i] = v >= n ? kNone : v;   // (padding is 0xFFFFFFFF >= n)
+  }
+  __syncthreads();
   uint32_t n_valid = 0;   // candidates that name a node: their entries are kept in order at the front of the list
   // the row sums of one round (G candidates side by side) go to the list; acc is this lane's share of candidate v
   auto append = [&](uint32_t v, double acc) {
@@ -116,9 +127,7 @@ __global__ __launch_bounds__(64) void rerank_kernel(const float *__restrict__ X,
 #pragma unroll
         for (int r = 0; r < kRounds; ++r) {
           const uint32_t ci = base + r * G + grp;
-          uint32_t v = cand[ci < n_cand ? ci : n_cand - 1];
-          if (ci >= n_cand || v >= n) v = kNone;   // (padding is 0xFFFFFFFF >= n)
-          vv[r] = v;
+          vv[r] = ci < n_cand ? ids_s[ci] : kNone;
         }
 #pragma unroll
         for (int r = 0; r < kRounds; ++r) {
@@ -162,8 +171,7 @@ __global__ __launch_bounds__(64) void rerank_kernel(const float *__restrict__ X,
   }
   for (uint32_t base = 0; !done && base < n_cand; base += G) {
     const uint32_t ci = base + grp;
-    uint32_t v = ci < n_cand ? cand[ci] : kNone;
-    if (v != kNone && v >= n) v = kNone;
+    const uint32_t v = ci < n_cand ? ids_s[ci] : kNone;
     double acc = 0.0;
     if (v != kNone) {
       const float *x = X + (uint64_t)v * d;
