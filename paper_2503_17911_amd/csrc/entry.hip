@@ -48,28 +48,43 @@ __global__ __launch_bounds__(64) void entry_scan_kernel(const uint8_t *__restric
   uint64_t best[kScanKeep];
 #pragma unroll
   for (int t = 0; t < kScanKeep; ++t) best[t] = ~0ull;
-  for (uint32_t base = 0; base < n_pivots; base += G) {
-    const uint32_t pi = base + grp;
-    const uint32_t pc = pi < n_pivots ? pi : n_pivots - 1;
-    const uint8_t *rp = pcodes + (uint64_t)pc * row_stride;
-    int dot = 0, dot_lo = 0;
+  // four groups of G pivots per round: their rows are requested together, so
+  // that a round costs one trip to the pivot table (it stays in the L2s)
+  constexpr int UNR = 4;
+  for (uint32_t base = 0; base < n_pivots; base += G * UNR) {
+    uint4 rows[UNR][CPL];
+    float pn[UNR];
+    uint32_t pid[UNR];
 #pragma unroll
-    for (int j = 0; j < CPL; ++j) {
-      const uint4 cj = *reinterpret_cast<const uint4 *>(rp + coff[j]);
-      dot += chunk_dot<BITS>(cj, tqr[j]);
-      if (q15) dot_lo += chunk_dot<BITS>(cj, tqr_lo[j]);
+    for (int u = 0; u < UNR; ++u) {
+      const uint32_t pi = base + u * G + grp;
+      const uint32_t pc = pi < n_pivots ? pi : n_pivots - 1;
+      const uint8_t *rp = pcodes + (uint64_t)pc * row_stride;
+#pragma unroll
+      for (int j = 0; j < CPL; ++j) rows[u][j] = *reinterpret_cast<const uint4 *>(rp + coff[j]);
+      pn[u] = pnorm ? pnorm[pc] : 0.0f;
+      pid[u] = pids[pc];
     }
-    dot = group_sum_i32<LPR>(dot) + bias;
-    if (q15) dot_lo = group_sum_i32<LPR>(dot_lo) + bias_lo;
-    const float pn = pnorm ? pnorm[pc] : 0.0f;
-    const float key = q15 ? key_from_idot15(metric, s, qlo, dot, dot_lo, pn) : key_from_idot(metric, s, qlo, dot, pn);
-    uint64_t c = (sub == 0 && pi < n_pivots) ? pack_ki(order_u32(key), pids[pc]) : ~0ull;
-    // sorted insertion into this lane's short list
 #pragma unroll
-    for (int t = 0; t < kScanKeep; ++t) {
-      const uint64_t lo = c < best[t] ? c : best[t];
-      c = c < best[t] ? best[t] : c;
-      best[t] = lo;
+    for (int u = 0; u < UNR; ++u) {
+      const uint32_t pi = base + u * G + grp;
+      int dot = 0, dot_lo = 0;
+#pragma unroll
+      for (int j = 0; j < CPL; ++j) {
+        dot += chunk_dot<BITS>(rows[u][j], tqr[j]);
+        if (q15) dot_lo += chunk_dot<BITS>(rows[u][j], tqr_lo[j]);
+      }
+      dot = group_sum_i32<LPR>(dot) + bias;
+      if (q15) dot_lo = group_sum_i32<LPR>(dot_lo) + bias_lo;
+      const float key = q15 ? key_from_idot15(metric, s, qlo, dot, dot_lo, pn[u]) : key_from_idot(metric, s, qlo, dot, pn[u]);
+      uint64_t c = (sub == 0 && pi < n_pivots) ? pack_ki(order_u32(key), pid[u]) : ~0ull;
+      // sorted insertion into this lane's short list
+#pragma unroll
+      for (int t = 0; t < kScanKeep; ++t) {
+        const uint64_t lo = c < best[t] ? c : best[t];
+        c = c < best[t] ? best[t] : c;
+        best[t] = lo;
+      }
     }
   }
   // the n_entry smallest over all lanes, one at a time: every lane offers the
