@@ -31,14 +31,15 @@
 // execution bit for bit.  With P > 1 expansions per step the P closest
 // un-expanded entries are expanded together (rows filtered in that order).
 #pragma once
+// Tuning constants (measured on the 1M x 128 8-bit workload; a build may override them):
 #ifndef ANN_U
-#define ANN_U 2
+#define ANN_U 2  // groups of code rows requested together in the multi-expansion kernels
 #endif
 #ifndef ANN_FEW
-#define ANN_FEW 4
+#define ANN_FEW 4  // up to this many candidates are merged by merge_few(), more by merge()
 #endif
 #ifndef ANN_WPE
-#define ANN_WPE 6
+#define ANN_WPE 6  // wavefronts per SIMD the 8-bit multi-expansion FAST kernels are compiled for
 #endif
 #include "ann_internal.hpp"
 #include "device_utils.hpp"
