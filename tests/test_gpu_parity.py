@@ -229,6 +229,42 @@ def test_norm_terms_read_with_the_adjacency_row_give_identical_results(H, n, d, 
     ix.close()
 
 
+@pytest.mark.parametrize("seed", [3, 4])
+def test_random_shapes_and_option_mixes_match_the_oracle(H, seed):
+    """A seeded sweep over shapes no other case names (odd degrees, row lengths
+    that pad, tiny and large pools) crossed with the options that pick a kernel:
+    expansions per step, layout, visited set.  Pools, keys, dot products and
+    counts against the oracle, as everywhere."""
+    rng = np.random.default_rng(seed)
+    for case in range(25):
+        bits = int(rng.choice([8, 8, 4]))
+        d = int(rng.choice([16, 30, 64, 96, 100, 128, 200, 256, 384, 768, 960]))
+        n, nq = int(rng.integers(40, 2500)), int(rng.integers(3, 16))
+        R = min(int(rng.choice([3, 8, 16, 20, 32, 33, 48, 64])), n - 1)
+        metric = str(rng.choice(["l2", "l2", "ip"]))
+        w, X, Q, adj = small_case(n, d, R, nq, seed=100 * seed + case, metric=metric, bits=bits, normalize=(metric == "ip"))
+        m = metric_id(metric)
+        lv = oracle.sq_fit(X, bits)
+        ix = H.GpuIndex(X, adj, 0, [lv], m)
+        if metric == "l2":
+            ix.build_row_norms()
+        for _ in range(3):
+            ef = int(rng.choice([1, 2, 5, 16, 40, 64, 65, 100, 128, 200, 256, 300, 512]))
+            P = int(rng.choice([1, 1, 2, 3, 4, 4]))
+            kw = dict(layout=int(rng.choice([0, 2])) if metric == "l2" else 0)
+            if P > 1:
+                kw.update(mode=1, expansions_per_step=P)
+            cache = bool(rng.integers(0, 2))
+            if cache:
+                kw.update(visited_slots=0)
+            orc = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=P)
+            try:
+                assert_search_equal(ix.search(Q, ef, **kw), orc, check_counts=not cache)
+            except AssertionError as e:
+                raise AssertionError(f"case {case}: n={n} d={d} R={R} bits={bits} {metric} ef={ef} P={P} {kw}: {e}")
+        ix.close()
+
+
 def test_norm_terms_with_the_adjacency_row_and_the_edge_filter(H):
     """Layout 2 under the label test and the per-expansion cap (general kernel)."""
     w, X, Q, adj = small_case(1500, 64, 16, 16, seed=77)
