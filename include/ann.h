@@ -151,8 +151,12 @@ typedef struct {
  *                    execution of Algorithm 1 with (key, id) tie-breaking;
  *                 1: several expansions per step (faster, approximate order of
  *                    expansion; same pool/visited semantics).
- *   expansions_per_step   mode 1 only, 1..4 (0 = library default, 4): the closest
- *                 un-expanded entries expanded together in one step.
+ *   expansions_per_step   mode 1 only, 1..8 (0 = library default, 4): the closest
+ *                 un-expanded entries expanded together in one step.  More of
+ *                 them shorten a query's chain of dependent steps and evaluate
+ *                 more nodes: 8 is faster than 4 where the batch is too small
+ *                 to fill the GPU (measured on 1,000 queries with 480-byte code
+ *                 rows), slower where it does.
  *   visited_kind, visited_slots   how the visited set V is kept in LDS
  *                 (visited_slots a power of two <= 8192, 0 = library default).
  *                 ANN_VISITED_CACHE: a two-way set-associative cache of node

@@ -12,7 +12,7 @@ CSRC = PKG / "csrc"
 INCLUDE = PKG.parent / "include"
 LIBDIR = PKG / "lib"
 LIB = LIBDIR / "libann_gfx950.so"
-SOURCES = ["host.hip", "sq.hip", "search.hip", "search_fast.hip", "search_general.hip", "rerank.hip", "bruteforce.hip", "entry.hip", "schedule.hip"]
+SOURCES = ["host.hip", "sq.hip", "search.hip", "search_fast.hip", "search_general.hip", "search_fast_wide.hip", "search_general_wide.hip", "rerank.hip", "bruteforce.hip", "entry.hip", "schedule.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -ffp-contract=off: roundings are part of the results that must match a
 # reference bit for bit; fused multiply-adds are written explicitly (fmaf).

@@ -34,7 +34,7 @@ ann_status check_search_args(const char *fn, const ann_index *index, const float
   if (params->mode > 1) return fail(ANN_EINVAL, "%s: unknown mode %u", fn, params->mode);
   if (params->mode == 0 && params->expansions_per_step > 1) return fail(ANN_EINVAL, "%s: expansions_per_step needs mode 1", fn);
   if (params->expansions_per_step > (uint32_t)kMaxExpansionsPerStep) return fail(ANN_ECAPACITY, "%s: expansions_per_step = %u exceeds %d", fn, params->expansions_per_step, kMaxExpansionsPerStep);
-  const uint32_t p = params->mode == 0 ? 1u : (params->expansions_per_step ? params->expansions_per_step : (uint32_t)kMaxExpansionsPerStep);
+  const uint32_t p = params->mode == 0 ? 1u : (params->expansions_per_step ? params->expansions_per_step : (uint32_t)kDefaultExpansionsPerStep);
   if (entry_ids && n_entry == 0) return fail(ANN_EINVAL, "%s: entry_ids given with n_entry == 0", fn);
   if (entry_ids && n_entry > ANN_MAX_ENTRIES) return fail(ANN_ECAPACITY, "%s: n_entry = %u exceeds ANN_MAX_ENTRIES = %u", fn, n_entry, ANN_MAX_ENTRIES);
 
@@ -131,9 +131,15 @@ ann_status launch_search_with(const ann_index *index, uint32_t nq, const ann_sea
   int m = 1;
   while (64 * m < (int)ef) m <<= 1;
   const bool multi = params->mode != 0;
+  // more than the default number of expansions per step: the kernels built for the maximum
+  const bool wide_step = multi && p > (uint32_t)kDefaultExpansionsPerStep;
+  const uint32_t p_built = wide_step ? (uint32_t)kMaxExpansionsPerStep : (uint32_t)kDefaultExpansionsPerStep;
   // FAST multi-expansion kernels: the staging area (64 m entries, at least 32 per expansion) must hold a step's ids
-  const bool ids_fit = index->degree <= 32 || 64 * m >= (int)(64 * p);
-  const bool fast = packed && !a.filtered && !a.prs_codes && !a.q15 && (!multi || (ids_fit && p == (uint32_t)kMaxExpansionsPerStep));
+  const bool ids_fit = index->degree <= 32 || 64 * m >= (int)(64 * p_built);
+  const bool fast = packed && !a.filtered && !a.prs_codes && !a.q15 && (!multi || (ids_fit && p == p_built));
+  if (wide_step)
+    return fast ? launch_search_fast_wide(a, L.bits, L.search_lanes, m, st)
+                : launch_search_general_wide(a, L.bits, L.search_lanes, m, st);
   return fast ? launch_search_fast(a, L.bits, L.search_lanes, m, multi, st)
               : launch_search_general(a, L.bits, L.search_lanes, m, multi, st);
 }

@@ -3,6 +3,6 @@
 
 namespace ann {
 ann_status launch_search_fast(const SearchArgs &a, uint32_t bits, uint32_t lpr, int m, bool multi, hipStream_t st) {
-  return launch_search<true>(a, bits, lpr, m, multi, st);
+  return launch_search<true, false>(a, bits, lpr, m, multi, st);
 }
 }  // namespace ann

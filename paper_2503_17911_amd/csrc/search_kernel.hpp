@@ -32,6 +32,16 @@
 // un-expanded entries are expanded together (rows filtered in that order).
 #pragma once
 // Tuning constants (measured on the 1M x 128 8-bit workload; a build may override them):
+// Wavefronts per SIMD a kernel is compiled for set its register budget (512 / n, in eights).  LDS is handed
+// out in blocks of 1,280 bytes, 128 to a compute unit: 5 blocks (up to 6,400 B) let 25 one-wavefront workgroups
+// stay resident, 6 blocks 21, 4 blocks 32.  Measured: the multi-expansion kernels need their 80 (four
+// expansions) and 96 (eight) registers - compiled for one wavefront more they spill and run 15-17 % slower.
+#ifndef ANN_WPE_EXACT
+#define ANN_WPE_EXACT 7  // one expansion per step, FAST kernels (72 registers)
+#endif
+#ifndef ANN_WPE_WIDE
+#define ANN_WPE_WIDE 5  // eight expansions per step, FAST kernels (96 registers)
+#endif
 #ifndef ANN_U
 #define ANN_U 2  // groups of code rows requested together in the multi-expansion kernels
 #endif
@@ -995,7 +1005,7 @@ struct SearchWave {
 };
 
 template <int BITS, int LPR, int M, int PMAX, bool FAST>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? (FAST ? (PMAX > 1 ? (BITS == 8 ? ANN_WPE : 5) : 7) : 5) : (M == 4 ? 4 : 3)))) void search_kernel(SearchArgs args) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(M <= 2 ? (FAST ? (PMAX > 4 ? ANN_WPE_WIDE : (PMAX > 1 ? (BITS == 8 ? ANN_WPE : 5) : ANN_WPE_EXACT)) : 5) : (M == 4 ? 4 : 3)))) void search_kernel(SearchArgs args) {
   extern __shared__ uint64_t smem[];
   if (blockIdx.x >= args.nq) return;
   const uint32_t qi = args.order ? args.order[blockIdx.x] : blockIdx.x;
@@ -1030,17 +1040,30 @@ static ann_status launch_lpr(const SearchArgs &args, uint32_t lpr, int m, hipStr
   }
 }
 
-constexpr int kMaxExpansionsPerStep = 4;
+// Expansions per step: any count up to kMaxExpansionsPerStep; the kernels are
+// built for 1, 4 and 8 picked entries (a count in between runs in the next
+// larger general kernel).  The library default stays at 4: eight shorten a
+// query's chain of dependent steps (fewer, wider steps: better when the batch
+// is too small to fill the chip) but evaluate more nodes (worse when it does).
+constexpr int kMaxExpansionsPerStep = 8;
+constexpr int kDefaultExpansionsPerStep = 4;
 
-// One translation unit per FAST value instantiates its kernels through this.
-template <bool FAST>
+// One translation unit per (FAST, PMAX > 4) instantiates its kernels through this.
+template <bool FAST, bool WIDE_STEP>
 static ann_status launch_search(const SearchArgs &a, uint32_t bits, uint32_t lpr, int m, bool multi, hipStream_t st) {
-  if (!multi) return bits == 8 ? launch_lpr<8, 1, FAST>(a, lpr, m, st) : launch_lpr<4, 1, FAST>(a, lpr, m, st);
-  return bits == 8 ? launch_lpr<8, kMaxExpansionsPerStep, FAST>(a, lpr, m, st)
-                   : launch_lpr<4, kMaxExpansionsPerStep, FAST>(a, lpr, m, st);
+  if constexpr (WIDE_STEP) {
+    return bits == 8 ? launch_lpr<8, kMaxExpansionsPerStep, FAST>(a, lpr, m, st)
+                     : launch_lpr<4, kMaxExpansionsPerStep, FAST>(a, lpr, m, st);
+  } else {
+    if (!multi) return bits == 8 ? launch_lpr<8, 1, FAST>(a, lpr, m, st) : launch_lpr<4, 1, FAST>(a, lpr, m, st);
+    return bits == 8 ? launch_lpr<8, kDefaultExpansionsPerStep, FAST>(a, lpr, m, st)
+                     : launch_lpr<4, kDefaultExpansionsPerStep, FAST>(a, lpr, m, st);
+  }
 }
 
 ann_status launch_search_fast(const SearchArgs &a, uint32_t bits, uint32_t lpr, int m, bool multi, hipStream_t st);
 ann_status launch_search_general(const SearchArgs &a, uint32_t bits, uint32_t lpr, int m, bool multi, hipStream_t st);
+ann_status launch_search_fast_wide(const SearchArgs &a, uint32_t bits, uint32_t lpr, int m, hipStream_t st);
+ann_status launch_search_general_wide(const SearchArgs &a, uint32_t bits, uint32_t lpr, int m, hipStream_t st);
 
 }  // namespace ann

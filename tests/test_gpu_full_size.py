@@ -19,9 +19,9 @@ pytestmark = pytest.mark.gpu
 PAD = 0xFFFFFFFF
 
 # workload, [(ef, mode, P)], sample stride for the fp64 ground truth
-FULL = [("c3", [(128, 0, 1), (256, 1, 4)], 67),
-        ("c4", [(64, 0, 1), (128, 1, 4)], 997),
-        ("c5", [(256, 0, 1), (512, 1, 4)], 1250)]
+FULL = [("c3", [(128, 0, 1), (256, 1, 4), (256, 1, 8)], 67),
+        ("c4", [(64, 0, 1), (128, 1, 4), (128, 1, 8)], 997),
+        ("c5", [(256, 0, 1), (512, 1, 4), (512, 1, 8)], 1250)]
 
 
 def oracle_fit(X, bits):

@@ -142,12 +142,19 @@ def test_search_bit_exact_small_cases(H, n, d, R, nq, metric, bits, efs):
         # multi-expansion, default configuration: degrees above 32 take the folded kernels only with ef > 192
         orc4 = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=4)
         assert_search_equal(ix.search(Q, ef, mode=1, visited_slots=0), orc4, check_counts=False)
+        # eight expansions per step: the kernels with the wider step (degrees above 32: folded only with ef > 448)
+        orc8 = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=8)
+        assert_search_equal(ix.search(Q, ef, mode=1, expansions_per_step=8, visited_slots=0), orc8, check_counts=False)
+        assert_search_equal(ix.search(Q, ef, mode=1, expansions_per_step=8), orc8)
     ix.close()
 
 
 @pytest.mark.parametrize("n,d,R,nq,metric,bits,ef,P", [
     (10000, 128, 32, 50, "l2", 8, 64, 4), (10000, 128, 32, 50, "l2", 8, 128, 2), (3000, 96, 32, 20, "ip", 8, 256, 3),
-    (1500, 960, 32, 8, "l2", 4, 100, 4), (1200, 768, 48, 8, "ip", 4, 512, 4), (40, 16, 5, 6, "l2", 8, 16, 4)])
+    (1500, 960, 32, 8, "l2", 4, 100, 4), (1200, 768, 48, 8, "ip", 4, 512, 4), (40, 16, 5, 6, "l2", 8, 16, 4),
+    (10000, 128, 32, 50, "l2", 8, 128, 8), (10000, 128, 32, 50, "l2", 8, 64, 6), (3000, 96, 32, 20, "ip", 8, 256, 5),
+    (1500, 960, 32, 8, "l2", 4, 256, 8), (1200, 768, 48, 8, "ip", 4, 512, 8), (1200, 768, 64, 8, "ip", 4, 300, 7),
+    (40, 16, 5, 6, "l2", 8, 16, 8)])
 def test_multi_expansion_matches_the_batched_oracle(H, n, d, R, nq, metric, bits, ef, P):
     """Fast mode: the P closest un-expanded entries per step.  Same pool and
     visited semantics, so it too is compared bit for bit, against the oracle
@@ -217,7 +224,7 @@ def test_norm_terms_read_with_the_adjacency_row_give_identical_results(H, n, d, 
         assert_search_equal(ix.search(Q, ef, layout=2), orc)
         assert_search_equal(ix.search(Q, ef, layout=2, visited_slots=0), orc, check_counts=False)
         assert_search_equal(ix.search(Q, ef), orc)                       # the plain layout still works beside it
-        for P in (3, 4):
+        for P in (3, 4, 8):
             orcp = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=P)
             assert_search_equal(ix.search(Q, ef, layout=2, mode=1, expansions_per_step=P), orcp)
             assert_search_equal(ix.search(Q, ef, layout=2, mode=1, expansions_per_step=P, visited_slots=0), orcp,
@@ -250,7 +257,7 @@ def test_random_shapes_and_option_mixes_match_the_oracle(H, seed):
             ix.build_row_norms()
         for _ in range(3):
             ef = int(rng.choice([1, 2, 5, 16, 40, 64, 65, 100, 128, 200, 256, 300, 512]))
-            P = int(rng.choice([1, 1, 2, 3, 4, 4]))
+            P = int(rng.choice([1, 1, 2, 3, 4, 4, 5, 6, 7, 8, 8]))
             kw = dict(layout=int(rng.choice([0, 2])) if metric == "l2" else 0)
             if P > 1:
                 kw.update(mode=1, expansions_per_step=P)
@@ -419,7 +426,7 @@ def test_small_visited_table_rebuilds_without_changing_results(H, c1):
 
 
 @pytest.mark.parametrize("slots", [64, 256, 1024, 8192])
-@pytest.mark.parametrize("P", [1, 4])
+@pytest.mark.parametrize("P", [1, 4, 8])
 def test_visited_cache_forgets_without_changing_results(H, c1, slots, P):
     """The default visited set is a small two-way cache that forgets a node when
     another takes its slot.  A forgotten node is evaluated again and then either
@@ -653,7 +660,7 @@ def c2_full(H):
     ix.close()
 
 
-@pytest.mark.parametrize("ef,mode,P", [(128, 0, 1), (128, 1, 4), (256, 1, 4)])
+@pytest.mark.parametrize("ef,mode,P", [(128, 0, 1), (128, 1, 4), (256, 1, 4), (128, 1, 8)])
 def test_c2_full_size_every_query_against_the_oracle(H, c2_full, ef, mode, P):
     """The benchmark workload in the launch configuration bench.py times
     (default visited set, scheduled batch, reused folding, both modes): all
@@ -685,13 +692,16 @@ def test_c2_multi_expansion_recall_is_within_0p005_of_the_sequential_oracle(H, c
     w, X, Q, adj, entry, lv, ix, order, gt = (c2_full[k] for k in ("w", "X", "Q", "adj", "entry", "lv", "ix", "order", "gt"))
     for ef in w.ef:
         n_r = min(2 * w.k, ef)
-        ids, _, _, _ = ix.search(Q, ef, k=w.k, want_idot=False, mode=1, visited_slots=0, query_order=order)
-        rid, _ = ix.rerank(Q, ids, n_r, w.k)
         oi, ok, _, oc = threaded(lambda sl: oracle.search_batch(lv, w.d, adj, entry, Q[sl], ef), w.nq)
         roid, _ = threaded(lambda sl: oracle.rerank_batch(X, Q[sl], oi[sl, :n_r], w.k), w.nq)
-        r_gpu, r_orc = oracle.recall(rid, gt), oracle.recall(roid, gt)
-        print(f"c2 ef={ef}: recall@10 multi-expansion {r_gpu:.4f}, sequential oracle {r_orc:.4f}")
-        assert r_gpu >= r_orc - 0.005, (ef, r_gpu, r_orc)
+        r_orc = oracle.recall(roid, gt)
+        for P in (0, 8):                  # the library's default (four) and the most it takes
+            ids, _, _, _ = ix.search(Q, ef, k=w.k, want_idot=False, mode=1, expansions_per_step=P, visited_slots=0,
+                                     query_order=order)
+            rid, _ = ix.rerank(Q, ids, n_r, w.k)
+            r_gpu = oracle.recall(rid, gt)
+            print(f"c2 ef={ef}: recall@10 multi-expansion ({P or 4} per step) {r_gpu:.4f}, sequential oracle {r_orc:.4f}")
+            assert r_gpu >= r_orc - 0.005, (ef, P, r_gpu, r_orc)
         # exact mode returns the oracle's ids, so its recall is the oracle's
         eid, _, _, _ = ix.search(Q, ef, k=w.k, want_idot=False, mode=0, visited_slots=0, query_order=order)
         assert (eid == oi).all()

@@ -92,7 +92,7 @@ def test_label_filter_paper_example():
     assert cnt[0, 1] == 1 + len(g["visited"])
 
 
-@pytest.mark.parametrize("P", [1, 2, 4])
+@pytest.mark.parametrize("P", [1, 2, 4, 8])
 @pytest.mark.parametrize("metric,bits", [(oracle.L2, 8), (oracle.IP, 8), (oracle.L2, 4)])
 def test_ef_at_least_n_is_bruteforce_under_tau_l(metric, bits, P):
     """With ef >= N on a graph where every node is reachable the final pool is
@@ -110,7 +110,7 @@ def test_ef_at_least_n_is_bruteforce_under_tau_l(metric, bits, P):
         assert cnt[qi].tolist() == [300, 300, 300, 0]
 
 
-@pytest.mark.parametrize("P", [1, 2, 4])
+@pytest.mark.parametrize("P", [1, 2, 4, 8])
 def test_complete_graph_one_expansion_sees_everything(P):
     n, ef = 40, 7
     w = inputs.Workload("cg", n, 8, 3, 0.3, 4, seed=3)
@@ -126,7 +126,7 @@ def test_complete_graph_one_expansion_sees_everything(P):
         assert cnt[qi, 0] in (ef, ef + 1)       # entry + survivors (entry may or may not survive)
 
 
-@pytest.mark.parametrize("P", [1, 2, 3, 4])
+@pytest.mark.parametrize("P", [1, 2, 3, 4, 7, 8])
 @pytest.mark.parametrize("metric,bits,ef", [(oracle.L2, 8, 10), (oracle.IP, 8, 33), (oracle.L2, 4, 64)])
 def test_properties_that_hold_for_any_number_of_expansions_per_step(metric, bits, ef, P):
     """Whatever P is: (1) the pool is the ef smallest (key, id) pairs over the
@@ -173,7 +173,7 @@ def test_matches_naive_python_search_with_heavy_ties(seed):
         for metric in (oracle.L2, oracle.IP):
             entries = rng.integers(0, n, size=(len(Q), 3)).astype(np.uint32)
             entries[:, 2] = entries[:, 0]       # duplicate entry
-            for use_labels, P in ((False, 1), (True, 1), (False, 3), (True, 2)):
+            for use_labels, P in ((False, 1), (True, 1), (False, 3), (True, 2), (False, 8), (True, 6)):
                 kw = dict(labels=labels, alpha_s=1.2, m_s=3) if use_labels else {}
                 kw["expansions_per_step"] = P
                 ids, keys, dots, cnt = oracle.search_batch(lv, 4, adj, 0, Q, ef, metric=metric, entries=entries,
