@@ -268,10 +268,10 @@ def main():
     # recall sweep
     efs = [args.ef] if args.ef else ([int(e) for e in args.ef_list.split(",")] if args.ef_list else list(w.ef))
     modes = [args.mode] if args.mode >= 0 else [0, 1]
-    # expansions per step of the multi-expansion mode: the library's default (4) and its maximum (8: fewer and
+    # expansions per step of the multi-expansion mode: 4 and the library's maximum (8: fewer and
     # wider steps, more evaluations - faster where the batch does not fill the chip), unless one is asked for
-    p_lists = {0: [0], 1: [args.expansions] if args.expansions else [0, 8]}
-    p_of = lambda mode_, p_: 1 if mode_ == 0 else (p_ or 4)
+    p_lists = {0: [0], 1: [args.expansions] if args.expansions else [4, 8]}
+    p_of = lambda mode_, p_: 1 if mode_ == 0 else p_
     sweep = []
     sweep_counts = {}
     chosen = None
@@ -604,7 +604,7 @@ def main():
                 ann.ann_schedule_queries(ent, nq, n, v_order, st)
                 order_v = v_order
             ann.ann_search_batch(index, qd, nq, k=k, ef=ef_v, mode=1, out_ids=pool_v, out_keys=keys_of(pool_v), entry_ids=ent, n_entry=1,
-                                 expansions_per_step=args.expansions if mode == 1 else 0,
+                                 expansions_per_step=args.expansions if mode == 1 else ann.ann_default_expansions_per_step(ef_v, adj.shape[1]),
                                  query_order=order_v, reuse_folded_queries=True, layout=args.layout if args.layout != 1 else 0, stream=st)
             finish(pool_v, ef_v)
 
@@ -623,7 +623,7 @@ def main():
                 torch.cuda.synchronize()
                 ms_v = v0.elapsed_time(v1) / n_v
                 variant = {"entry": "closest of 1024 scanned pivots", "ef": ef_v,
-                           "mode": f"multi-expansion ({p_of(1, args.expansions if mode == 1 else 0)} per step)",
+                           "mode": f"multi-expansion ({args.expansions if mode == 1 else ann.ann_default_expansions_per_step(ef_v, adj.shape[1])} per step)",
                            f"recall_at_{k}": round(rec_v, 4), "ms_per_step": round(ms_v, 4),
                            "value": round(nq / (ms_v * 1e-3), 1)}
                 log(f"[bench] variant with entry-point stage: ef={ef_v} recall@{k}={rec_v:.4f} {ms_v:.3f} ms/step "
@@ -737,7 +737,7 @@ def main():
         "->".join(f"SQ{b}" for b in w.bits)
     mfma_scan = scheduling and bits == 8 and d <= 256 and (entries is None or args.n_entry == 1)
     default_config = (not args.query_15bit and not adaptive and not args.unit_norm_l2_keys and not args.rerank_mult and args.workload == "c2" and not args.n and not args.nq and not args.visited_slots and not args.visited_kind
-                      and not args.pivots and auto_layout and not args.expansions and args.coverage == 1.0
+                      and not args.pivots and auto_layout and args.expansions == 4 and args.coverage == 1.0
                       and args.schedule_pivots == 256
                       and ef == 128 and mode == 1)
     traffic = MEASURED_TRAFFIC.get(kernel_source_hash()) if default_config else None

@@ -31,7 +31,7 @@ _STATUS_NAMES = ["ANN_OK", "ANN_EINVAL", "ANN_ENOMEM", "ANN_EDEVICE", "ANN_EUNSU
 EXPORTED_SYMBOLS = ["ann_sq_train", "ann_sq_train_truncated", "ann_sq_encode", "ann_upload_index", "ann_free_index", "ann_query_prep",
                     "ann_search_batch", "ann_rescore", "ann_rerank", "ann_rerank_adaptive", "ann_bruteforce_topk", "ann_build_entry_table",
                     "ann_entry_scan", "ann_build_prs", "ann_build_prs_ratio", "ann_build_row_norms", "ann_schedule_queries", "ann_reserve_workspace",
-                    "ann_search_batch_static", "ann_last_error", "ann_version"]
+                    "ann_search_batch_static", "ann_default_expansions_per_step", "ann_last_error", "ann_version"]
 
 
 class AnnError(RuntimeError):
@@ -88,8 +88,10 @@ def _load_library() -> ctypes.CDLL:
     lib.ann_build_entry_table.argtypes = [vp, u32, vp]
     lib.ann_entry_scan.argtypes = [vp, vp, u32, u32, vp, vp]
     lib.ann_schedule_queries.argtypes = [vp, u32, u32, vp, vp]
-    for name in EXPORTED_SYMBOLS[:-2]:
+    for name in EXPORTED_SYMBOLS[:-3]:
         getattr(lib, name).restype = i32
+    lib.ann_default_expansions_per_step.argtypes = [u32, u32]
+    lib.ann_default_expansions_per_step.restype = u32
     lib.ann_last_error.restype = ctypes.c_char_p
     lib.ann_version.restype = ctypes.c_char_p
     return lib
@@ -118,6 +120,10 @@ def _check(status: int):
 
 def ann_last_error() -> str:
     return _lib.ann_last_error().decode()
+
+
+def ann_default_expansions_per_step(ef: int, degree: int) -> int:
+    return int(_lib.ann_default_expansions_per_step(ef, degree))
 
 
 def ann_version() -> str:

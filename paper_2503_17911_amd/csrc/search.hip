@@ -34,7 +34,7 @@ ann_status check_search_args(const char *fn, const ann_index *index, const float
   if (params->mode > 1) return fail(ANN_EINVAL, "%s: unknown mode %u", fn, params->mode);
   if (params->mode == 0 && params->expansions_per_step > 1) return fail(ANN_EINVAL, "%s: expansions_per_step needs mode 1", fn);
   if (params->expansions_per_step > (uint32_t)kMaxExpansionsPerStep) return fail(ANN_ECAPACITY, "%s: expansions_per_step = %u exceeds %d", fn, params->expansions_per_step, kMaxExpansionsPerStep);
-  const uint32_t p = params->mode == 0 ? 1u : (params->expansions_per_step ? params->expansions_per_step : (uint32_t)kDefaultExpansionsPerStep);
+  const uint32_t p = params->mode == 0 ? 1u : (params->expansions_per_step ? params->expansions_per_step : ann_default_expansions_per_step(params->ef, index->degree));
   if (entry_ids && n_entry == 0) return fail(ANN_EINVAL, "%s: entry_ids given with n_entry == 0", fn);
   if (entry_ids && n_entry > ANN_MAX_ENTRIES) return fail(ANN_ECAPACITY, "%s: n_entry = %u exceeds ANN_MAX_ENTRIES = %u", fn, n_entry, ANN_MAX_ENTRIES);
 
@@ -147,6 +147,12 @@ ann_status launch_search_with(const ann_index *index, uint32_t nq, const ann_sea
 }  // namespace
 
 
+
+extern "C" uint32_t ann_default_expansions_per_step(uint32_t ef, uint32_t degree) {
+  // pools of more than 256 entries take eight registers per lane: their staging area holds 8 x 64 ids
+  const bool folded_kernel_for_eight = degree <= 32 || ef > 256;
+  return ef > 128 && folded_kernel_for_eight ? (uint32_t)kMaxExpansionsPerStep : (uint32_t)kDefaultExpansionsPerStep;
+}
 
 extern "C" ann_status ann_search_batch(ann_index *index, const float *q, uint32_t nq, const ann_search_params *params,
                                        const uint32_t *entry_ids, uint32_t n_entry, uint32_t *out_ids, float *out_keys,

@@ -140,7 +140,10 @@ def test_search_bit_exact_small_cases(H, n, d, R, nq, metric, bits, efs):
         # the default configuration (visited cache: the kernels with the switches folded away)
         assert_search_equal(ix.search(Q, ef, visited_slots=0), orc, check_counts=False)
         # multi-expansion, default configuration: degrees above 32 take the folded kernels only with ef > 192
-        orc4 = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=4)
+        import paper_2503_17911_amd as ann
+        p_default = ann.ann_default_expansions_per_step(ef, adj.shape[1])
+        assert p_default == (8 if ef > 128 and (adj.shape[1] <= 32 or ef > 256) else 4)
+        orc4 = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=p_default)
         assert_search_equal(ix.search(Q, ef, mode=1, visited_slots=0), orc4, check_counts=False)
         # eight expansions per step: the kernels with the wider step (degrees above 32: folded only with ef > 448)
         orc8 = oracle.search_batch(lv, d, adj, 0, Q, ef, metric=m, expansions_per_step=8)
@@ -325,6 +328,24 @@ def test_upload_rejects_bad_graphs(H):
     with pytest.raises(ann.AnnError) as e:
         H.GpuIndex(X, bad, 0, [lv], oracle.L2)
     assert e.value.status == ann.EINVAL
+
+
+def test_search_rejects_bad_step_widths(H):
+    """More expansions per step than the kernels are built for, or any with one
+    expansion per step asked for, are errors of the call, not silent defaults."""
+    import paper_2503_17911_amd as ann
+    w, X, Q, adj = small_case(200, 16, 6, 2, seed=4)
+    lv = oracle.sq_fit(X, 8)
+    ix = H.GpuIndex(X, adj, 0, [lv], oracle.L2)
+    with pytest.raises(ann.AnnError) as e:
+        ix.search(Q, 16, mode=1, expansions_per_step=9)
+    assert e.value.status == ann.ECAPACITY
+    with pytest.raises(ann.AnnError) as e:
+        ix.search(Q, 16, mode=0, expansions_per_step=2)
+    assert e.value.status == ann.EINVAL
+    assert_search_equal(ix.search(Q, 16, mode=1, expansions_per_step=8),
+                        oracle.search_batch(lv, w.d, adj, 0, Q, 16, expansions_per_step=8))
+    ix.close()
 
 
 def test_label_filter_paper_example_on_gpu(H):
