@@ -37,7 +37,7 @@ KERNEL_SOURCES = ("paper_2503_17911_amd/csrc/search_kernel.hpp", "paper_2503_179
 MEASURED_TRAFFIC = {
     # sha256 of KERNEL_SOURCES -> bytes per launch on c2, ef=128, multi-expansion, 10,000 queries scheduled by 256 pivots
     # (medians over the 140 launches of that grid in one run of this script under rocprofv3 --pmc, profiles/)
-    "04ea0c3b16d3d3cff22f33bb8b46d36bc58b761cb0f625246f20d0d3f023d06a": 836328.7 * 1024 * 2.0 + 5000.0 * 1024 * 1.0,
+    "b598a5a99d45afe0bf1e877e0b72efeba591fa4907f40e1cceb52562de09619a": 836399.5 * 1024 * 2.0 + 5000.0 * 1024 * 1.0,
 }
 
 
