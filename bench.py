@@ -292,12 +292,13 @@ def main():
                 args.layout = lay
                 run_step(ef, mode, pool)        # first launch of this kernel variant: not timed
                 ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                reps_sw = 12 if rec >= 0.95 else 3      # the candidates for the headline are timed longer
                 ev0.record()
-                for _ in range(3):
+                for _ in range(reps_sw):
                     run_step(ef, mode, pool)
                 ev1.record()
                 torch.cuda.synchronize()
-                ms = ev0.elapsed_time(ev1) / 3
+                ms = ev0.elapsed_time(ev1) / reps_sw
                 sweep.append(dict(ef=ef, mode=mode, expansions_per_step=p_of(mode, p_), layout=lay, recall=round(rec, 4),
                                   qps=round(nq / ms * 1e3), n_exp=float(c[:, 0].mean()), n_dist=float(c[:, 1].mean()),
                                   rebuilds=int(c[:, 3].sum())))
@@ -307,7 +308,7 @@ def main():
                     meeting.append((ef, mode, rec, c, ms, lay, p_))
             args.layout = layouts[0]
     if meeting:
-        # the fastest configuration that meets the target; configurations within 2 % of it (three launches each:
+        # the fastest configuration that meets the target; configurations within 2 % of it (a dozen launches each:
         # closer than the timing resolves) are ranked by the evaluations they need, then by time
         t_best = min(m_[4] for m_ in meeting)
         chosen = min((m_ for m_ in meeting if m_[4] <= 1.02 * t_best), key=lambda m_: (float(m_[3][:, 1].mean()), m_[4]))
